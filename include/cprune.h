@@ -1,0 +1,222 @@
+/*
+ * cprune.h - C ABI of the MI355X (gfx950) hot path of compiler-informed channel
+ * pruning: L1-norm filter ranking, weight / activation channel gather with
+ * batch-norm folding, MFMA implicit-GEMM convolution with fused bias,
+ * residual and activation, the memory-bound layers around it, per-shape kernel
+ * variant selection by timing on the device, and whole-network inference.
+ *
+ * Conventions for every call
+ *   - Returns an int status: CPRUNE_OK (0) or a negative CPRUNE_ERR_* code.  On an
+ *     argument error nothing is launched and no output is touched.
+ *   - Unless marked "host", pointers are DEVICE pointers owned by the caller;
+ *     tensors are dense NCHW (activations) / OIHW (weights), row-major.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it and return; the exceptions (they
+ *     synchronise) are cprune_select_tile, cprune_net_create,
+ *     cprune_net_layer_times and cprune_net_destroy.
+ *   - The library allocates device memory only inside a cprune_net handle.
+ *     Other calls take scratch from the caller: `ws` / `ws_bytes`, sized by the
+ *     matching *_workspace_bytes query; too little -> CPRUNE_ERR_WORKSPACE.
+ *   - Index lists are int32, strictly ascending, in range.  Device-resident
+ *     lists cannot be validated by the host; kernels clamp an index into range
+ *     instead of faulting, so a bad list gives wrong values, not a fault.
+ *   - Tensors must hold fewer than 2^31 elements.
+ */
+#ifndef CPRUNE_H
+#define CPRUNE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CPRUNE_OK 0
+#define CPRUNE_ERR_INVALID_ARG (-1) /* NULL / out-of-range argument */
+#define CPRUNE_ERR_UNSUPPORTED (-2) /* valid but not implemented (dtype, groups, variant) */
+#define CPRUNE_ERR_WORKSPACE (-3)   /* ws_bytes below the *_workspace_bytes query */
+#define CPRUNE_ERR_DEVICE (-4)      /* a HIP call failed; see cprune_last_hip_error */
+#define CPRUNE_ERR_NOT_TUNED (-5)   /* reserved */
+
+typedef enum { CPRUNE_F32 = 0, CPRUNE_F16 = 1, CPRUNE_BF16 = 2 } cprune_dtype;
+typedef enum { CPRUNE_ACT_NONE = 0, CPRUNE_ACT_RELU = 1, CPRUNE_ACT_RELU6 = 2 } cprune_act;
+
+const char* cprune_status_string(int status); /* host string, never NULL */
+int cprune_last_hip_error(void);              /* hipError_t of the last CPRUNE_ERR_DEVICE */
+
+/* ------------------------------------------------------------------------
+ * Filter ranking (paper Section 3.5, last paragraph: each filter is scored by
+ * the sum of its absolute weights and filters are pruned starting from the
+ * smallest sum).
+ *
+ * w            [c_out][c_in_per_group][kh][kw] fp32, the raw (unfolded) weights
+ * keep         number of filters that survive, 1..c_out
+ * scores_out   [c_out] double, the L1 sums (fp64 accumulation); may be NULL
+ * order_out    [c_out] int32, filter indices by (score descending, index
+ *              ascending): equal scores rank the lower index first; may be NULL
+ * kept_out     [keep] int32, the surviving filters in ascending index order
+ * ws           cprune_rank_filters_workspace_bytes(c_out) bytes of scratch
+ * The kept list is a pure function of the scores; the scores are summed in a
+ * fixed order, so repeated calls give identical bits.
+ */
+size_t cprune_rank_filters_workspace_bytes(int c_out);
+int cprune_rank_filters(const float* w, int c_out, int c_in_per_group, int kh, int kw, int keep,
+                        double* scores_out, int32_t* order_out, int32_t* kept_out,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Weight gather with batch-norm folding (paper Section 2.1 / Fig. 2: removing a
+ * filter removes an output channel, removing an input channel shrinks every
+ * filter; Section 3.5: the next layer's input channels are pruned to match).
+ *
+ *   w_out[i][c][u][v] = s_i * w[keep_out[i]][keep_in[c]][u][v]
+ *   bias_out[i]       = beta + (conv_bias - mean) * s_i,  s_i = gamma / sqrt(var + eps)
+ * with gamma, beta, mean, var, conv_bias taken at keep_out[i]; computed in fp64
+ * and rounded once.  gamma..var all NULL = no BN (s = 1, bias = conv_bias or 0).
+ *
+ * w            [c_out][c_in][kh][kw] fp32 source (c_in = channels per filter)
+ * keep_out     [n_keep_out] or NULL (= all c_out filters, n_keep_out ignored)
+ * keep_in      [n_keep_in]  or NULL (= all c_in channels, n_keep_in ignored)
+ * out_dtype    element type of w_out (fp32, fp16 or bf16, round-to-nearest-even)
+ * w_out        [n_keep_out][n_keep_in][kh][kw]; bias_out [n_keep_out] fp32, may be
+ *              NULL when there is neither BN nor conv_bias
+ */
+int cprune_gather_pruned_weights(const float* w, int c_out, int c_in, int kh, int kw,
+                                 const int32_t* keep_out, int n_keep_out,
+                                 const int32_t* keep_in, int n_keep_in,
+                                 const float* gamma, const float* beta, const float* mean,
+                                 const float* var, float eps, const float* conv_bias,
+                                 cprune_dtype out_dtype, void* w_out, float* bias_out,
+                                 void* stream);
+
+/* Activation channel gather (Section 2.1: removing input channels c_i):
+ * y[n][i][h][w] = x[n][idx[i]][h][w]; x [n][c][h][w], y [n][n_idx][h][w], same dtype. */
+int cprune_gather_channels(const void* x, int n, int c, int h, int w, cprune_dtype dtype,
+                           const int32_t* idx, int n_idx, void* y, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Convolution subgraph (paper Section 3.4: a subgraph is Conv2d (+BN) (+ReLU);
+ * this is the device program whose latency the method measures).
+ *
+ *   y[n][o][p][q] = act( bias[o] + sum_{c,u,v} x[n][c][p*stride+u-pad][q*stride+v-pad]
+ *                                              * w[o][c][u][v]  (+ residual[n][o][p][q]) )
+ * cross-correlation, zero padding, h_out = (h + 2 pad - kh) / stride + 1 (floor).
+ * groups = 1: dense, runs as an implicit GEMM on MFMA (fp32 accumulate).
+ * groups = c_in = c_out: depthwise, a bandwidth-bound stencil kernel.
+ */
+typedef struct {
+  int32_t n, c_in, h, w;   /* input  [n][c_in][h][w] */
+  int32_t c_out, kh, kw;   /* weight [c_out][c_in/groups][kh][kw] */
+  int32_t stride, pad;
+  int32_t groups;          /* 1, or c_in (with c_out == c_in) */
+  int32_t dtype;           /* cprune_dtype of x, w, residual, y; bias is always fp32 */
+  int32_t act;             /* cprune_act */
+  int32_t has_residual;    /* 0 / 1 */
+} cprune_conv_desc;
+
+/* Kernel variants of the dense path: a work-group tile (output channels x
+ * output pixels) and a split of the reduction.  Ids are 0..n-1 and the same for
+ * every shape; a variant that cannot run a given shape is CPRUNE_ERR_UNSUPPORTED. */
+int cprune_num_tile_variants(void);
+int cprune_tile_variant_info(int variant, int* tile_m, int* tile_p, int* split_k); /* host out */
+
+/* Scratch needed by `variant` (-1 = the largest any variant needs for desc). */
+size_t cprune_conv_workspace_bytes(const cprune_conv_desc* desc, int variant);
+
+/* bias may be NULL (= 0); residual must be non-NULL iff desc->has_residual.
+ * tile_variant -1 = the variant remembered for this shape by cprune_select_tile,
+ * or a built-in heuristic when the shape has not been timed. */
+int cprune_conv2d_bn_relu(const cprune_conv_desc* desc, const void* x, const void* w_folded,
+                          const float* bias, const void* residual, void* y, int tile_variant,
+                          void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Variant selection by timing on the device (paper Section 3.2, step 2: for each
+ * task the compiler generates candidate programs and keeps the one that runs
+ * fastest on the target; layers of equal shape share a task).  Times every
+ * variant that supports desc with `warmup` untimed and `iters` timed launches on
+ * the caller's buffers (y and ws are overwritten), remembers the fastest for
+ * this shape (process-wide, keyed by every field of desc) and returns it.
+ * all_ms_out: host [cprune_num_tile_variants()] per-launch ms, < 0 where
+ * unsupported; may be NULL.  variant_out / best_ms_out: host.  Synchronises.
+ */
+int cprune_select_tile(const cprune_conv_desc* desc, const void* x, const void* w_folded,
+                       const float* bias, const void* residual, void* y, void* ws,
+                       size_t ws_bytes, int warmup, int iters, int* variant_out,
+                       float* best_ms_out, float* all_ms_out, void* stream);
+/* Forget every remembered choice. */
+void cprune_clear_tile_cache(void);
+/* The remembered (or heuristic) variant for desc; host out. */
+int cprune_cached_tile(const cprune_conv_desc* desc, int* variant_out, int* was_timed_out);
+
+/* ------------------------------------------------------------------------
+ * Memory-bound layers of the evaluated networks (paper Section 4: VGG-16,
+ * ResNet-18, MobileNetV2).
+ */
+/* max over the in-bounds elements of each k x k window; y [n][c][ho][wo] */
+int cprune_maxpool2d(const void* x, int n, int c, int h, int w, int k, int stride, int pad,
+                     cprune_dtype dtype, void* y, void* stream);
+/* spatial mean; y [n][c] */
+int cprune_global_avgpool(const void* x, int n, int c, int h, int w, cprune_dtype dtype,
+                          void* y, void* stream);
+/* y[n][o] = act(bias[o] + sum_f x[n][f] w[o][f]); runs on the dense conv path. */
+size_t cprune_fc_workspace_bytes(int n, int f, int c_out, cprune_dtype dtype);
+int cprune_fc(const void* x, const void* w, const float* bias, int n, int f, int c_out,
+              cprune_act act, cprune_dtype dtype, void* y, void* ws, size_t ws_bytes,
+              void* stream);
+
+/* ------------------------------------------------------------------------
+ * Whole-network inference (paper Algorithm 1, step 9: run the aggregate of the
+ * tuned tasks on the device and measure its latency).
+ */
+typedef enum {
+  CPRUNE_LAYER_CONV = 0,     /* dense or depthwise conv + bias (+residual) + act */
+  CPRUNE_LAYER_MAXPOOL = 1,
+  CPRUNE_LAYER_GAVGPOOL = 2,
+  CPRUNE_LAYER_FC = 3
+} cprune_layer_kind;
+
+typedef struct {
+  int32_t kind;        /* cprune_layer_kind */
+  int32_t input;       /* index of the producing layer, -1 = the network input */
+  int32_t residual;    /* index of the layer added before act, -1 = none */
+  int32_t c_in, c_out; /* channels after pruning (pools: c_out = c_in) */
+  int32_t k, stride, pad;
+  int32_t groups;      /* 1 or c_in */
+  int32_t act;         /* cprune_act */
+  const void* weight;  /* device, folded, in the net's dtype; NULL for pools */
+  const float* bias;   /* device fp32 [c_out] or NULL */
+} cprune_layer_desc;
+
+typedef struct cprune_net cprune_net;
+
+/* Builds a handle: copies every layer's weights and bias into memory the handle
+ * owns, allocates one activation buffer per layer for `max_batch` images and the
+ * conv scratch, and picks a tile variant per conv shape (timing it on the device
+ * when tune != 0, as cprune_select_tile does, for batch `max_batch`).  `layers` is
+ * a host array.  in_c/in_h/in_w: the network input [n][in_c][in_h][in_w]. */
+int cprune_net_create(const cprune_layer_desc* layers, int n_layers, int in_c, int in_h,
+                      int in_w, int max_batch, cprune_dtype dtype, int tune, void* stream,
+                      cprune_net** out);
+/* logits: [n][c_out of the last layer] in the net's dtype.  1 <= n <= max_batch.
+ * use_graph != 0 replays a HIP graph of the layer sequence, captured on first use
+ * for this n (the capture call itself synchronises nothing but must not overlap
+ * other work on `stream`). */
+int cprune_net_forward(cprune_net* net, const void* x, int n, void* logits, int use_graph,
+                       void* stream);
+/* Per-layer device time of one forward, averaged over `iters` runs, bracketing
+ * every layer with events on `stream`; ms_out: host [n_layers].  Synchronises. */
+int cprune_net_layer_times(cprune_net* net, const void* x, int n, int iters, float* ms_out,
+                           void* stream);
+/* Copies layer `layer`'s activation of the last forward (batch n) to dst (device). */
+int cprune_net_copy_activation(cprune_net* net, int layer, int n, void* dst, size_t dst_bytes,
+                               void* stream);
+/* The tile variant in use for layer `layer` (-1 for layers without one); host out. */
+int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out);
+int cprune_net_destroy(cprune_net* net);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CPRUNE_H */

@@ -230,7 +230,7 @@ def fc(x, w, bias=None, act=0) -> np.ndarray:
 
 # ---- network level -------------------------------------------------------
 
-BN_EPS = 1e-5
+BN_EPS = float(np.float32(1e-5))  # the value as it crosses a float-typed boundary
 
 
 def prune_net(net, params: List[dict], keep_override: Optional[Dict[int, int]] = None,

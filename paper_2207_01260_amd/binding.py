@@ -1,0 +1,321 @@
+"""ctypes binding of libcprune_hip.so: same names as the C ABI, argument
+marshalling only.  Tensors are torch CUDA tensors (device memory and streams are
+PyTorch's); every step of the path runs in the library's kernels.  There is no
+fallback: a missing library raises.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+from . import build as _build
+
+F32, F16, BF16 = 0, 1, 2
+ACT_NONE, ACT_RELU, ACT_RELU6 = 0, 1, 2
+LAYER_CONV, LAYER_MAXPOOL, LAYER_GAVGPOOL, LAYER_FC = 0, 1, 2, 3
+
+OK = 0
+ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_NOT_TUNED = -1, -2, -3, -4, -5
+
+TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
+DTYPE_OF_TORCH = {v: k for k, v in TORCH_DTYPE.items()}
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("n", "c_in", "h", "w", "c_out", "kh", "kw", "stride", "pad", "groups", "dtype",
+                 "act", "has_residual")]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("kind", "input", "residual", "c_in", "c_out", "k", "stride", "pad", "groups",
+                 "act")] + [("weight", C.c_void_p), ("bias", C.c_void_p)]
+
+
+EXPORTS = [
+    "cprune_status_string", "cprune_last_hip_error",
+    "cprune_rank_filters_workspace_bytes", "cprune_rank_filters",
+    "cprune_gather_pruned_weights", "cprune_gather_channels",
+    "cprune_num_tile_variants", "cprune_tile_variant_info", "cprune_conv_workspace_bytes",
+    "cprune_conv2d_bn_relu", "cprune_select_tile", "cprune_clear_tile_cache",
+    "cprune_cached_tile", "cprune_maxpool2d", "cprune_global_avgpool",
+    "cprune_fc_workspace_bytes", "cprune_fc",
+    "cprune_net_create", "cprune_net_forward", "cprune_net_layer_times",
+    "cprune_net_copy_activation", "cprune_net_layer_variant", "cprune_net_destroy",
+]
+
+_lib = None
+
+
+class CPruneError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().cprune_status_string(status).decode()
+        if status == ERR_DEVICE:
+            msg += f" (hipError {lib().cprune_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{status}]")
+
+
+def lib():
+    """The loaded shared library; built on first use if it is not there yet."""
+    global _lib
+    if _lib is None:
+        path = _build.library_path()
+        if not os.path.exists(path):
+            _build.build()
+        L = C.CDLL(path)
+        L.cprune_status_string.restype = C.c_char_p
+        L.cprune_status_string.argtypes = [C.c_int]
+        for name in ("cprune_rank_filters_workspace_bytes", "cprune_conv_workspace_bytes",
+                     "cprune_fc_workspace_bytes"):
+            getattr(L, name).restype = C.c_size_t
+        L.cprune_clear_tile_cache.restype = None
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise CPruneError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return C.c_void_p(None)
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _ws(nbytes: int, device) -> Optional[torch.Tensor]:
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+# ---- ranking / gather ------------------------------------------------------
+
+def cprune_rank_filters(w: torch.Tensor, keep: int, want_scores=True, want_order=True,
+                        stream=None):
+    """-> (scores fp64 or None, order int32 or None, kept int32 ascending)."""
+    assert w.dtype == torch.float32 and w.dim() == 4
+    c_out, cpg, kh, kw = w.shape
+    dev = w.device
+    scores = torch.empty(c_out, dtype=torch.float64, device=dev) if want_scores else None
+    order = torch.empty(c_out, dtype=torch.int32, device=dev) if want_order else None
+    kept = torch.empty(max(keep, 1), dtype=torch.int32, device=dev)
+    nws = lib().cprune_rank_filters_workspace_bytes(C.c_int(c_out))
+    ws = _ws(nws, dev)
+    st = lib().cprune_rank_filters(_ptr(w), C.c_int(c_out), C.c_int(cpg), C.c_int(kh), C.c_int(kw),
+                                   C.c_int(keep), _ptr(scores), _ptr(order), _ptr(kept), _ptr(ws),
+                                   C.c_size_t(ws.numel()), _stream(stream))
+    _check(st, "cprune_rank_filters")
+    return scores, order, kept
+
+
+def cprune_gather_pruned_weights(w: torch.Tensor, keep_out=None, keep_in=None, bn=None,
+                                 eps: float = 1e-5, conv_bias=None, out_dtype: int = F32,
+                                 stream=None) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """bn = (gamma, beta, mean, var) device fp32 vectors over the unpruned filters, or None.
+    -> (w_out [n_out][n_in][kh][kw] in out_dtype, bias_out fp32 [n_out] or None)."""
+    assert w.dtype == torch.float32 and w.dim() == 4
+    c_out, c_in, kh, kw = w.shape
+    n_out = c_out if keep_out is None else keep_out.numel()
+    n_in = c_in if keep_in is None else keep_in.numel()
+    w_out = torch.empty((n_out, n_in, kh, kw), dtype=TORCH_DTYPE[out_dtype], device=w.device)
+    need_bias = bn is not None or conv_bias is not None
+    bias_out = torch.empty(n_out, dtype=torch.float32, device=w.device) if need_bias else None
+    g, b, m, v = bn if bn is not None else (None, None, None, None)
+    st = lib().cprune_gather_pruned_weights(
+        _ptr(w), C.c_int(c_out), C.c_int(c_in), C.c_int(kh), C.c_int(kw),
+        _ptr(keep_out), C.c_int(n_out), _ptr(keep_in), C.c_int(n_in),
+        _ptr(g), _ptr(b), _ptr(m), _ptr(v), C.c_float(eps), _ptr(conv_bias),
+        C.c_int(out_dtype), _ptr(w_out), _ptr(bias_out), _stream(stream))
+    _check(st, "cprune_gather_pruned_weights")
+    return w_out, bias_out
+
+
+def cprune_gather_channels(x: torch.Tensor, idx: torch.Tensor, stream=None) -> torch.Tensor:
+    n, c, h, w = x.shape
+    y = torch.empty((n, idx.numel(), h, w), dtype=x.dtype, device=x.device)
+    st = lib().cprune_gather_channels(_ptr(x), C.c_int(n), C.c_int(c), C.c_int(h), C.c_int(w),
+                                      C.c_int(DTYPE_OF_TORCH[x.dtype]), _ptr(idx),
+                                      C.c_int(idx.numel()), _ptr(y), _stream(stream))
+    _check(st, "cprune_gather_channels")
+    return y
+
+
+# ---- convolution -------------------------------------------------------------
+
+def conv_desc(x_shape, w_shape, stride=1, pad=0, groups=1, dtype=F32, act=ACT_RELU,
+              has_residual=False) -> ConvDesc:
+    n, c_in, h, w = x_shape
+    c_out, _, kh, kw = w_shape
+    return ConvDesc(n, c_in, h, w, c_out, kh, kw, stride, pad, groups, dtype, act,
+                    1 if has_residual else 0)
+
+
+def out_shape(d: ConvDesc):
+    ho = (d.h + 2 * d.pad - d.kh) // d.stride + 1
+    wo = (d.w + 2 * d.pad - d.kw) // d.stride + 1
+    return (d.n, d.c_out, ho, wo)
+
+
+def cprune_num_tile_variants() -> int:
+    return int(lib().cprune_num_tile_variants())
+
+
+def cprune_tile_variant_info(v: int) -> Tuple[int, int, int]:
+    tm, tp, sk = C.c_int(), C.c_int(), C.c_int()
+    _check(lib().cprune_tile_variant_info(C.c_int(v), C.byref(tm), C.byref(tp), C.byref(sk)),
+           "cprune_tile_variant_info")
+    return tm.value, tp.value, sk.value
+
+
+def cprune_conv_workspace_bytes(d: ConvDesc, variant: int = -1) -> int:
+    return int(lib().cprune_conv_workspace_bytes(C.byref(d), C.c_int(variant)))
+
+
+def cprune_conv2d_bn_relu(d: ConvDesc, x, w, bias=None, residual=None, tile_variant: int = -1,
+                          ws: Optional[torch.Tensor] = None, y: Optional[torch.Tensor] = None,
+                          stream=None) -> torch.Tensor:
+    if y is None:
+        y = torch.empty(out_shape(d), dtype=TORCH_DTYPE[d.dtype], device=x.device)
+    if ws is None:
+        ws = _ws(cprune_conv_workspace_bytes(d, tile_variant), x.device)
+    st = lib().cprune_conv2d_bn_relu(C.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(residual),
+                                     _ptr(y), C.c_int(tile_variant), _ptr(ws),
+                                     C.c_size_t(ws.numel()), _stream(stream))
+    _check(st, "cprune_conv2d_bn_relu")
+    return y
+
+
+def cprune_select_tile(d: ConvDesc, x, w, bias=None, residual=None, warmup: int = 2,
+                       iters: int = 8, stream=None):
+    """-> (variant, best_ms, all_ms list)."""
+    y = torch.empty(out_shape(d), dtype=TORCH_DTYPE[d.dtype], device=x.device)
+    ws = _ws(cprune_conv_workspace_bytes(d, -1), x.device)
+    nv = cprune_num_tile_variants()
+    all_ms = (C.c_float * nv)()
+    v, best = C.c_int(-1), C.c_float(0)
+    st = lib().cprune_select_tile(C.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y),
+                                  _ptr(ws), C.c_size_t(ws.numel()), C.c_int(warmup), C.c_int(iters),
+                                  C.byref(v), C.byref(best), all_ms, _stream(stream))
+    _check(st, "cprune_select_tile")
+    return v.value, best.value, list(all_ms)
+
+
+def cprune_clear_tile_cache() -> None:
+    lib().cprune_clear_tile_cache()
+
+
+def cprune_cached_tile(d: ConvDesc) -> Tuple[int, bool]:
+    v, timed = C.c_int(), C.c_int()
+    _check(lib().cprune_cached_tile(C.byref(d), C.byref(v), C.byref(timed)), "cprune_cached_tile")
+    return v.value, bool(timed.value)
+
+
+# ---- other layers --------------------------------------------------------------
+
+def cprune_maxpool2d(x, k, stride, pad=0, stream=None):
+    n, c, h, w = x.shape
+    ho, wo = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
+    y = torch.empty((n, c, ho, wo), dtype=x.dtype, device=x.device)
+    st = lib().cprune_maxpool2d(_ptr(x), C.c_int(n), C.c_int(c), C.c_int(h), C.c_int(w), C.c_int(k),
+                                C.c_int(stride), C.c_int(pad), C.c_int(DTYPE_OF_TORCH[x.dtype]),
+                                _ptr(y), _stream(stream))
+    _check(st, "cprune_maxpool2d")
+    return y
+
+
+def cprune_global_avgpool(x, stream=None):
+    n, c, h, w = x.shape
+    y = torch.empty((n, c), dtype=x.dtype, device=x.device)
+    st = lib().cprune_global_avgpool(_ptr(x), C.c_int(n), C.c_int(c), C.c_int(h), C.c_int(w),
+                                     C.c_int(DTYPE_OF_TORCH[x.dtype]), _ptr(y), _stream(stream))
+    _check(st, "cprune_global_avgpool")
+    return y
+
+
+def cprune_fc(x, w, bias=None, act=ACT_NONE, stream=None):
+    n = x.shape[0]
+    f = x.numel() // n
+    c_out = w.shape[0]
+    dt = DTYPE_OF_TORCH[x.dtype]
+    y = torch.empty((n, c_out), dtype=x.dtype, device=x.device)
+    ws = _ws(lib().cprune_fc_workspace_bytes(C.c_int(n), C.c_int(f), C.c_int(c_out), C.c_int(dt)),
+             x.device)
+    st = lib().cprune_fc(_ptr(x), _ptr(w), _ptr(bias), C.c_int(n), C.c_int(f), C.c_int(c_out),
+                         C.c_int(act), C.c_int(dt), _ptr(y), _ptr(ws), C.c_size_t(ws.numel()),
+                         _stream(stream))
+    _check(st, "cprune_fc")
+    return y
+
+
+# ---- network handle ------------------------------------------------------------
+
+class Net:
+    """Owner of a cprune_net handle."""
+
+    def __init__(self, layer_descs, in_chw, max_batch: int, dtype: int = F32, tune: bool = True,
+                 stream=None):
+        arr = (LayerDesc * len(layer_descs))(*layer_descs)
+        self._h = C.c_void_p(None)
+        self.n_layers = len(layer_descs)
+        self.out_features = layer_descs[-1].c_out
+        self.dtype = dtype
+        self.max_batch = max_batch
+        st = lib().cprune_net_create(arr, C.c_int(len(layer_descs)), C.c_int(in_chw[0]),
+                                     C.c_int(in_chw[1]), C.c_int(in_chw[2]), C.c_int(max_batch),
+                                     C.c_int(dtype), C.c_int(1 if tune else 0), _stream(stream),
+                                     C.byref(self._h))
+        _check(st, "cprune_net_create")
+
+    def forward(self, x, logits=None, use_graph=False, stream=None):
+        n = x.shape[0]
+        if logits is None:
+            logits = torch.empty((n, self.out_features), dtype=TORCH_DTYPE[self.dtype],
+                                 device=x.device)
+        st = lib().cprune_net_forward(self._h, _ptr(x), C.c_int(n), _ptr(logits),
+                                      C.c_int(1 if use_graph else 0), _stream(stream))
+        _check(st, "cprune_net_forward")
+        return logits
+
+    def layer_times(self, x, iters=10, stream=None):
+        ms = (C.c_float * self.n_layers)()
+        st = lib().cprune_net_layer_times(self._h, _ptr(x), C.c_int(x.shape[0]), C.c_int(iters), ms,
+                                          _stream(stream))
+        _check(st, "cprune_net_layer_times")
+        return list(ms)
+
+    def activation(self, layer: int, n: int, shape, stream=None):
+        out = torch.empty((n,) + tuple(shape), dtype=TORCH_DTYPE[self.dtype], device="cuda")
+        st = lib().cprune_net_copy_activation(self._h, C.c_int(layer), C.c_int(n), _ptr(out),
+                                              C.c_size_t(out.numel() * out.element_size()),
+                                              _stream(stream))
+        _check(st, "cprune_net_copy_activation")
+        return out
+
+    def layer_variant(self, layer: int) -> int:
+        v = C.c_int()
+        _check(lib().cprune_net_layer_variant(self._h, C.c_int(layer), C.byref(v)),
+               "cprune_net_layer_variant")
+        return v.value
+
+    def close(self):
+        if self._h:
+            lib().cprune_net_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,552 @@
+// C-ABI entry points: argument validation, the per-shape variant cache and
+// on-device selection, the single-layer calls and the network handle.
+#include "common.hpp"
+
+#include <map>
+#include <mutex>
+#include <vector>
+#include <array>
+#include <cmath>
+#include <cstring>
+
+namespace cprune {
+
+static thread_local hipError_t g_last_hip_error = hipSuccess;
+void set_last_hip_error(hipError_t e) { g_last_hip_error = e; }
+
+// ---- descriptor validation ---------------------------------------------------
+int validate_conv_desc(const cprune_conv_desc* d) {
+  if (!d) return CPRUNE_ERR_INVALID_ARG;
+  if (d->n < 1 || d->c_in < 1 || d->h < 1 || d->w < 1 || d->c_out < 1) return CPRUNE_ERR_INVALID_ARG;
+  if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0) return CPRUNE_ERR_INVALID_ARG;
+  if (!dtype_ok(d->dtype) || !act_ok(d->act)) return CPRUNE_ERR_INVALID_ARG;
+  if (d->has_residual != 0 && d->has_residual != 1) return CPRUNE_ERR_INVALID_ARG;
+  if (d->groups < 1) return CPRUNE_ERR_INVALID_ARG;
+  if (d->h + 2 * d->pad < d->kh || d->w + 2 * d->pad < d->kw) return CPRUNE_ERR_INVALID_ARG;
+  if (d->groups != 1 && !(d->groups == d->c_in && d->c_out == d->c_in)) return CPRUNE_ERR_UNSUPPORTED;
+  if (d->kh > 7 || d->kw > 7) return CPRUNE_ERR_UNSUPPORTED;
+  if (d->pad >= d->kh || d->pad >= d->kw) return CPRUNE_ERR_UNSUPPORTED;  // every window holds a real element
+  const long ho = conv_out_dim(d->h, d->kh, d->stride, d->pad), wo = conv_out_dim(d->w, d->kw, d->stride, d->pad);
+  const long lim = 1L << 31;
+  if ((long)d->n * d->c_in * d->h * d->w >= lim || (long)d->n * d->c_out * ho * wo >= lim) return CPRUNE_ERR_UNSUPPORTED;
+  if ((long)d->c_out * (d->c_in / d->groups) * d->kh * d->kw >= lim) return CPRUNE_ERR_UNSUPPORTED;
+  if ((long)d->c_in * d->kh * d->kw * d->kh * d->kw >= lim) return CPRUNE_ERR_UNSUPPORTED;  // exact magic division
+  return CPRUNE_OK;
+}
+
+// ---- variant cache -------------------------------------------------------------
+typedef std::array<int, 13> DescKey;
+static DescKey key_of(const cprune_conv_desc& d) {
+  return DescKey{d.n, d.c_in, d.h, d.w, d.c_out, d.kh, d.kw, d.stride, d.pad, d.groups, d.dtype, d.act,
+                 d.has_residual};
+}
+static std::mutex g_cache_mutex;
+static std::map<DescKey, int> g_cache;
+
+void remember_variant(const cprune_conv_desc& d, int v) {
+  std::lock_guard<std::mutex> lock(g_cache_mutex);
+  g_cache[key_of(d)] = v;
+}
+
+// Untimed fallback: a coarse cost model (rounds of work-groups over the chip
+// times the MFMA blocks one work-group issues, plus fixed per-group and
+// per-slice overheads), used only for shapes that were never timed.
+int heuristic_variant(const cprune_conv_desc& d) {
+  const long ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
+  const long P = (long)d.n * ho * wo, O = d.c_out;
+  const long K = (long)d.c_in * d.kh * d.kw;
+  const long kt = d.dtype == CPRUNE_F32 ? 16 : 32;
+  const long slabs = (K + kt - 1) / kt;
+  double best = 1e300;
+  int best_v = 0;
+  for (int v = 0; v < num_variants(); ++v) {
+    if (!variant_supports(d, v)) continue;
+    const TileVariant& tv = variant(v);
+    const long mt = tv.tile_m(), pt = tv.tile_p();
+    const long tm = (O + mt - 1) / mt, tp = (P + pt - 1) / pt;
+    const long groups = tm * tp * tv.split_k;
+    const double rows16 = std::ceil((double)O / tm / 16.0);
+    const double per_wave_rows = tv.wm > 1 ? std::ceil(rows16 / tv.wm) : rows16;
+    const double blocks = per_wave_rows * tv.nb;           // MFMA blocks per wave per slab
+    const double stage = (double)(mt + pt) / 64.0;          // staging cost per slab
+    const double per_group = (double)((slabs + tv.split_k - 1) / tv.split_k) * (blocks + 0.5 * stage) + 60.0;
+    const double rounds = std::ceil((double)groups / 512.0);
+    double cost = rounds * per_group;
+    if (tv.split_k > 1) cost += 80.0 + (double)O * P * tv.split_k / 4096.0;
+    if (cost < best) { best = cost; best_v = v; }
+  }
+  return best_v;
+}
+
+int cached_or_heuristic_variant(const cprune_conv_desc& d, bool* timed) {
+  {
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    auto it = g_cache.find(key_of(d));
+    if (it != g_cache.end()) {
+      if (timed) *timed = true;
+      return it->second;
+    }
+  }
+  if (timed) *timed = false;
+  return heuristic_variant(d);
+}
+
+static int conv_dispatch(const cprune_conv_desc& d, const void* x, const void* w, const float* bias,
+                         const void* residual, void* y, int v, void* ws, size_t ws_bytes, hipStream_t s) {
+  if (d.groups != 1) return launch_conv_depthwise(d, x, w, bias, residual, y, s);
+  if (v < 0) v = cached_or_heuristic_variant(d, nullptr);
+  if (!variant_supports(d, v)) return CPRUNE_ERR_UNSUPPORTED;
+  const size_t need = conv_ws_bytes(d, v);
+  if (need > 0 && (!ws || ws_bytes < need)) return CPRUNE_ERR_WORKSPACE;
+  return launch_conv_dense(d, x, w, bias, residual, y, v, ws, s);
+}
+
+// Times every supported variant on the given buffers; returns the fastest.
+static int select_tile_impl(const cprune_conv_desc& d, const void* x, const void* w, const float* bias,
+                            const void* residual, void* y, void* ws, size_t ws_bytes, int warmup,
+                            int iters, int* variant_out, float* best_ms_out, float* all_ms_out,
+                            hipStream_t s) {
+  hipEvent_t e0, e1;
+  CPRUNE_HIP_TRY(hipEventCreate(&e0));
+  hipError_t ee = hipEventCreate(&e1);
+  if (ee != hipSuccess) { hipEventDestroy(e0); set_last_hip_error(ee); return CPRUNE_ERR_DEVICE; }
+  int best_v = -1;
+  float best_ms = 0.0f;
+  int rc = CPRUNE_OK;
+  const int nv = d.groups == 1 ? num_variants() : 1;
+  for (int v = 0; v < nv && rc == CPRUNE_OK; ++v) {
+    if (all_ms_out) all_ms_out[v] = -1.0f;
+    if (d.groups == 1) {
+      if (!variant_supports(d, v)) continue;
+      if (conv_ws_bytes(d, v) > ws_bytes) continue;  // not timed: the caller's scratch cannot run it
+    }
+    for (int i = 0; i < warmup && rc == CPRUNE_OK; ++i) rc = conv_dispatch(d, x, w, bias, residual, y, v, ws, ws_bytes, s);
+    if (rc != CPRUNE_OK) break;
+    hipError_t e = hipEventRecord(e0, s);
+    for (int i = 0; i < iters && rc == CPRUNE_OK; ++i) rc = conv_dispatch(d, x, w, bias, residual, y, v, ws, ws_bytes, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
+    ms /= (float)iters;
+    if (all_ms_out) all_ms_out[v] = ms;
+    if (best_v < 0 || ms < best_ms) { best_v = v; best_ms = ms; }
+  }
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  if (rc != CPRUNE_OK) return rc;
+  if (best_v < 0) return CPRUNE_ERR_WORKSPACE;
+  if (d.groups == 1) remember_variant(d, best_v);
+  if (variant_out) *variant_out = best_v;
+  if (best_ms_out) *best_ms_out = best_ms;
+  return CPRUNE_OK;
+}
+
+}  // namespace cprune
+
+using namespace cprune;
+
+extern "C" const char* cprune_status_string(int status) {
+  switch (status) {
+    case CPRUNE_OK: return "ok";
+    case CPRUNE_ERR_INVALID_ARG: return "invalid argument";
+    case CPRUNE_ERR_UNSUPPORTED: return "unsupported configuration";
+    case CPRUNE_ERR_WORKSPACE: return "workspace too small";
+    case CPRUNE_ERR_DEVICE: return "HIP call failed";
+    case CPRUNE_ERR_NOT_TUNED: return "shape not tuned";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int cprune_last_hip_error(void) { return (int)g_last_hip_error; }
+
+extern "C" int cprune_num_tile_variants(void) { return num_variants(); }
+
+extern "C" int cprune_tile_variant_info(int v, int* tile_m, int* tile_p, int* split_k) {
+  if (v < 0 || v >= num_variants()) return CPRUNE_ERR_INVALID_ARG;
+  const TileVariant& tv = variant(v);
+  if (tile_m) *tile_m = tv.tile_m();
+  if (tile_p) *tile_p = tv.tile_p();
+  if (split_k) *split_k = tv.split_k;
+  return CPRUNE_OK;
+}
+
+extern "C" size_t cprune_conv_workspace_bytes(const cprune_conv_desc* desc, int v) {
+  if (validate_conv_desc(desc) != CPRUNE_OK) return 0;
+  if (v >= num_variants()) return 0;
+  return conv_ws_bytes(*desc, v);
+}
+
+extern "C" int cprune_conv2d_bn_relu(const cprune_conv_desc* desc, const void* x, const void* w,
+                                     const float* bias, const void* residual, void* y, int tile_variant,
+                                     void* ws, size_t ws_bytes, void* stream) {
+  int rc = validate_conv_desc(desc);
+  if (rc != CPRUNE_OK) return rc;
+  if (!x || !w || !y) return CPRUNE_ERR_INVALID_ARG;
+  if ((desc->has_residual != 0) != (residual != nullptr)) return CPRUNE_ERR_INVALID_ARG;
+  if (tile_variant < -1 || tile_variant >= num_variants()) return CPRUNE_ERR_INVALID_ARG;
+  return conv_dispatch(*desc, x, w, bias, residual, y, tile_variant, ws, ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" int cprune_select_tile(const cprune_conv_desc* desc, const void* x, const void* w,
+                                  const float* bias, const void* residual, void* y, void* ws,
+                                  size_t ws_bytes, int warmup, int iters, int* variant_out,
+                                  float* best_ms_out, float* all_ms_out, void* stream) {
+  int rc = validate_conv_desc(desc);
+  if (rc != CPRUNE_OK) return rc;
+  if (!x || !w || !y || !variant_out) return CPRUNE_ERR_INVALID_ARG;
+  if ((desc->has_residual != 0) != (residual != nullptr)) return CPRUNE_ERR_INVALID_ARG;
+  if (warmup < 0 || iters < 1) return CPRUNE_ERR_INVALID_ARG;
+  return select_tile_impl(*desc, x, w, bias, residual, y, ws, ws ? ws_bytes : 0, warmup, iters, variant_out,
+                          best_ms_out, all_ms_out, (hipStream_t)stream);
+}
+
+extern "C" void cprune_clear_tile_cache(void) {
+  std::lock_guard<std::mutex> lock(g_cache_mutex);
+  g_cache.clear();
+}
+
+extern "C" int cprune_cached_tile(const cprune_conv_desc* desc, int* variant_out, int* was_timed_out) {
+  int rc = validate_conv_desc(desc);
+  if (rc != CPRUNE_OK) return rc;
+  if (!variant_out) return CPRUNE_ERR_INVALID_ARG;
+  if (desc->groups != 1) return CPRUNE_ERR_UNSUPPORTED;
+  bool timed = false;
+  *variant_out = cached_or_heuristic_variant(*desc, &timed);
+  if (was_timed_out) *was_timed_out = timed ? 1 : 0;
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_maxpool2d(const void* x, int n, int c, int h, int w, int k, int stride, int pad,
+                                cprune_dtype dtype, void* y, void* stream) {
+  if (!x || !y || n < 1 || c < 1 || h < 1 || w < 1 || k < 1 || stride < 1 || pad < 0) return CPRUNE_ERR_INVALID_ARG;
+  if (!dtype_ok(dtype) || h + 2 * pad < k || w + 2 * pad < k) return CPRUNE_ERR_INVALID_ARG;
+  if (pad >= k) return CPRUNE_ERR_UNSUPPORTED;
+  if ((long)n * c * h * w >= (1L << 31)) return CPRUNE_ERR_UNSUPPORTED;
+  return launch_maxpool(x, n, c, h, w, k, stride, pad, dtype, y, (hipStream_t)stream);
+}
+
+extern "C" int cprune_global_avgpool(const void* x, int n, int c, int h, int w, cprune_dtype dtype,
+                                     void* y, void* stream) {
+  if (!x || !y || n < 1 || c < 1 || h < 1 || w < 1 || !dtype_ok(dtype)) return CPRUNE_ERR_INVALID_ARG;
+  if ((long)n * c * h * w >= (1L << 31)) return CPRUNE_ERR_UNSUPPORTED;
+  return launch_gavgpool(x, n, c, h * w, dtype, y, (hipStream_t)stream);
+}
+
+static cprune_conv_desc fc_desc(int n, int f, int c_out, int act, int dtype) {
+  cprune_conv_desc d;
+  d.n = n; d.c_in = f; d.h = 1; d.w = 1; d.c_out = c_out; d.kh = 1; d.kw = 1; d.stride = 1; d.pad = 0;
+  d.groups = 1; d.dtype = dtype; d.act = act; d.has_residual = 0;
+  return d;
+}
+
+extern "C" size_t cprune_fc_workspace_bytes(int n, int f, int c_out, cprune_dtype dtype) {
+  if (n < 1 || f < 1 || c_out < 1 || !dtype_ok(dtype)) return 0;
+  cprune_conv_desc d = fc_desc(n, f, c_out, CPRUNE_ACT_NONE, dtype);
+  return conv_ws_bytes(d, -1);
+}
+
+extern "C" int cprune_fc(const void* x, const void* w, const float* bias, int n, int f, int c_out,
+                         cprune_act act, cprune_dtype dtype, void* y, void* ws, size_t ws_bytes,
+                         void* stream) {
+  if (n < 1 || f < 1 || c_out < 1 || !x || !w || !y) return CPRUNE_ERR_INVALID_ARG;
+  if (!dtype_ok(dtype) || !act_ok(act)) return CPRUNE_ERR_INVALID_ARG;
+  cprune_conv_desc d = fc_desc(n, f, c_out, act, dtype);
+  int rc = validate_conv_desc(&d);
+  if (rc != CPRUNE_OK) return rc;
+  // choose among the variants the caller's scratch can run
+  int v = cached_or_heuristic_variant(d, nullptr);
+  if (conv_ws_bytes(d, v) > (ws ? ws_bytes : 0)) {
+    cprune_conv_desc tmp = d;
+    int best = -1;
+    for (int i = 0; i < num_variants(); ++i)
+      if (variant_supports(tmp, i) && variant(i).split_k == 1 && variant(i).tile_m() == variant(v).tile_m() &&
+          variant(i).tile_p() == variant(v).tile_p()) { best = i; break; }
+    if (best < 0) return CPRUNE_ERR_WORKSPACE;
+    v = best;
+  }
+  return launch_conv_dense(d, x, w, bias, nullptr, y, v, ws, (hipStream_t)stream);
+}
+
+// ---- network handle ------------------------------------------------------------
+struct NetLayer {
+  cprune_layer_desc d;
+  int h_in, w_in, h_out, w_out;
+  void* w = nullptr;
+  float* b = nullptr;
+  void* act = nullptr;        // [max_batch][c_out][h_out][w_out]
+  size_t per_image = 0;       // elements per image of the output
+  int variant = -1;           // dense conv / fc: variant for max_batch
+};
+
+struct GraphKey {
+  int n; const void* x; void* logits; hipStream_t s;
+  bool operator<(const GraphKey& o) const {
+    if (n != o.n) return n < o.n;
+    if (x != o.x) return x < o.x;
+    if (logits != o.logits) return logits < o.logits;
+    return s < o.s;
+  }
+};
+
+struct cprune_net {
+  std::vector<NetLayer> layers;
+  int in_c, in_h, in_w, max_batch, dtype;
+  std::vector<void*> allocs;
+  void* ws = nullptr;
+  size_t ws_bytes = 0;
+  std::map<GraphKey, hipGraphExec_t> graphs;
+  int last_n = 0;
+};
+
+static cprune_conv_desc layer_conv_desc(const cprune_net& net, const NetLayer& L, int n) {
+  cprune_conv_desc d;
+  d.n = n; d.c_in = L.d.c_in; d.c_out = L.d.c_out; d.dtype = net.dtype; d.act = L.d.act;
+  d.has_residual = L.d.residual >= 0 ? 1 : 0;
+  if (L.d.kind == CPRUNE_LAYER_FC) {
+    d.c_in = L.d.c_in * L.h_in * L.w_in;
+    d.h = d.w = 1; d.kh = d.kw = 1; d.stride = 1; d.pad = 0; d.groups = 1;
+  } else {
+    d.h = L.h_in; d.w = L.w_in; d.kh = d.kw = L.d.k; d.stride = L.d.stride; d.pad = L.d.pad;
+    d.groups = L.d.groups;
+  }
+  return d;
+}
+
+static void net_free(cprune_net* net) {
+  for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
+  for (void* p : net->allocs) hipFree(p);
+  delete net;
+}
+
+static int net_run_layer(cprune_net* net, int i, const void* x, int n, void* out_override, hipStream_t s) {
+  NetLayer& L = net->layers[i];
+  const void* src = L.d.input < 0 ? x : net->layers[L.d.input].act;
+  void* dst = out_override ? out_override : L.act;
+  switch (L.d.kind) {
+    case CPRUNE_LAYER_CONV:
+    case CPRUNE_LAYER_FC: {
+      cprune_conv_desc d = layer_conv_desc(*net, L, n);
+      const void* res = L.d.residual >= 0 ? net->layers[L.d.residual].act : nullptr;
+      int v = -1;
+      if (d.groups == 1) v = (n == net->max_batch) ? L.variant : cached_or_heuristic_variant(d, nullptr);
+      return conv_dispatch(d, src, L.w, L.b, res, dst, v, net->ws, net->ws_bytes, s);
+    }
+    case CPRUNE_LAYER_MAXPOOL:
+      return launch_maxpool(src, n, L.d.c_in, L.h_in, L.w_in, L.d.k, L.d.stride, L.d.pad, net->dtype, dst, s);
+    case CPRUNE_LAYER_GAVGPOOL:
+      return launch_gavgpool(src, n, L.d.c_in, L.h_in * L.w_in, net->dtype, dst, s);
+  }
+  return CPRUNE_ERR_INVALID_ARG;
+}
+
+static int net_enqueue(cprune_net* net, const void* x, int n, void* logits, hipStream_t s) {
+  const int nl = (int)net->layers.size();
+  for (int i = 0; i < nl; ++i) {
+    int rc = net_run_layer(net, i, x, n, (i == nl - 1) ? logits : nullptr, s);
+    if (rc != CPRUNE_OK) return rc;
+  }
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, int in_c, int in_h,
+                                 int in_w, int max_batch, cprune_dtype dtype, int tune, void* stream,
+                                 cprune_net** out) {
+  if (!layers || !out || n_layers < 1 || in_c < 1 || in_h < 1 || in_w < 1 || max_batch < 1) return CPRUNE_ERR_INVALID_ARG;
+  if (!dtype_ok(dtype)) return CPRUNE_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  cprune_net* net = new cprune_net();
+  net->in_c = in_c; net->in_h = in_h; net->in_w = in_w; net->max_batch = max_batch; net->dtype = dtype;
+  net->layers.resize(n_layers);
+  const size_t es = dtype_size(dtype);
+  int rc = CPRUNE_OK;
+  // shapes and validation
+  for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
+    NetLayer& L = net->layers[i];
+    L.d = layers[i];
+    const cprune_layer_desc& d = L.d;
+    if (d.input < -1 || d.input >= i || d.residual < -1 || d.residual >= i) { rc = CPRUNE_ERR_INVALID_ARG; break; }
+    int c, h, w;
+    if (d.input < 0) { c = in_c; h = in_h; w = in_w; }
+    else { const NetLayer& S = net->layers[d.input]; c = S.d.c_out; h = S.h_out; w = S.w_out; }
+    L.h_in = h; L.w_in = w;
+    if (d.kind == CPRUNE_LAYER_FC) {
+      if (d.c_in != c || d.c_out < 1 || !d.weight || !act_ok(d.act) || d.residual >= 0) { rc = CPRUNE_ERR_INVALID_ARG; break; }
+      L.h_out = L.w_out = 1;
+    } else if (d.kind == CPRUNE_LAYER_GAVGPOOL) {
+      if (d.c_in != c || d.c_out != c) { rc = CPRUNE_ERR_INVALID_ARG; break; }
+      L.h_out = L.w_out = 1;
+    } else if (d.kind == CPRUNE_LAYER_MAXPOOL || d.kind == CPRUNE_LAYER_CONV) {
+      if (d.c_in != c || d.k < 1 || d.stride < 1 || d.pad < 0 || h + 2 * d.pad < d.k || w + 2 * d.pad < d.k) { rc = CPRUNE_ERR_INVALID_ARG; break; }
+      L.h_out = conv_out_dim(h, d.k, d.stride, d.pad);
+      L.w_out = conv_out_dim(w, d.k, d.stride, d.pad);
+      if (d.kind == CPRUNE_LAYER_MAXPOOL) {
+        if (d.c_out != c || d.pad >= d.k) { rc = CPRUNE_ERR_INVALID_ARG; break; }
+      } else {
+        if (!d.weight) { rc = CPRUNE_ERR_INVALID_ARG; break; }
+        cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
+        rc = validate_conv_desc(&cd);
+        if (rc != CPRUNE_OK) break;
+      }
+    } else { rc = CPRUNE_ERR_INVALID_ARG; break; }
+    if (d.residual >= 0) {
+      const NetLayer& R = net->layers[d.residual];
+      if (d.kind != CPRUNE_LAYER_CONV || R.d.c_out != d.c_out || R.h_out != L.h_out || R.w_out != L.w_out) { rc = CPRUNE_ERR_INVALID_ARG; break; }
+    }
+    L.per_image = (size_t)d.c_out * L.h_out * L.w_out;
+  }
+  if (rc != CPRUNE_OK) { net_free(net); return rc; }
+
+  auto dev_alloc = [&](size_t bytes, void** p) -> int {
+    hipError_t e = hipMalloc(p, bytes ? bytes : 16);
+    if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
+    net->allocs.push_back(*p);
+    return CPRUNE_OK;
+  };
+  // weights, biases, activations, scratch
+  for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
+    NetLayer& L = net->layers[i];
+    const cprune_layer_desc& d = L.d;
+    if (d.kind == CPRUNE_LAYER_CONV || d.kind == CPRUNE_LAYER_FC) {
+      size_t nw;
+      if (d.kind == CPRUNE_LAYER_FC) nw = (size_t)d.c_out * d.c_in * L.h_in * L.w_in;
+      else nw = (size_t)d.c_out * (d.c_in / d.groups) * d.k * d.k;
+      rc = dev_alloc(nw * es, &L.w);
+      if (rc != CPRUNE_OK) break;
+      hipError_t e = hipMemcpyAsync(L.w, d.weight, nw * es, hipMemcpyDeviceToDevice, s);
+      if (e == hipSuccess && d.bias) {
+        rc = dev_alloc((size_t)d.c_out * sizeof(float), (void**)&L.b);
+        if (rc != CPRUNE_OK) break;
+        e = hipMemcpyAsync(L.b, d.bias, (size_t)d.c_out * sizeof(float), hipMemcpyDeviceToDevice, s);
+      }
+      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
+      if (d.groups == 1 || d.kind == CPRUNE_LAYER_FC) {
+        cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
+        size_t need = conv_ws_bytes(cd, -1);
+        if (need > net->ws_bytes) net->ws_bytes = need;
+      }
+    }
+    const size_t abytes = L.per_image * max_batch * es;
+    rc = dev_alloc(abytes, &L.act);
+    if (rc != CPRUNE_OK) break;
+    hipError_t e = hipMemsetAsync(L.act, 0, abytes, s);
+    if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
+  }
+  void* scratch_in = nullptr;
+  if (rc == CPRUNE_OK && net->ws_bytes) rc = dev_alloc(net->ws_bytes, &net->ws);
+  if (rc == CPRUNE_OK) {
+    size_t ib = (size_t)max_batch * in_c * in_h * in_w * es;
+    rc = dev_alloc(ib, &scratch_in);
+    if (rc == CPRUNE_OK) {
+      hipError_t e = hipMemsetAsync(scratch_in, 0, ib, s);
+      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
+    }
+  }
+  // variant per dense layer
+  for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
+    NetLayer& L = net->layers[i];
+    if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) continue;
+    cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
+    bool timed = false;
+    int v = cached_or_heuristic_variant(cd, &timed);
+    if (tune && !timed) {
+      const void* src = L.d.input < 0 ? scratch_in : net->layers[L.d.input].act;
+      const void* res = L.d.residual >= 0 ? net->layers[L.d.residual].act : nullptr;
+      rc = select_tile_impl(cd, src, L.w, L.b, res, L.act, net->ws, net->ws_bytes, 2, 6, &v, nullptr, nullptr, s);
+    }
+    L.variant = v;
+  }
+  if (rc == CPRUNE_OK) {
+    hipError_t e = hipStreamSynchronize(s);
+    if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
+  }
+  if (rc != CPRUNE_OK) { net_free(net); return rc; }
+  *out = net;
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_net_forward(cprune_net* net, const void* x, int n, void* logits, int use_graph,
+                                  void* stream) {
+  if (!net || !x || !logits) return CPRUNE_ERR_INVALID_ARG;
+  if (n < 1 || n > net->max_batch) return CPRUNE_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  net->last_n = n;
+  if (!use_graph) return net_enqueue(net, x, n, logits, s);
+  GraphKey key{n, x, logits, s};
+  auto it = net->graphs.find(key);
+  if (it == net->graphs.end()) {
+    hipGraph_t graph = nullptr;
+    CPRUNE_HIP_TRY(hipStreamBeginCapture(s, hipStreamCaptureModeRelaxed));
+    int rc = net_enqueue(net, x, n, logits, s);
+    hipError_t e = hipStreamEndCapture(s, &graph);
+    if (rc != CPRUNE_OK) { if (graph) hipGraphDestroy(graph); return rc; }
+    if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    hipGraphDestroy(graph);
+    if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
+    it = net->graphs.emplace(key, exec).first;
+  }
+  CPRUNE_HIP_TRY(hipGraphLaunch(it->second, s));
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_net_layer_times(cprune_net* net, const void* x, int n, int iters, float* ms_out,
+                                      void* stream) {
+  if (!net || !x || !ms_out || iters < 1) return CPRUNE_ERR_INVALID_ARG;
+  if (n < 1 || n > net->max_batch) return CPRUNE_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  const int nl = (int)net->layers.size();
+  std::vector<hipEvent_t> ev(nl + 1, nullptr);
+  int rc = CPRUNE_OK;
+  for (int i = 0; i <= nl; ++i) {
+    hipError_t e = hipEventCreate(&ev[i]);
+    if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
+  }
+  for (int i = 0; i < nl; ++i) ms_out[i] = 0.0f;
+  net->last_n = n;
+  for (int it = 0; it < iters && rc == CPRUNE_OK; ++it) {
+    for (int i = 0; i < nl && rc == CPRUNE_OK; ++i) {
+      hipError_t e = hipEventRecord(ev[i], s);
+      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
+      rc = net_run_layer(net, i, x, n, nullptr, s);
+    }
+    if (rc != CPRUNE_OK) break;
+    hipError_t e = hipEventRecord(ev[nl], s);
+    if (e == hipSuccess) e = hipEventSynchronize(ev[nl]);
+    for (int i = 0; i < nl && e == hipSuccess; ++i) {
+      float ms = 0.0f;
+      e = hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
+      ms_out[i] += ms / (float)iters;
+    }
+    if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
+  }
+  for (int i = 0; i <= nl; ++i) if (ev[i]) hipEventDestroy(ev[i]);
+  return rc;
+}
+
+extern "C" int cprune_net_copy_activation(cprune_net* net, int layer, int n, void* dst, size_t dst_bytes,
+                                          void* stream) {
+  if (!net || !dst || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
+  if (n < 1 || n > net->max_batch) return CPRUNE_ERR_INVALID_ARG;
+  const NetLayer& L = net->layers[layer];
+  const size_t bytes = L.per_image * n * dtype_size(net->dtype);
+  if (dst_bytes < bytes) return CPRUNE_ERR_INVALID_ARG;
+  CPRUNE_HIP_TRY(hipMemcpyAsync(dst, L.act, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out) {
+  if (!net || !variant_out || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
+  *variant_out = net->layers[layer].variant;
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_net_destroy(cprune_net* net) {
+  if (!net) return CPRUNE_ERR_INVALID_ARG;
+  hipError_t e = hipDeviceSynchronize();
+  net_free(net);
+  if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
+  return CPRUNE_OK;
+}

@@ -1,0 +1,167 @@
+// Bandwidth-bound layers of the evaluated networks: depthwise convolution
+// (MobileNetV2's 3x3 stage between the pruned 1x1 expansion and projection),
+// max pooling and global average pooling.  No contraction across channels, so
+// these are plain coalesced kernels: consecutive lanes take consecutive output
+// columns of one (image, channel) plane.
+#include "common.hpp"
+
+namespace cprune {
+namespace {
+
+template <typename T> __device__ __forceinline__ float ld(const T* p) { return (float)*p; }
+template <typename T> __device__ __forceinline__ void st(T* p, float v) { *p = (T)v; }
+
+__device__ __forceinline__ float act_f(float v, int act) {
+  if (act == CPRUNE_ACT_RELU) return fmaxf(v, 0.0f);
+  if (act == CPRUNE_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
+  return v;
+}
+
+// grid.x = n*c planes, grid.y slices the output plane; weights of the plane's
+// channel are read once into registers (k <= 7).
+template <typename T, int K>
+__global__ __launch_bounds__(256) void depthwise_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                        const float* __restrict__ bias,
+                                                        const T* __restrict__ res, T* __restrict__ y,
+                                                        int c, int h, int wd, int ho, int wo, int stride,
+                                                        int pad, int act) {
+  const int plane = blockIdx.x;
+  const int ch = plane % c;
+  float wk[K * K];
+#pragma unroll
+  for (int i = 0; i < K * K; ++i) wk[i] = ld(w + (long)ch * K * K + i);
+  const float b = bias ? bias[ch] : 0.0f;
+  const T* xp = x + (long)plane * h * wd;
+  const long obase = (long)plane * ho * wo;
+  const int total = ho * wo;
+  for (int e = blockIdx.y * 256 + threadIdx.x; e < total; e += gridDim.y * 256) {
+    int oy = e / wo, ox = e - oy * wo;
+    int iy0 = oy * stride - pad, ix0 = ox * stride - pad;
+    float acc = 0.0f;
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+      int iy = iy0 + u;
+      if ((unsigned)iy >= (unsigned)h) continue;
+#pragma unroll
+      for (int v = 0; v < K; ++v) {
+        int ix = ix0 + v;
+        if ((unsigned)ix < (unsigned)wd) acc += ld(xp + (long)iy * wd + ix) * wk[u * K + v];
+      }
+    }
+    acc += b;
+    if (res) acc += ld(res + obase + e);
+    st(y + obase + e, act_f(acc, act));
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T* __restrict__ y, int h,
+                                                      int wd, int ho, int wo, int k, int stride,
+                                                      int pad) {
+  const int plane = blockIdx.x;
+  const T* xp = x + (long)plane * h * wd;
+  const int total = ho * wo;
+  for (int e = blockIdx.y * 256 + threadIdx.x; e < total; e += gridDim.y * 256) {
+    int oy = e / wo, ox = e - oy * wo;
+    int iy0 = oy * stride - pad, ix0 = ox * stride - pad;
+    float m = 0.0f;
+    bool have = false;
+    for (int u = 0; u < k; ++u) {
+      int iy = iy0 + u;
+      if ((unsigned)iy >= (unsigned)h) continue;
+      for (int v = 0; v < k; ++v) {
+        int ix = ix0 + v;
+        if ((unsigned)ix >= (unsigned)wd) continue;
+        float val = ld(xp + (long)iy * wd + ix);
+        if (!have || val > m) { m = val; have = true; }
+      }
+    }
+    st(y + (long)plane * total + e, m);
+  }
+}
+
+// One wavefront per (image, channel) plane: strided partial sums, then a
+// shuffle tree; 4 planes per work-group.
+template <typename T>
+__global__ __launch_bounds__(256) void gavgpool_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                       int planes, int hw) {
+  const int plane = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (plane >= planes) return;
+  const int lane = threadIdx.x & 63;
+  const T* xp = x + (long)plane * hw;
+  float s = 0.0f;
+  for (int i = lane; i < hw; i += 64) s += ld(xp + i);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+  if (lane == 0) st(y + plane, s / (float)hw);
+}
+
+int plane_slices(int total) {
+  int s = (total + 1023) / 1024;
+  return s < 1 ? 1 : (s > 64 ? 64 : s);
+}
+
+template <typename T>
+int depthwise_dispatch(const cprune_conv_desc& d, const void* x, const void* w, const float* bias,
+                       const void* res, void* y, hipStream_t s) {
+  const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
+  dim3 grid((unsigned)(d.n * d.c_in), (unsigned)plane_slices(ho * wo));
+#define GO(K)                                                                                     \
+  hipLaunchKernelGGL((depthwise_kernel<T, K>), grid, dim3(256), 0, s, (const T*)x, (const T*)w,  \
+                     bias, (const T*)res, (T*)y, d.c_in, d.h, d.w, ho, wo, d.stride, d.pad, d.act)
+  switch (d.kh) {
+    case 1: GO(1); break;
+    case 3: GO(3); break;
+    case 5: GO(5); break;
+    case 7: GO(7); break;
+    default: return CPRUNE_ERR_UNSUPPORTED;
+  }
+#undef GO
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+}  // namespace
+
+int launch_conv_depthwise(const cprune_conv_desc& d, const void* x, const void* w, const float* bias,
+                          const void* residual, void* y, hipStream_t s) {
+  if (d.kh != d.kw) return CPRUNE_ERR_UNSUPPORTED;
+  if (d.dtype == CPRUNE_F32) return depthwise_dispatch<float>(d, x, w, bias, residual, y, s);
+  if (d.dtype == CPRUNE_F16) return depthwise_dispatch<_Float16>(d, x, w, bias, residual, y, s);
+  return depthwise_dispatch<__bf16>(d, x, w, bias, residual, y, s);
+}
+
+int launch_maxpool(const void* x, int n, int c, int h, int w, int k, int stride, int pad, int dt,
+                   void* y, hipStream_t s) {
+  const int ho = conv_out_dim(h, k, stride, pad), wo = conv_out_dim(w, k, stride, pad);
+  dim3 grid((unsigned)(n * c), (unsigned)plane_slices(ho * wo));
+  if (dt == CPRUNE_F32)
+    hipLaunchKernelGGL(maxpool_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (float*)y, h, w,
+                       ho, wo, k, stride, pad);
+  else if (dt == CPRUNE_F16)
+    hipLaunchKernelGGL(maxpool_kernel<_Float16>, grid, dim3(256), 0, s, (const _Float16*)x,
+                       (_Float16*)y, h, w, ho, wo, k, stride, pad);
+  else
+    hipLaunchKernelGGL(maxpool_kernel<__bf16>, grid, dim3(256), 0, s, (const __bf16*)x, (__bf16*)y, h,
+                       w, ho, wo, k, stride, pad);
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+int launch_gavgpool(const void* x, int n, int c, int hw, int dt, void* y, hipStream_t s) {
+  const int planes = n * c;
+  dim3 grid((unsigned)((planes + 3) / 4));
+  if (dt == CPRUNE_F32)
+    hipLaunchKernelGGL(gavgpool_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (float*)y,
+                       planes, hw);
+  else if (dt == CPRUNE_F16)
+    hipLaunchKernelGGL(gavgpool_kernel<_Float16>, grid, dim3(256), 0, s, (const _Float16*)x,
+                       (_Float16*)y, planes, hw);
+  else
+    hipLaunchKernelGGL(gavgpool_kernel<__bf16>, grid, dim3(256), 0, s, (const __bf16*)x, (__bf16*)y,
+                       planes, hw);
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+}  // namespace cprune

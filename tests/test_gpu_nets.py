@@ -1,0 +1,141 @@
+"""GPU parity of the whole path (rank -> gather/fold -> inference handle) against the
+CPU oracle on the same seeded networks.  Kept lists bit-exact; logits and every layer's
+activations within the normalised max error bar (1e-4 fp32, 2e-2 fp16 / bf16 against the
+fp32 oracle)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2207_01260_amd import binding as B
+from paper_2207_01260_amd import pipeline, synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {B.F32: 1e-4, B.F16: 2e-2, B.BF16: 2e-2}
+
+
+def nmax(g, r):
+    g = np.asarray(g, dtype=np.float64)
+    r = np.asarray(r, dtype=np.float64)
+    assert g.shape == r.shape, (g.shape, r.shape)
+    return float(np.max(np.abs(g - r)) / max(np.max(np.abs(r)), 1e-30))
+
+
+def _run(orc, net, cid, batch, dtype, tune, check_layers=True, use_graph=False):
+    params = synth.layer_params(net, cid)
+    x = synth.net_input(net, cid, batch)
+    ref_layers, ref_kept = orc.prune_net(net, params)
+    ref_acts = orc.forward(net, ref_layers, x, return_all=True)
+
+    dparams = pipeline.upload_params(params)
+    layers, kept = pipeline.prune_net(net, dparams, dtype)
+    assert sorted(kept) == sorted(ref_kept)
+    for i in kept:
+        assert np.array_equal(kept[i].cpu().numpy(), ref_kept[i]), net.layers[i].name
+    if dtype == B.F32:
+        for q, r in zip(layers, ref_layers):
+            if "w" in q:
+                assert np.array_equal(q["w"].cpu().numpy(), r["w"])
+                assert np.array_equal(q["b"].cpu().numpy(), r["b"])
+    handle = pipeline.build_net(net, layers, batch, dtype, tune=tune)
+    xd = torch.from_numpy(x).cuda().to(B.TORCH_DTYPE[dtype])
+    logits = handle.forward(xd, use_graph=use_graph)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    if check_layers:
+        for i, r in enumerate(ref_acts[:-1]):
+            a = handle.activation(i, batch, r.shape[1:]).float().cpu().numpy()
+            e = nmax(a, r)
+            assert e < tol, (net.layers[i].name, e)
+    err = nmax(logits.float().cpu().numpy(), ref_acts[-1])
+    assert err < tol, err
+    return handle, xd, logits, ref_acts[-1]
+
+
+def test_single_layer_config(orc):
+    """One 3x3 conv+BN+ReLU, 64 filters ranked, top 45 kept, 32x32, batch 1."""
+    net = synth.single_conv(64, 64, 32)
+    params = synth.layer_params(net, 1)
+    params[0]["keep"] = 45
+    x = synth.net_input(net, 1, 1)
+    ref_layers, ref_kept = orc.prune_net(net, params)
+    ref = orc.forward(net, ref_layers, x)
+    dparams = pipeline.upload_params(params)
+    layers, kept = pipeline.prune_net(net, dparams)
+    assert np.array_equal(kept[0].cpu().numpy(), ref_kept[0]) and kept[0].numel() == 45
+    d = B.conv_desc(x.shape, layers[0]["w"].shape, 1, 1)
+    y = B.cprune_conv2d_bn_relu(d, torch.from_numpy(x).cuda(), layers[0]["w"], layers[0]["b"])
+    assert nmax(y.cpu().numpy(), ref) < 1e-4
+    # dropping the filters == zeroing those channels of the unpruned layer, then slicing
+    full_layers, _ = pipeline.prune_net(net, dparams, keep_override={0: 64})
+    dfull = B.conv_desc(x.shape, full_layers[0]["w"].shape, 1, 1)
+    yfull = B.cprune_conv2d_bn_relu(dfull, torch.from_numpy(x).cuda(), full_layers[0]["w"],
+                                    full_layers[0]["b"])
+    sliced = B.cprune_gather_channels(yfull, kept[0])
+    assert nmax(sliced.cpu().numpy(), ref) < 1e-4
+
+
+@pytest.mark.parametrize("batch", [1, 3])
+def test_vgg16_fp32(orc, batch):
+    print("vgg16 fp32 batch", batch, flush=True)
+    handle, xd, logits, _ = _run(orc, synth.vgg16(10, 32), 2, batch, B.F32, tune=(batch == 3))
+    # graph replay gives the same bits as the eager run, several times over
+    for _ in range(3):
+        again = handle.forward(xd, use_graph=True)
+        torch.cuda.synchronize()
+        assert torch.equal(again, logits)
+    handle.close()
+
+
+@pytest.mark.parametrize("dtype", [B.F16, B.BF16])
+def test_vgg16_16bit(orc, dtype):
+    print("vgg16 16-bit", dtype, flush=True)
+    handle, *_ = _run(orc, synth.vgg16(10, 32), 2, 2, dtype, tune=False)
+    handle.close()
+
+
+def test_vgg16_smaller_batch_than_max(orc):
+    net = synth.vgg16(10, 32)
+    params = synth.layer_params(net, 2)
+    x = synth.net_input(net, 2, 4)
+    ref_layers, _ = orc.prune_net(net, params)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params))
+    handle = pipeline.build_net(net, layers, 4, tune=False)
+    xd = torch.from_numpy(x).cuda()
+    y4 = handle.forward(xd).cpu().numpy()
+    y2 = handle.forward(xd[:2].contiguous()).cpu().numpy()
+    ref = orc.forward(net, ref_layers, x)
+    assert nmax(y4, ref) < 1e-4 and nmax(y2, ref[:2]) < 1e-4
+    with pytest.raises(B.CPruneError):
+        handle.forward(torch.zeros((5, 3, 32, 32), device="cuda"))
+    handle.close()
+
+
+def test_resnet18_reduced_input(orc):
+    print("resnet18 64x64", flush=True)
+    handle, *_ = _run(orc, synth.resnet18(100, 64), 3, 2, B.F32, tune=False)
+    handle.close()
+
+
+def test_resnet18_bf16(orc):
+    handle, *_ = _run(orc, synth.resnet18(100, 64), 3, 2, B.BF16, tune=False, check_layers=False)
+    handle.close()
+
+
+def test_mobilenetv2_reduced_input(orc):
+    print("mobilenetv2 64x64", flush=True)
+    handle, *_ = _run(orc, synth.mobilenetv2(100, 64), 4, 2, B.F32, tune=False)
+    handle.close()
+
+
+def test_resnet18_full_size_batch1(orc):
+    print("resnet18 224 b1", flush=True)
+    handle, *_ = _run(orc, synth.resnet18(1000, 224), 3, 1, B.F32, tune=False, check_layers=False)
+    handle.close()
+
+
+def test_mobilenetv2_full_size_batch1(orc):
+    print("mobilenetv2 224 b1", flush=True)
+    handle, *_ = _run(orc, synth.mobilenetv2(1000, 224), 4, 1, B.F32, tune=False,
+                      check_layers=False)
+    handle.close()

@@ -1,0 +1,286 @@
+"""GPU parity: every C-ABI call against the CPU oracle on the same seeded inputs.
+
+Bar: ranking / kept lists and gathers bit-exact; fp32 activations within 1e-4
+normalised max error  max|gpu - ref| / max|ref|  per output tensor; fp16 / bf16
+within 2e-2 against the fp32 oracle on the same fp32 inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2207_01260_amd import binding as B
+from paper_2207_01260_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {B.F32: 1e-4, B.F16: 2e-2, B.BF16: 2e-2}
+EPS = float(np.float32(1e-5))
+
+
+def nmax(g, r):
+    g = np.asarray(g, dtype=np.float64)
+    r = np.asarray(r, dtype=np.float64)
+    assert g.shape == r.shape
+    return float(np.max(np.abs(g - r)) / max(np.max(np.abs(r)), 1e-30))
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(B.TORCH_DTYPE[dtype])
+
+
+def host(t):
+    return t.float().cpu().numpy() if t.dtype != torch.float32 else t.cpu().numpy()
+
+
+# ---- ranking -------------------------------------------------------------------
+
+@pytest.mark.parametrize("shape,keep", [
+    ((64, 64, 3, 3), 45), ((7, 3, 3, 3), 1), ((1, 5, 1, 1), 1), ((130, 17, 3, 3), 129),
+    ((512, 512, 3, 3), 300), ((960, 160, 1, 1), 500), ((32, 1, 3, 3), 11), ((64, 3, 7, 7), 64),
+])
+def test_rank_filters_bit_exact(orc, shape, keep):
+    print("rank", shape, keep, flush=True)
+    w = synth.tensor_normal(shape, 101, *shape)
+    s_ref, order_ref, kept_ref = orc.rank_filters(w, keep)
+    assert synth.min_relative_gap(s_ref) > 1e-9 or shape[0] == 1
+    s, order, kept = B.cprune_rank_filters(dev(w), keep)
+    assert np.array_equal(kept.cpu().numpy(), kept_ref)
+    assert np.array_equal(order.cpu().numpy(), order_ref)
+    assert np.max(np.abs(s.cpu().numpy() - s_ref) / s_ref) < 1e-12
+    # kept list alone (scores in caller scratch), twice: identical bits
+    _, _, kept2 = B.cprune_rank_filters(dev(w), keep, want_scores=False, want_order=False)
+    assert np.array_equal(kept2.cpu().numpy(), kept_ref)
+
+
+def test_rank_ties_and_dyadic(orc):
+    # dyadic weights: sums exact in any order -> true ties, lower index first
+    base = np.where(synth.uniform01(5, 6 * 4 * 9) < 0.5, -1.0, 1.0).reshape(6, 4, 3, 3)
+    scale = np.array([0.5, 0.25, 0.5, 1.0, 0.25, 0.5]).reshape(6, 1, 1, 1)
+    w = (base * scale).astype(np.float32)
+    for keep in range(1, 7):
+        s_ref, order_ref, kept_ref = orc.rank_filters(w, keep)
+        s, order, kept = B.cprune_rank_filters(dev(w), keep)
+        assert order_ref.tolist() == [3, 0, 2, 5, 1, 4]
+        assert np.array_equal(order.cpu().numpy(), order_ref)
+        assert np.array_equal(kept.cpu().numpy(), kept_ref)
+        assert np.array_equal(s.cpu().numpy(), s_ref)
+    # duplicated filters
+    w = synth.tensor_normal((40, 8, 3, 3), 102)
+    w[7] = w[3]
+    w[22] = w[3]
+    for keep in (1, 5, 20, 39):
+        _, order_ref, kept_ref = orc.rank_filters(w, keep)
+        _, order, kept = B.cprune_rank_filters(dev(w), keep)
+        assert np.array_equal(order.cpu().numpy(), order_ref)
+        assert np.array_equal(kept.cpu().numpy(), kept_ref)
+
+
+def test_rank_nested_all_keeps(orc):
+    w = synth.tensor_normal((128, 128, 3, 3), 103)
+    s_ref = orc.l1_scores(w)
+    wd = dev(w)
+    for keep in (1, 2, 15, 16, 17, 45, 64, 127, 128):
+        _, kept_ref = orc.rank(s_ref, keep)
+        _, _, kept = B.cprune_rank_filters(wd, keep, want_scores=False, want_order=False)
+        assert np.array_equal(kept.cpu().numpy(), kept_ref)
+
+
+# ---- gather / fold ---------------------------------------------------------------
+
+def _bn(c, tag):
+    return (synth.tensor_uniform((c,), 0.5, 1.5, tag, 1), synth.tensor_normal((c,), tag, 2, std=0.1),
+            synth.tensor_normal((c,), tag, 3, std=0.1), synth.tensor_uniform((c,), 0.5, 1.5, tag, 4))
+
+
+@pytest.mark.parametrize("shape,n_out,n_in", [
+    ((64, 64, 3, 3), 45, None), ((64, 64, 3, 3), None, 45), ((37, 29, 3, 3), 20, 11),
+    ((96, 16, 1, 1), 50, None), ((10, 512, 1, 1), None, 300), ((32, 1, 3, 3), 13, None),
+    ((512, 512, 3, 3), 301, 277), ((8, 3, 7, 7), None, None),
+])
+def test_gather_fold_bit_exact(orc, shape, n_out, n_in):
+    print("gather", shape, n_out, n_in, flush=True)
+    w = synth.tensor_normal(shape, 110, *shape)
+    rng = np.random.RandomState(shape[0] * 7 + shape[1])
+    ko = None if n_out is None else np.sort(rng.choice(shape[0], n_out, replace=False)).astype(np.int32)
+    ki = None if n_in is None else np.sort(rng.choice(shape[1], n_in, replace=False)).astype(np.int32)
+    g, b, m, v = _bn(shape[0], 111)
+    wg = orc.gather_weights(w, ko, ki)
+    w_ref, b_ref = orc.fold_bn(wg, orc.gather_vec(g, ko), orc.gather_vec(b, ko),
+                               orc.gather_vec(m, ko), orc.gather_vec(v, ko), EPS)
+    w_out, b_out = B.cprune_gather_pruned_weights(
+        dev(w), None if ko is None else dev(ko), None if ki is None else dev(ki),
+        (dev(g), dev(b), dev(m), dev(v)), EPS)
+    assert np.array_equal(w_out.cpu().numpy(), w_ref)
+    assert np.array_equal(b_out.cpu().numpy(), b_ref)
+    # no BN: a pure gather
+    w_out2, b2 = B.cprune_gather_pruned_weights(dev(w), None if ko is None else dev(ko),
+                                                None if ki is None else dev(ki))
+    assert b2 is None and np.array_equal(w_out2.cpu().numpy(), wg)
+    # 16-bit outputs are the fp32 result rounded to nearest even
+    for dt in (B.F16, B.BF16):
+        w16, _ = B.cprune_gather_pruned_weights(
+            dev(w), None if ko is None else dev(ko), None if ki is None else dev(ki),
+            (dev(g), dev(b), dev(m), dev(v)), EPS, None, dt)
+        ref16 = torch.from_numpy(w_ref).to(B.TORCH_DTYPE[dt])
+        bad = int((w16.cpu() != ref16).sum())
+        assert bad == 0, (dt, bad, ref16.numel())
+
+
+def test_gather_with_conv_bias(orc):
+    w = synth.tensor_normal((12, 5, 3, 3), 112)
+    cb = synth.tensor_normal((12,), 113)
+    g, b, m, v = _bn(12, 114)
+    ko = np.array([0, 2, 3, 7, 11], np.int32)
+    w_ref, b_ref = orc.fold_bn(orc.gather_weights(w, ko, None), orc.gather_vec(g, ko),
+                               orc.gather_vec(b, ko), orc.gather_vec(m, ko), orc.gather_vec(v, ko),
+                               EPS, orc.gather_vec(cb, ko))
+    w_out, b_out = B.cprune_gather_pruned_weights(dev(w), dev(ko), None,
+                                                  (dev(g), dev(b), dev(m), dev(v)), EPS, dev(cb))
+    assert np.array_equal(w_out.cpu().numpy(), w_ref) and np.array_equal(b_out.cpu().numpy(), b_ref)
+    _, b_only = B.cprune_gather_pruned_weights(dev(w), dev(ko), None, None, EPS, dev(cb))
+    assert np.array_equal(b_only.cpu().numpy(), cb[ko])
+
+
+@pytest.mark.parametrize("dt", [B.F32, B.F16])
+def test_gather_channels(orc, dt):
+    x = synth.tensor_normal((3, 37, 9, 11), 115)
+    idx = np.array([0, 5, 6, 20, 36], np.int32)
+    xd = dev(x, dt)
+    y = B.cprune_gather_channels(xd, dev(idx))
+    assert torch.equal(y.cpu(), xd.cpu()[:, idx.tolist()])
+    if dt == B.F32:
+        assert np.array_equal(y.cpu().numpy(), orc.gather_channels(x, idx))
+
+
+# ---- convolution ---------------------------------------------------------------------
+
+def _conv_case(orc, n, c_in, h, w, c_out, k, stride, pad, act=B.ACT_RELU, residual=False,
+               dtype=B.F32, variants=(-1,), tag=0):
+    x = synth.tensor_normal((n, c_in, h, w), 120, tag, n, c_in, h)
+    wt = synth.tensor_normal((c_out, c_in, k, k), 121, tag, c_out, std=(2.0 / (c_in * k * k)) ** 0.5)
+    bias = synth.tensor_normal((c_out,), 122, tag, std=0.1)
+    d = B.conv_desc(x.shape, wt.shape, stride, pad, 1, dtype, act, residual)
+    res = synth.tensor_normal(B.out_shape(d), 123, tag) if residual else None
+    ref = orc.conv2d_bias_act(x, wt, bias, stride, pad, 1, act, res)
+    xd, wd, bd = dev(x, dtype), dev(wt, dtype), dev(bias)
+    rd = dev(res, dtype) if residual else None
+    worst = 0.0
+    for v in variants:
+        if v >= 0:
+            ws_need = B.cprune_conv_workspace_bytes(d, v)
+            try:
+                y = B.cprune_conv2d_bn_relu(d, xd, wd, bd, rd, v)
+            except B.CPruneError as e:
+                assert e.status == B.ERR_UNSUPPORTED, (v, str(e))
+                continue
+            assert ws_need >= 0
+        else:
+            y = B.cprune_conv2d_bn_relu(d, xd, wd, bd, rd, -1)
+        err = nmax(host(y), ref)
+        assert err < TOL[dtype], (v, B.cprune_tile_variant_info(v) if v >= 0 else v, err)
+        worst = max(worst, err)
+    return worst
+
+
+def test_conv_config1_every_variant(orc):
+    """64 -> 45 of 64 filters at 32x32, batch 1: every tile variant must agree with the oracle."""
+    nv = B.cprune_num_tile_variants()
+    print("conv config1 all variants", nv, flush=True)
+    _conv_case(orc, 1, 64, 32, 32, 45, 3, 1, 1, variants=range(nv), tag=1)
+
+
+@pytest.mark.parametrize("cfg", [
+    # n, c_in, h, w, c_out, k, stride, pad
+    (2, 45, 13, 11, 37, 3, 1, 1),       # ragged everywhere, two images share tiles
+    (3, 7, 9, 9, 5, 3, 1, 1),           # tiny
+    (1, 3, 32, 32, 64, 3, 1, 1),        # first VGG layer: K = 27
+    (2, 64, 16, 16, 128, 1, 1, 0),      # 1x1 == GEMM
+    (2, 29, 15, 17, 33, 1, 2, 0),       # 1x1 stride 2 (downsample shortcut)
+    (2, 16, 17, 15, 24, 3, 2, 1),       # 3x3 stride 2
+    (1, 3, 37, 35, 20, 7, 2, 3),        # stem 7x7/2
+    (1, 8, 6, 6, 300, 3, 1, 1),         # many filters, few pixels
+    (5, 33, 2, 2, 70, 3, 1, 1),         # 2x2 maps (deep VGG layers)
+    (4, 100, 1, 1, 10, 1, 1, 0),        # FC-shaped
+    (1, 16, 8, 8, 16, 5, 1, 2),
+])
+def test_conv_shapes_every_variant(orc, cfg):
+    print("conv", cfg, flush=True)
+    _conv_case(orc, *cfg, variants=list(range(B.cprune_num_tile_variants())) + [-1], tag=2)
+
+
+def test_conv_act_and_residual(orc):
+    for act in (B.ACT_NONE, B.ACT_RELU, B.ACT_RELU6):
+        for res in (False, True):
+            _conv_case(orc, 2, 19, 10, 10, 23, 3, 1, 1, act=act, residual=res, variants=(-1, 0, 9, 46),
+                       tag=3)
+
+
+@pytest.mark.parametrize("dtype", [B.F16, B.BF16])
+def test_conv_16bit(orc, dtype):
+    print("conv 16-bit", dtype, flush=True)
+    nv = B.cprune_num_tile_variants()
+    _conv_case(orc, 1, 64, 32, 32, 45, 3, 1, 1, dtype=dtype, variants=range(nv), tag=4)
+    _conv_case(orc, 2, 45, 13, 11, 37, 3, 1, 1, dtype=dtype, variants=range(nv), tag=4)
+    _conv_case(orc, 2, 29, 15, 17, 33, 1, 2, 0, dtype=dtype, residual=True, variants=(-1, 3), tag=4)
+    _conv_case(orc, 1, 3, 37, 35, 20, 7, 2, 3, dtype=dtype, variants=(-1, 5), tag=4)
+
+
+def test_conv_repeatable(orc):
+    x = dev(synth.tensor_normal((2, 64, 16, 16), 124))
+    w = dev(synth.tensor_normal((96, 64, 3, 3), 125, std=0.05))
+    d = B.conv_desc(x.shape, w.shape, 1, 1)
+    for v in (0, 3 * 5 + 2, -1):
+        a = B.cprune_conv2d_bn_relu(d, x, w, None, None, v)
+        b = B.cprune_conv2d_bn_relu(d, x, w, None, None, v)
+        assert torch.equal(a, b)
+
+
+def test_select_tile_and_cache(orc):
+    B.cprune_clear_tile_cache()
+    x = dev(synth.tensor_normal((2, 32, 16, 16), 126))
+    w = dev(synth.tensor_normal((40, 32, 3, 3), 127, std=0.08))
+    d = B.conv_desc(x.shape, w.shape, 1, 1)
+    v0, timed0 = B.cprune_cached_tile(d)
+    assert not timed0 and 0 <= v0 < B.cprune_num_tile_variants()
+    v, best, all_ms = B.cprune_select_tile(d, x, w, warmup=1, iters=3)
+    assert 0 <= v < len(all_ms) and all_ms[v] == pytest.approx(best) and best > 0
+    assert best == min(m for m in all_ms if m >= 0)
+    v1, timed1 = B.cprune_cached_tile(d)
+    assert timed1 and v1 == v
+    ref = orc.conv2d_bias_act(x.cpu().numpy(), w.cpu().numpy(), None, 1, 1, 1, B.ACT_RELU)
+    assert nmax(B.cprune_conv2d_bn_relu(d, x, w).cpu().numpy(), ref) < 1e-4
+    B.cprune_clear_tile_cache()
+    assert not B.cprune_cached_tile(d)[1]
+
+
+# ---- depthwise / pools / fc ------------------------------------------------------------
+
+@pytest.mark.parametrize("cfg", [(2, 37, 14, 14, 3, 1, 1), (2, 24, 15, 13, 3, 2, 1), (1, 8, 9, 9, 5, 1, 2)])
+@pytest.mark.parametrize("dtype", [B.F32, B.F16])
+def test_depthwise(orc, cfg, dtype):
+    n, c, h, w, k, s, p = cfg
+    x = synth.tensor_normal((n, c, h, w), 130, *cfg)
+    wt = synth.tensor_normal((c, 1, k, k), 131, *cfg, std=0.4)
+    bias = synth.tensor_normal((c,), 132, std=0.1)
+    d = B.conv_desc(x.shape, (c, 1, k, k), s, p, c, dtype, B.ACT_RELU6, False)
+    y = B.cprune_conv2d_bn_relu(d, dev(x, dtype), dev(wt, dtype), dev(bias))
+    ref = orc.conv2d_bias_act(x, wt, bias, s, p, c, B.ACT_RELU6)
+    assert nmax(host(y), ref) < TOL[dtype]
+
+
+def test_maxpool_gavgpool_fc(orc):
+    x = synth.tensor_normal((3, 13, 16, 16), 140)
+    assert np.array_equal(B.cprune_maxpool2d(dev(x), 2, 2).cpu().numpy(), orc.maxpool(x, 2, 2))
+    x2 = -1.0 - np.abs(synth.tensor_normal((2, 5, 15, 13), 141))
+    assert np.array_equal(B.cprune_maxpool2d(dev(x2), 3, 2, 1).cpu().numpy(), orc.maxpool(x2, 3, 2, 1))
+    g = B.cprune_global_avgpool(dev(x)).cpu().numpy()
+    assert nmax(g, orc.gavgpool(x).reshape(3, 13)) < 1e-6
+    h16 = B.cprune_maxpool2d(dev(x, B.F16), 2, 2)
+    assert torch.equal(h16.cpu(), torch.nn.functional.max_pool2d(dev(x, B.F16).cpu().float(), 2, 2).half())
+    for (n, f, c) in [(1, 300, 10), (64, 331, 10), (5, 1280, 1000)]:
+        xf = synth.tensor_normal((n, f), 142, n)
+        wf = synth.tensor_normal((c, f), 143, n, std=(2.0 / f) ** 0.5)
+        bf = synth.tensor_normal((c,), 144, std=0.1)
+        y = B.cprune_fc(dev(xf), dev(wf), dev(bf)).cpu().numpy()
+        assert nmax(y, orc.fc(xf, wf, bf)) < 1e-4
