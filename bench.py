@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark: images/s of the pruned VGG-16 (32x32 inputs) on one MI355X.
+
+A step is one pass of the inference hot path over one batch of synthetic images:
+13 pruned conv+BN+ReLU layers (MFMA implicit GEMM), 5 max-pools and the FC, through
+cprune_net_forward.  The one-off pruning stage (L1 ranking, kept-list selection, weight
+gather with BN folding) and the per-shape tile selection run before the timed region and
+are reported separately (`prune_ms`, `tune_s`).  Inputs and weights are resident in HBM
+when timing starts.
+
+Prints ONE JSON line; see the design doc for the definition of every field.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}   # dense MFMA TFLOP/s, MI355X
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--dtype", default="f32", choices=["f32", "f16", "bf16"])
+    ap.add_argument("--no-graph", action="store_true", help="launch layer by layer, no HIP graph")
+    ap.add_argument("--no-tune", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip batch-1 and fp16 side figures")
+    ap.add_argument("--cpu-images", type=int, default=0, help="oracle sample size (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2207_01260_amd import binding as B
+    from paper_2207_01260_amd import pipeline, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    dt = {"f32": B.F32, "f16": B.F16, "bf16": B.BF16}[args.dtype]
+
+    net = synth.vgg16(10, 32)
+    cid = 2
+    params = synth.layer_params(net, cid)
+    dparams = pipeline.upload_params(params)
+
+    def build(dtype, batch, tune):
+        layers, kept = pipeline.prune_net(net, dparams, dtype)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        handle = pipeline.build_net(net, layers, batch, dtype, tune=tune)
+        return handle, layers, kept, time.perf_counter() - t0
+
+    def time_forward(handle, x, steps, warmup, graph):
+        logits = torch.empty((x.shape[0], 10), dtype=x.dtype, device="cuda")
+        for _ in range(warmup):
+            handle.forward(x, logits, use_graph=graph)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            handle.forward(x, logits, use_graph=graph)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    # ---- prune stage (one-off), timed on its own -------------------------------------
+    pipeline.prune_net(net, dparams, dt)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reps = 5
+    for _ in range(reps):
+        pipeline.prune_net(net, dparams, dt)
+    torch.cuda.synchronize()
+    prune_ms = (time.perf_counter() - t0) / reps * 1e3
+
+    # ---- main measurement -------------------------------------------------------------
+    graph = not args.no_graph
+    handle, layers, kept, tune_s = build(dt, args.batch, not args.no_tune)
+    kept_counts = {i: int(k.numel()) for i, k in kept.items()}
+    x = torch.from_numpy(synth.net_input(net, cid, args.batch)).cuda().to(B.TORCH_DTYPE[dt])
+    ms = time_forward(handle, x, args.steps, args.warmup, graph)
+    value = args.batch / (ms * 1e-3)
+
+    # per-layer device time (HIP events on the launch stream), conv layers = dominant kernel
+    layer_ms = handle.layer_times(x, iters=20)
+    conv_ms = sum(m for m, L in zip(layer_ms, net.layers) if L.kind == "conv")
+    n_conv = sum(1 for L in net.layers if L.kind == "conv")
+    conv_flops = pipeline.useful_flops(net, kept_counts, args.batch, conv_only=True)
+    total_flops = pipeline.useful_flops(net, kept_counts, args.batch)
+    achieved = conv_flops / (conv_ms * 1e-3) / 1e12
+    per_layer = []
+    shp = synth.shapes(net, kept_counts)
+    for i, (L, m) in enumerate(zip(net.layers, layer_ms)):
+        if L.kind != "conv":
+            continue
+        cin, cout, ho, wo = shp[i]
+        fl = 2.0 * args.batch * cout * cin * 9 * ho * wo
+        tm, tp, sk = B.cprune_tile_variant_info(handle.layer_variant(i))
+        per_layer.append({"layer": L.name, "c_in": cin, "c_out": cout, "hw": ho, "us": round(m * 1e3, 2),
+                          "tflops": round(fl / (m * 1e-3) / 1e12, 2), "tile": f"{tm}x{tp}/k{sk}"})
+
+    out = {
+        "metric": "images/sec pruned VGG-16 32x32",
+        "value": round(value, 1), "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"pruned VGG-16 (13 conv + FC), 32x32x3 inputs, keep ratios U(0.4,0.9), "
+                               f"batch {args.batch}", "batch": args.batch, "hip_graph": graph,
+                   "kept_filters": [kept_counts[i] for i in sorted(kept_counts)]},
+        "useful_gflop_per_step": round(total_flops / 1e9, 3),
+        "whole_net_tflops": round(total_flops / (ms * 1e-3) / 1e12, 2),
+        "prune_ms": round(prune_ms, 3), "tune_s": round(tune_s, 2),
+        "roofline": {"bound": "mfma", "kernel": "conv_igemm_kernel (all conv layers of one step)",
+                     "achieved": round(achieved, 2), "peak": PEAK[args.dtype], "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK[args.dtype], 4), "traffic": None,
+                     "launches_per_step": n_conv, "avg_launch_us": round(conv_ms / n_conv * 1e3, 2),
+                     "useful_gflop_per_launch_avg": round(conv_flops / n_conv / 1e9, 3)},
+        "layers": per_layer,
+    }
+    handle.close()
+
+    if not args.no_extras:
+        extras = {}
+        for name, dtype, batch in [("f32_b1", B.F32, 1), ("f16_b64", B.F16, 64), ("f16_b1", B.F16, 1),
+                                   ("f32_b64", B.F32, 64)]:
+            if dtype == dt and batch == args.batch:
+                continue
+            h, _, _, _ = build(dtype, batch, not args.no_tune)
+            xb = torch.from_numpy(synth.net_input(net, cid, batch)).cuda().to(B.TORCH_DTYPE[dtype])
+            m_graph = time_forward(h, xb, max(50, args.steps // 2), 10, True)
+            m_eager = time_forward(h, xb, max(50, args.steps // 2), 10, False)
+            extras[name] = {"images_per_s": round(batch / (min(m_graph, m_eager) * 1e-3), 1),
+                            "ms_graph": round(m_graph, 4), "ms_eager": round(m_eager, 4)}
+            h.close()
+        out["extras"] = extras
+
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.num_threads()
+        ref_layers, _ = oracle.prune_net(net, params)
+        x1 = synth.net_input(net, cid, 2)
+        t0 = time.perf_counter()
+        oracle.forward(net, ref_layers, x1)
+        per_img = (time.perf_counter() - t0) / 2
+        n_img = args.cpu_images or int(min(512, max(4, 15.0 / max(per_img, 1e-4))))
+        xs = synth.net_input(net, cid, n_img)
+        t0 = time.perf_counter()
+        oracle.forward(net, ref_layers, xs)
+        dt_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(n_img / dt_cpu, 2), "unit": "images/s", "cores": threads,
+                               "kind": "oracle",
+                               "sample": f"{n_img} images of the same pruned VGG-16, fp64-accumulate "
+                                         f"direct loops, OpenMP over (image, filter), {dt_cpu:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -200,9 +200,9 @@ int cprune_net_create(const cprune_layer_desc* layers, int n_layers, int in_c, i
                       int in_w, int max_batch, cprune_dtype dtype, int tune, void* stream,
                       cprune_net** out);
 /* logits: [n][c_out of the last layer] in the net's dtype.  1 <= n <= max_batch.
- * use_graph != 0 replays a HIP graph of the layer sequence, captured on first use
- * for this n (the capture call itself synchronises nothing but must not overlap
- * other work on `stream`). */
+ * use_graph != 0 replays a HIP graph of the layer sequence on `stream`; the graph is
+ * recorded (on a stream the handle owns, nothing executes while recording) the
+ * first time a given (n, x, logits) triple is seen and kept until destroy. */
 int cprune_net_forward(cprune_net* net, const void* x, int n, void* logits, int use_graph,
                        void* stream);
 /* Per-layer device time of one forward, averaged over `iters` runs, bracketing

@@ -281,12 +281,11 @@ struct NetLayer {
 };
 
 struct GraphKey {
-  int n; const void* x; void* logits; hipStream_t s;
+  int n; const void* x; void* logits;
   bool operator<(const GraphKey& o) const {
     if (n != o.n) return n < o.n;
     if (x != o.x) return x < o.x;
-    if (logits != o.logits) return logits < o.logits;
-    return s < o.s;
+    return logits < o.logits;
   }
 };
 
@@ -297,6 +296,7 @@ struct cprune_net {
   void* ws = nullptr;
   size_t ws_bytes = 0;
   std::map<GraphKey, hipGraphExec_t> graphs;
+  hipStream_t capture_stream = nullptr;  // graphs are recorded here (the caller's may be the null stream)
   int last_n = 0;
 };
 
@@ -316,6 +316,7 @@ static cprune_conv_desc layer_conv_desc(const cprune_net& net, const NetLayer& L
 
 static void net_free(cprune_net* net) {
   for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
+  if (net->capture_stream) hipStreamDestroy(net->capture_stream);
   for (void* p : net->allocs) hipFree(p);
   delete net;
 }
@@ -473,13 +474,15 @@ extern "C" int cprune_net_forward(cprune_net* net, const void* x, int n, void* l
   hipStream_t s = (hipStream_t)stream;
   net->last_n = n;
   if (!use_graph) return net_enqueue(net, x, n, logits, s);
-  GraphKey key{n, x, logits, s};
+  GraphKey key{n, x, logits};
   auto it = net->graphs.find(key);
   if (it == net->graphs.end()) {
+    if (!net->capture_stream) CPRUNE_HIP_TRY(hipStreamCreateWithFlags(&net->capture_stream, hipStreamNonBlocking));
+    hipStream_t cs = net->capture_stream;
     hipGraph_t graph = nullptr;
-    CPRUNE_HIP_TRY(hipStreamBeginCapture(s, hipStreamCaptureModeRelaxed));
-    int rc = net_enqueue(net, x, n, logits, s);
-    hipError_t e = hipStreamEndCapture(s, &graph);
+    CPRUNE_HIP_TRY(hipStreamBeginCapture(cs, hipStreamCaptureModeRelaxed));
+    int rc = net_enqueue(net, x, n, logits, cs);
+    hipError_t e = hipStreamEndCapture(cs, &graph);
     if (rc != CPRUNE_OK) { if (graph) hipGraphDestroy(graph); return rc; }
     if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
     hipGraphExec_t exec = nullptr;
