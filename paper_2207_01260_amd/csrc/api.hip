@@ -28,6 +28,11 @@ int validate_conv_desc(const cprune_conv_desc* d) {
   if (d->pad >= d->kh || d->pad >= d->kw) return CPRUNE_ERR_UNSUPPORTED;  // every window holds a real element
   const long ho = conv_out_dim(d->h, d->kh, d->stride, d->pad), wo = conv_out_dim(d->w, d->kw, d->stride, d->pad);
   const long lim = 1L << 31;
+  if (d->groups == 1) {  // the dense kernel addresses x and w with 31-bit byte offsets
+    const long es = (long)dtype_size(d->dtype);
+    if ((long)d->n * d->c_in * d->h * d->w * es >= lim) return CPRUNE_ERR_UNSUPPORTED;
+    if ((long)d->c_out * d->c_in * d->kh * d->kw * es >= lim) return CPRUNE_ERR_UNSUPPORTED;
+  }
   if ((long)d->n * d->c_in * d->h * d->w >= lim || (long)d->n * d->c_out * ho * wo >= lim) return CPRUNE_ERR_UNSUPPORTED;
   if ((long)d->c_out * (d->c_in / d->groups) * d->kh * d->kw >= lim) return CPRUNE_ERR_UNSUPPORTED;
   if ((long)d->c_in * d->kh * d->kw * d->kh * d->kw >= lim) return CPRUNE_ERR_UNSUPPORTED;  // exact magic division

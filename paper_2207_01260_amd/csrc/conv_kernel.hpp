@@ -1,0 +1,429 @@
+// Dense convolution as an implicit GEMM on the gfx950 matrix cores (device code).
+//
+// The subgraph of Section 3.4 of the paper (Conv2d + folded BN + ReLU) at the
+// channel counts filter pruning leaves behind (Section 2.1): rows of the GEMM
+// are the c_out surviving filters, columns the n*h_out*w_out output pixels, the
+// reduction runs over k = (c, u, v) in the weights' own OIHW order.  Nothing is
+// padded in HBM: tails in every dimension are zero-filled while staging into
+// LDS and skipped in the epilogue; whole 16-row MFMA blocks past c_out are not
+// issued at all (the main loop is compiled once per block count and the
+// work-group picks its copy).
+//
+// One work-group = 4 wavefronts arranged WM x WN; a wavefront owns MB x NB
+// accumulator blocks of 16x16 (v_mfma_f32_16x16x4_f32 for fp32 data,
+// v_mfma_f32_16x16x32_{f16,bf16} for 16-bit data).  Per slab of the reduction
+// (KT = 16 floats or 32 halves of k per row) the work-group stages an A tile
+// [MT][KT] of weights and a B tile [PT][KT] of gathered input pixels into
+// double-buffered LDS, rows k-contiguous, so each lane fetches its MFMA
+// operands for the whole slab with one 16-byte LDS read per block.  The order
+// in which k is consumed inside a slab is a permutation of the natural one
+// (lane group g holds columns 4g..4g+3 of a 16-byte quad layout); A and B use
+// the same permutation, which leaves the sum unchanged.
+//
+// The im2col gather is table-driven: for each k of a slab a small LDS table
+// holds the input byte offset (c*H*W + u*W + v) and the tap bits (u, v); each
+// staging thread keeps, per pixel it serves, a base offset and the mask of the
+// taps that fall inside the image.  Loads are raw buffer loads: an element that
+// is padding, past the end of k, or past the last pixel gets an offset beyond
+// the buffer's size and reads as zero, without a branch.
+#pragma once
+#include "common.hpp"
+
+#include <type_traits>
+
+namespace cprune {
+
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+struct ConvArgs {
+  const void* x;
+  const void* w;
+  const float* bias;
+  const void* res;
+  void* y;
+  float* partial;  // [split_k][O][P] when split_k > 1
+  int N, C, H, W, O, KH, KW, stride, pad, Ho, Wo;
+  int K, P, HoWo, HW, KHW;
+  unsigned magic_khw, magic_kw;  // ceil(2^32 / d), 0 when d == 1
+  unsigned x_bytes, w_bytes;     // sizes of the x and w tensors (< 2^31)
+  int act;
+  int tiles_m, tiles_p;
+  int split_k, k_per_split;
+};
+
+constexpr unsigned kOutOfRange = 0x80000000u;  // beyond any buffer this kernel accepts
+constexpr int ROW_BYTES = 80;  // 64 bytes of k per row + 16 so rows rotate across LDS banks
+
+__device__ __forceinline__ unsigned fast_div(unsigned n, unsigned magic) {
+  return magic ? __umulhi(n, magic) : n;
+}
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == CPRUNE_ACT_RELU) return fmaxf(v, 0.0f);
+  if (act == CPRUNE_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
+  return v;
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  typedef uint32_t raw_t;
+  static __device__ __forceinline__ float to_f32(float v) { return v; }
+  static __device__ __forceinline__ float from_f32(float v) { return v; }
+  static __device__ __forceinline__ raw_t load(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+    return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
+  }
+};
+template <> struct Elem<_Float16> {
+  typedef uint16_t raw_t;
+  static __device__ __forceinline__ float to_f32(_Float16 v) { return (float)v; }
+  static __device__ __forceinline__ _Float16 from_f32(float v) { return (_Float16)v; }
+  static __device__ __forceinline__ raw_t load(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+    return __builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0);
+  }
+};
+template <> struct Elem<__bf16> {
+  typedef uint16_t raw_t;
+  static __device__ __forceinline__ float to_f32(__bf16 v) { return (float)v; }
+  static __device__ __forceinline__ __bf16 from_f32(float v) { return (__bf16)v; }
+  static __device__ __forceinline__ raw_t load(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+    return __builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0);
+  }
+};
+
+// All MFMAs of one slab for MBC x NB blocks; consecutive instructions touch
+// different accumulators.
+template <typename T, int MBC, int NB, int MB>
+__device__ __forceinline__ void mma_slab(const uint4 (&af)[MB], const uint4 (&bf)[NB], float4_t (&acc)[MB][NB]) {
+  if constexpr (sizeof(T) == 4) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+#pragma unroll
+      for (int i = 0; i < MBC; ++i) {
+        const uint32_t av = e == 0 ? af[i].x : e == 1 ? af[i].y : e == 2 ? af[i].z : af[i].w;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const uint32_t bv = e == 0 ? bf[j].x : e == 1 ? bf[j].y : e == 2 ? bf[j].z : bf[j].w;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(av), __uint_as_float(bv), acc[i][j], 0, 0, 0);
+        }
+      }
+    }
+  } else if constexpr (std::is_same<T, _Float16>::value) {
+#pragma unroll
+    for (int i = 0; i < MBC; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, af[i]),
+                                                           __builtin_bit_cast(half8_t, bf[j]), acc[i][j], 0, 0, 0);
+  } else {
+#pragma unroll
+    for (int i = 0; i < MBC; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, af[i]),
+                                                            __builtin_bit_cast(bf16x8_t, bf[j]), acc[i][j], 0, 0, 0);
+  }
+}
+
+template <typename T, int WM, int WN, int MB, int NB>
+__global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
+  typedef typename Elem<T>::raw_t raw_t;
+  constexpr int ES = (int)sizeof(T);
+  constexpr int EPI = 16 / ES;               // elements per 16-byte fragment
+  constexpr int KT = 4 * EPI;                // reduction elements per slab
+  constexpr int MT = WM * MB * 16;
+  constexpr int PT = WN * NB * 16;
+  constexpr int NIB = (PT * 4 + 255) / 256;  // B staging items (pixel, 16-byte quad) per thread
+  constexpr int A_ROWS = 256 / KT;           // A rows staged per pass (KT threads along k)
+  constexpr int NIA = (MT + A_ROWS - 1) / A_ROWS;
+
+  __shared__ __attribute__((aligned(16))) unsigned char sA[2][MT * ROW_BYTES];
+  __shared__ __attribute__((aligned(16))) unsigned char sB[2][PT * ROW_BYTES];
+  __shared__ __attribute__((aligned(16))) int tab_off[2][KT];
+  __shared__ __attribute__((aligned(16))) unsigned tab_bits[2][KT];
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = t >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int r = lane & 15, g = lane >> 4;
+
+  // Work-groups are handed to the 8 XCDs round-robin; give each XCD a contiguous
+  // run of tiles so the groups sharing an L2 share input pixels and weights.
+  int tile;
+  {
+    const int nb = a.tiles_m * a.tiles_p;
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int q = nb >> 3, rem = nb & 7;
+    tile = xcd * q + (xcd < rem ? xcd : rem) + local;
+  }
+  const int tile_m = tile % a.tiles_m;
+  const int tile_p = tile / a.tiles_m;
+  const int o0 = tile_m * MT;
+  const int p0 = tile_p * PT;
+  const int split = blockIdx.z;
+  const int kbeg = split * a.k_per_split;
+  const int kend = min(a.K, kbeg + a.k_per_split);
+  const int nslab = (kend - kbeg + KT - 1) / KT;
+
+  const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);
+  const __amdgpu_buffer_rsrc_t wr = make_rsrc(a.w, a.w_bytes);
+
+  // ---- per-thread staging state ----
+  int b_base[NIB];        // byte offset of the pixel's window origin (may be negative)
+  unsigned b_mask[NIB];   // taps inside the image: bit u (rows), bit 8+v (columns)
+  int b_lds[NIB];         // byte offset of the item's 16-byte slot in a B buffer, -1 = none
+  int b_tab[NIB];         // first table entry of the item's quad
+#pragma unroll
+  for (int j = 0; j < NIB; ++j) {
+    const int idx = t + 256 * j;
+    const int pi = idx % PT, q = idx / PT;
+    const bool item = idx < PT * 4;
+    unsigned pm = 0;
+    int base = 0;
+    const int p = p0 + pi;
+    if (item && p < a.P) {
+      const int n = p / a.HoWo;
+      const int rem = p - n * a.HoWo;
+      const int oy = rem / a.Wo;
+      const int ox = rem - oy * a.Wo;
+      const int iy0 = oy * a.stride - a.pad, ix0 = ox * a.stride - a.pad;
+      base = ((n * a.C * a.H + iy0) * a.W + ix0) * ES;
+      for (int u = 0; u < a.KH; ++u)
+        if ((unsigned)(iy0 + u) < (unsigned)a.H) pm |= 1u << u;
+      for (int v = 0; v < a.KW; ++v)
+        if ((unsigned)(ix0 + v) < (unsigned)a.W) pm |= 1u << (8 + v);
+    }
+    b_base[j] = base;
+    b_mask[j] = pm;
+    b_lds[j] = item ? pi * ROW_BYTES + q * 16 : -1;
+    b_tab[j] = item ? q * EPI : 0;
+  }
+  const int a_k = t % KT;
+  const int a_row0 = t / KT;
+  unsigned a_off[NIA];    // byte offset of (row, kbeg + a_k), kOutOfRange for rows past c_out
+#pragma unroll
+  for (int j = 0; j < NIA; ++j) {
+    const int m = a_row0 + j * A_ROWS;
+    const int o = o0 + m;
+    a_off[j] = (m < MT && o < a.O) ? (unsigned)(o * a.K + kbeg + a_k) * ES : kOutOfRange;
+  }
+
+  auto write_table = [&](int slab, int slot) {
+    if (t < KT) {
+      const int k = kbeg + slab * KT + t;
+      int off = 0;
+      unsigned bits = kOutOfRange;  // never satisfied by a pixel mask
+      if (k < kend) {
+        const unsigned c = fast_div((unsigned)k, a.magic_khw);
+        const unsigned rr = (unsigned)k - c * (unsigned)a.KHW;
+        const unsigned u = fast_div(rr, a.magic_kw);
+        const unsigned v = rr - u * (unsigned)a.KW;
+        off = (int)(c * (unsigned)a.HW + u * (unsigned)a.W + v) * ES;
+        bits = (1u << u) | (1u << (8 + v));
+      }
+      tab_off[slot][t] = off;
+      tab_bits[slot][t] = bits;
+    }
+  };
+
+  raw_t breg[NIB][EPI];
+  raw_t areg[NIA];
+
+  auto gload = [&](int slab, int slot) {
+    const int k0 = kbeg + slab * KT;
+    // offsets of elements that must read as zero get bit 31 set (arithmetic, not a
+    // select of two loads: the loads stay unconditional and issue back to back)
+    const unsigned kinval = (unsigned)(k0 + a_k >= kend) << 31;
+    const unsigned soff = (unsigned)(slab * KT * ES);
+#pragma unroll
+    for (int j = 0; j < NIA; ++j) areg[j] = Elem<T>::load(wr, a_off[j] | kinval, soff);
+#pragma unroll
+    for (int j = 0; j < NIB; ++j) {
+#pragma unroll
+      for (int e4 = 0; e4 < EPI; e4 += 4) {
+        const int4 offs = *(const int4*)&tab_off[slot][b_tab[j] + e4];
+        const uint4 bits = *(const uint4*)&tab_bits[slot][b_tab[j] + e4];
+        const unsigned m = b_mask[j];
+        breg[j][e4 + 0] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.x) | ((unsigned)((m & bits.x) != bits.x) << 31), 0);
+        breg[j][e4 + 1] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.y) | ((unsigned)((m & bits.y) != bits.y) << 31), 0);
+        breg[j][e4 + 2] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.z) | ((unsigned)((m & bits.z) != bits.z) << 31), 0);
+        breg[j][e4 + 3] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.w) | ((unsigned)((m & bits.w) != bits.w) << 31), 0);
+      }
+    }
+  };
+
+  auto lds_store = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < NIA; ++j) {
+      const int m = a_row0 + j * A_ROWS;
+      if (m < MT) *(raw_t*)&sA[buf][m * ROW_BYTES + a_k * ES] = areg[j];
+    }
+#pragma unroll
+    for (int j = 0; j < NIB; ++j) {
+      if (b_lds[j] >= 0) {
+        uint4 pk;
+        if constexpr (ES == 4) {
+          pk = make_uint4(breg[j][0], breg[j][1], breg[j][2], breg[j][3]);
+        } else {
+          pk = make_uint4((uint32_t)breg[j][0] | ((uint32_t)breg[j][1] << 16),
+                          (uint32_t)breg[j][2] | ((uint32_t)breg[j][3] << 16),
+                          (uint32_t)breg[j][4] | ((uint32_t)breg[j][5] << 16),
+                          (uint32_t)breg[j][6] | ((uint32_t)breg[j][7] << 16));
+        }
+        *(uint4*)&sB[buf][b_lds[j]] = pk;
+      }
+    }
+  };
+
+  // ---- accumulators ----
+  float4_t acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) acc[i][j] = (float4_t){0.f, 0.f, 0.f, 0.f};
+
+  // 16-row blocks of this wave that hold at least one real filter
+  const int m_wave = o0 + wm * MB * 16;
+  int mb_count = (a.O - m_wave + 15) / 16;
+  mb_count = mb_count < 0 ? 0 : (mb_count > MB ? MB : mb_count);
+
+  const int a_frag = (wm * MB * 16 + r) * ROW_BYTES + g * 16;
+  const int b_frag = (wn * NB * 16 + r) * ROW_BYTES + g * 16;
+
+  // ---- pipeline: the loop body is compiled for each possible block count ----
+  auto main_loop = [&](auto mbc_tag) {
+    constexpr int MBC = decltype(mbc_tag)::value;
+    if (nslab > 0) {
+      write_table(0, 0);
+      __syncthreads();
+      gload(0, 0);
+      if (nslab > 1) write_table(1, 1);
+      lds_store(0);
+      __syncthreads();
+    }
+    for (int s = 0; s < nslab; ++s) {
+      const int buf = s & 1;
+      // operands of this slab first (their LDS latency overlaps the address work below)
+      uint4 af[MB], bf[NB];
+#pragma unroll
+      for (int j = 0; j < NB; ++j) bf[j] = *(const uint4*)&sB[buf][b_frag + j * 16 * ROW_BYTES];
+#pragma unroll
+      for (int i = 0; i < MBC; ++i) af[i] = *(const uint4*)&sA[buf][a_frag + i * 16 * ROW_BYTES];
+      if (s + 1 < nslab) gload(s + 1, (s + 1) & 1);
+      if (s + 2 < nslab) write_table(s + 2, s & 1);
+      mma_slab<T, MBC, NB, MB>(af, bf, acc);
+      if (s + 1 < nslab) lds_store(buf ^ 1);
+      __syncthreads();
+    }
+  };
+  switch (mb_count) {
+#define CPRUNE_MBC_CASE(V) \
+  case V: if constexpr (MB >= V) main_loop(std::integral_constant<int, V>{}); break;
+    CPRUNE_MBC_CASE(0) CPRUNE_MBC_CASE(1) CPRUNE_MBC_CASE(2) CPRUNE_MBC_CASE(3) CPRUNE_MBC_CASE(4)
+    CPRUNE_MBC_CASE(5) CPRUNE_MBC_CASE(6) CPRUNE_MBC_CASE(7) CPRUNE_MBC_CASE(8)
+#undef CPRUNE_MBC_CASE
+    default: break;
+  }
+
+  // ---- epilogue ----
+  // lane holds rows 4g..4g+3 (filters) of column r (pixel) of each block
+  T* __restrict__ yg = (T*)a.y;
+  const T* __restrict__ rg = (const T*)a.res;
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int p = p0 + wn * NB * 16 + j * 16 + r;
+    if (p >= a.P) continue;
+    if (a.split_k > 1) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+        if (i >= mb_count) continue;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int o = m_wave + i * 16 + 4 * g + v;
+          if (o < a.O) a.partial[((size_t)split * a.O + o) * a.P + p] = acc[i][j][v];
+        }
+      }
+    } else {
+      const int n = p / a.HoWo;
+      const int rem = p - n * a.HoWo;
+      const size_t pix = (size_t)n * a.O * a.HoWo + rem;
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+        if (i >= mb_count) continue;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int o = m_wave + i * 16 + 4 * g + v;
+          if (o < a.O) {
+            float val = acc[i][j][v] + (a.bias ? a.bias[o] : 0.0f);
+            const size_t off = pix + (size_t)o * a.HoWo;
+            if (rg) val += Elem<T>::to_f32(rg[off]);
+            yg[off] = Elem<T>::from_f32(apply_act(val, a.act));
+          }
+        }
+      }
+    }
+  }
+}
+
+// Tile table shared by the launchers: wm, wn, mb, nb.
+#define CPRUNE_TILE_LIST(X) \
+  X(0, 1, 4, 4, 4)  /* 64 x 256  */ \
+  X(1, 1, 4, 8, 2)  /* 128 x 128 */ \
+  X(2, 2, 2, 4, 4)  /* 128 x 128 */ \
+  X(3, 1, 4, 2, 4)  /* 32 x 256  */ \
+  X(4, 1, 4, 4, 2)  /* 64 x 128  */ \
+  X(5, 1, 4, 1, 4)  /* 16 x 256  */ \
+  X(6, 1, 4, 3, 4)  /* 48 x 256  */ \
+  X(7, 1, 4, 2, 2)  /* 32 x 128  */ \
+  X(8, 1, 4, 1, 2)  /* 16 x 128  */ \
+  X(9, 1, 4, 4, 1)  /* 64 x 64   */ \
+  X(10, 1, 4, 2, 1) /* 32 x 64   */ \
+  X(11, 1, 4, 8, 1) /* 128 x 64  */ \
+  X(12, 4, 1, 2, 7) /* 128 x 112 */ \
+  X(13, 2, 2, 4, 6) /* 128 x 192 */ \
+  X(14, 1, 4, 6, 3) /* 96 x 192  */ \
+  X(15, 1, 4, 1, 1) /* 16 x 64   */ \
+  X(16, 2, 2, 8, 4) /* 256 x 128 */
+
+constexpr int kNumTiles = 17;
+
+template <typename T>
+inline void launch_tile(int tile, dim3 grid, hipStream_t s, const ConvArgs& a) {
+#define CPRUNE_TILE_CASE(ID, WM_, WN_, MB_, NB_)                                               \
+  case ID:                                                                                     \
+    hipLaunchKernelGGL((conv_igemm_kernel<T, WM_, WN_, MB_, NB_>), grid, dim3(256), 0, s, a);  \
+    break;
+  switch (tile) { CPRUNE_TILE_LIST(CPRUNE_TILE_CASE) }
+#undef CPRUNE_TILE_CASE
+}
+
+// Sums the split-K partials in slice order (deterministic), then the epilogue.
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(ConvArgs a) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t total = (size_t)a.O * a.P;
+  if (i >= total) return;
+  const int o = (int)(i / a.P);
+  const int p = (int)(i - (size_t)o * a.P);
+  float s = 0.0f;
+  for (int k = 0; k < a.split_k; ++k) s += a.partial[(size_t)k * total + i];
+  s += a.bias ? a.bias[o] : 0.0f;
+  const int n = p / a.HoWo;
+  const int rem = p - n * a.HoWo;
+  const size_t off = ((size_t)n * a.O + o) * a.HoWo + rem;
+  if (a.res) s += Elem<T>::to_f32(((const T*)a.res)[off]);
+  ((T*)a.y)[off] = Elem<T>::from_f32(apply_act(s, a.act));
+}
+
+// Per-dtype launch entry points, one translation unit each.
+void launch_conv_f32(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, dim3 reduce_grid);
+void launch_conv_f16(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, dim3 reduce_grid);
+void launch_conv_bf16(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, dim3 reduce_grid);
+
+}  // namespace cprune
