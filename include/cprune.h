@@ -116,10 +116,14 @@ typedef struct {
 } cprune_conv_desc;
 
 /* Kernel variants of the dense path: a work-group tile (output channels x
- * output pixels) and a split of the reduction.  Ids are 0..n-1 and the same for
- * every shape; a variant that cannot run a given shape is CPRUNE_ERR_UNSUPPORTED. */
+ * output pixels) and a scheduling mode.  sched 0: one output tile per work-group.
+ * sched n > 0: the (tile, reduction slab) work is laid out in one line and cut
+ * into equal runs for n * 256 work-groups; tiles cut between runs go through the
+ * caller's scratch and are summed in run order (deterministic).  Ids are 0..n-1
+ * and the same for every shape; a variant that cannot run a given shape is
+ * CPRUNE_ERR_UNSUPPORTED. */
 int cprune_num_tile_variants(void);
-int cprune_tile_variant_info(int variant, int* tile_m, int* tile_p, int* split_k); /* host out */
+int cprune_tile_variant_info(int variant, int* tile_m, int* tile_p, int* sched); /* host out */
 
 /* Scratch needed by `variant` (-1 = the largest any variant needs for desc). */
 size_t cprune_conv_workspace_bytes(const cprune_conv_desc* desc, int variant);

@@ -53,32 +53,26 @@ void remember_variant(const cprune_conv_desc& d, int v) {
   g_cache[key_of(d)] = v;
 }
 
-// Untimed fallback: a coarse cost model (rounds of work-groups over the chip
-// times the MFMA blocks one work-group issues, plus fixed per-group and
-// per-slice overheads), used only for shapes that were never timed.
+// Untimed fallback: the tile whose wavefronts reuse their LDS operands most (blocks
+// per operand fetched), discounted by the pixel columns a ragged last tile wastes;
+// work cut into equal runs for 512 resident work-groups, which needs no knowledge
+// of how the tile count divides the chip.  Used only for shapes never timed.
 int heuristic_variant(const cprune_conv_desc& d) {
   const long ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
   const long P = (long)d.n * ho * wo, O = d.c_out;
-  const long K = (long)d.c_in * d.kh * d.kw;
-  const long kt = d.dtype == CPRUNE_F32 ? 16 : 32;
-  const long slabs = (K + kt - 1) / kt;
-  double best = 1e300;
+  double best = -1.0;
   int best_v = 0;
   for (int v = 0; v < num_variants(); ++v) {
-    if (!variant_supports(d, v)) continue;
     const TileVariant& tv = variant(v);
+    if (tv.sched != 2 || !variant_supports(d, v)) continue;
     const long mt = tv.tile_m(), pt = tv.tile_p();
     const long tm = (O + mt - 1) / mt, tp = (P + pt - 1) / pt;
-    const long groups = tm * tp * tv.split_k;
-    const double rows16 = std::ceil((double)O / tm / 16.0);
-    const double per_wave_rows = tv.wm > 1 ? std::ceil(rows16 / tv.wm) : rows16;
-    const double blocks = per_wave_rows * tv.nb;           // MFMA blocks per wave per slab
-    const double stage = (double)(mt + pt) / 64.0;          // staging cost per slab
-    const double per_group = (double)((slabs + tv.split_k - 1) / tv.split_k) * (blocks + 0.5 * stage) + 60.0;
-    const double rounds = std::ceil((double)groups / 512.0);
-    double cost = rounds * per_group;
-    if (tv.split_k > 1) cost += 80.0 + (double)O * P * tv.split_k / 4096.0;
-    if (cost < best) { best = cost; best_v = v; }
+    double rows16 = std::ceil((double)O / tm / 16.0 / tv.wm);
+    if (rows16 > tv.mb) rows16 = tv.mb;
+    const double reuse = rows16 * tv.nb / (rows16 + tv.nb);
+    const double fill = (double)P / (double)(tp * pt);
+    const double score = reuse * fill;
+    if (score > best) { best = score; best_v = v; }
   }
   return best_v;
 }
@@ -168,12 +162,12 @@ extern "C" int cprune_last_hip_error(void) { return (int)g_last_hip_error; }
 
 extern "C" int cprune_num_tile_variants(void) { return num_variants(); }
 
-extern "C" int cprune_tile_variant_info(int v, int* tile_m, int* tile_p, int* split_k) {
+extern "C" int cprune_tile_variant_info(int v, int* tile_m, int* tile_p, int* sched) {
   if (v < 0 || v >= num_variants()) return CPRUNE_ERR_INVALID_ARG;
   const TileVariant& tv = variant(v);
   if (tile_m) *tile_m = tv.tile_m();
   if (tile_p) *tile_p = tv.tile_p();
-  if (split_k) *split_k = tv.split_k;
+  if (sched) *sched = tv.sched;
   return CPRUNE_OK;
 }
 
@@ -260,16 +254,16 @@ extern "C" int cprune_fc(const void* x, const void* w, const float* bias, int n,
   cprune_conv_desc d = fc_desc(n, f, c_out, act, dtype);
   int rc = validate_conv_desc(&d);
   if (rc != CPRUNE_OK) return rc;
-  // choose among the variants the caller's scratch can run
+  // the remembered or heuristic variant, or its one-tile-per-group twin when the
+  // caller's scratch is too small for cut tiles
   int v = cached_or_heuristic_variant(d, nullptr);
   if (conv_ws_bytes(d, v) > (ws ? ws_bytes : 0)) {
-    cprune_conv_desc tmp = d;
-    int best = -1;
+    int twin = -1;
     for (int i = 0; i < num_variants(); ++i)
-      if (variant_supports(tmp, i) && variant(i).split_k == 1 && variant(i).tile_m() == variant(v).tile_m() &&
-          variant(i).tile_p() == variant(v).tile_p()) { best = i; break; }
-    if (best < 0) return CPRUNE_ERR_WORKSPACE;
-    v = best;
+      if (variant_supports(d, i) && variant(i).sched == 0 && variant(i).tile_m() == variant(v).tile_m() &&
+          variant(i).tile_p() == variant(v).tile_p()) { twin = i; break; }
+    if (twin < 0) return CPRUNE_ERR_WORKSPACE;
+    v = twin;
   }
   return launch_conv_dense(d, x, w, bias, nullptr, y, v, ws, (hipStream_t)stream);
 }

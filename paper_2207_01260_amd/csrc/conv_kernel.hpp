@@ -20,6 +20,15 @@
 // (lane group g holds columns 4g..4g+3 of a 16-byte quad layout); A and B use
 // the same permutation, which leaves the sum unchanged.
 //
+// Work is cut by slab iterations, not by tiles: the (tile, slab) pairs are laid
+// out in one line, tile-major, and every work-group takes a contiguous run of
+// units_per_wg of them.  With units_per_wg = slabs this is one tile per
+// work-group; with fewer work-groups than tiles x slabs / units_per_wg the runs
+// cut through tiles, so all compute units finish together whatever the channel
+// and pixel counts are.  A tile that one work-group covers completely goes
+// straight to the epilogue; the pieces of a cut tile are written as raw
+// accumulators and summed, in run order, by conv_fixup_kernel (deterministic).
+//
 // The im2col gather is table-driven: for each k of a slab a small LDS table
 // holds the input byte offset (c*H*W + u*W + v) and the tap bits (u, v); each
 // staging thread keeps, per pixel it serves, a base offset and the mask of the
@@ -43,14 +52,16 @@ struct ConvArgs {
   const float* bias;
   const void* res;
   void* y;
-  float* partial;  // [split_k][O][P] when split_k > 1
+  float* partial;  // [2 * work-groups][MT * PT] accumulator tiles of split output tiles
   int N, C, H, W, O, KH, KW, stride, pad, Ho, Wo;
   int K, P, HoWo, HW, KHW;
   unsigned magic_khw, magic_kw;  // ceil(2^32 / d), 0 when d == 1
   unsigned x_bytes, w_bytes;     // sizes of the x and w tensors (< 2^31)
   int act;
   int tiles_m, tiles_p;
-  int split_k, k_per_split;
+  int slabs;          // reduction slabs per output tile
+  int units;          // tiles * slabs: the work, in slab iterations
+  int units_per_wg;   // contiguous run of units each work-group takes
 };
 
 constexpr unsigned kOutOfRange = 0x80000000u;  // beyond any buffer this kernel accepts
@@ -130,6 +141,51 @@ __device__ __forceinline__ void mma_slab(const uint4 (&af)[MB], const uint4 (&bf
   }
 }
 
+template <int WM, int WN, int MB, int NB>
+struct TileGeom {
+  static constexpr int MT = WM * MB * 16;
+  static constexpr int PT = WN * NB * 16;
+};
+
+// Where a work-group's run of units starts and ends.
+__device__ __forceinline__ void unit_range(const ConvArgs& a, int g, int& ub, int& ue) {
+  const long b = (long)g * a.units_per_wg;
+  ub = (int)(b < a.units ? b : a.units);
+  const long e = b + a.units_per_wg;
+  ue = (int)(e < a.units ? e : a.units);
+}
+
+// bias + residual + activation + store of one wave's accumulators.
+template <typename T, int WM, int WN, int MB, int NB>
+__device__ __forceinline__ void conv_epilogue(const ConvArgs& a, const float4_t (&acc)[MB][NB], int tile_m,
+                                              int tile_p, int wm, int wn, int r, int g4) {
+  constexpr int MT = WM * MB * 16, PT = WN * NB * 16;
+  T* __restrict__ yg = (T*)a.y;
+  const T* __restrict__ rg = (const T*)a.res;
+  const int m_wave = tile_m * MT + wm * MB * 16;
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int p = tile_p * PT + wn * NB * 16 + j * 16 + r;
+    if (p >= a.P) continue;
+    const int n = p / a.HoWo;
+    const int rem = p - n * a.HoWo;
+    const size_t pix = (size_t)n * a.O * a.HoWo + rem;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int o = m_wave + i * 16 + 4 * g4 + v;
+        if (o < a.O) {
+          float val = acc[i][j][v] + (a.bias ? a.bias[o] : 0.0f);
+          const size_t off = pix + (size_t)o * a.HoWo;
+          if (rg) val += Elem<T>::to_f32(rg[off]);
+          yg[off] = Elem<T>::from_f32(apply_act(val, a.act));
+        }
+      }
+    }
+  }
+}
+
 template <typename T, int WM, int WN, int MB, int NB>
 __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
   typedef typename Elem<T>::raw_t raw_t;
@@ -151,279 +207,278 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
   const int lane = t & 63;
   const int wave = t >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const int r = lane & 15, g = lane >> 4;
+  const int r = lane & 15, g4 = lane >> 4;
 
   // Work-groups are handed to the 8 XCDs round-robin; give each XCD a contiguous
-  // run of tiles so the groups sharing an L2 share input pixels and weights.
-  int tile;
+  // stretch of the work so the groups sharing an L2 share input pixels and weights.
+  int g;
   {
-    const int nb = a.tiles_m * a.tiles_p;
+    const int G = gridDim.x;
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-    const int q = nb >> 3, rem = nb & 7;
-    tile = xcd * q + (xcd < rem ? xcd : rem) + local;
+    const int q = G >> 3, rem = G & 7;
+    g = xcd * q + (xcd < rem ? xcd : rem) + local;
   }
-  const int tile_m = tile % a.tiles_m;
-  const int tile_p = tile / a.tiles_m;
-  const int o0 = tile_m * MT;
-  const int p0 = tile_p * PT;
-  const int split = blockIdx.z;
-  const int kbeg = split * a.k_per_split;
-  const int kend = min(a.K, kbeg + a.k_per_split);
-  const int nslab = (kend - kbeg + KT - 1) / KT;
+  int ub, ue;
+  unit_range(a, g, ub, ue);
 
   const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);
   const __amdgpu_buffer_rsrc_t wr = make_rsrc(a.w, a.w_bytes);
 
-  // ---- per-thread staging state ----
-  int b_base[NIB];        // byte offset of the pixel's window origin (may be negative)
-  unsigned b_mask[NIB];   // taps inside the image: bit u (rows), bit 8+v (columns)
-  int b_lds[NIB];         // byte offset of the item's 16-byte slot in a B buffer, -1 = none
-  int b_tab[NIB];         // first table entry of the item's quad
-#pragma unroll
-  for (int j = 0; j < NIB; ++j) {
-    const int idx = t + 256 * j;
-    const int pi = idx % PT, q = idx / PT;
-    const bool item = idx < PT * 4;
-    unsigned pm = 0;
-    int base = 0;
-    const int p = p0 + pi;
-    if (item && p < a.P) {
-      const int n = p / a.HoWo;
-      const int rem = p - n * a.HoWo;
-      const int oy = rem / a.Wo;
-      const int ox = rem - oy * a.Wo;
-      const int iy0 = oy * a.stride - a.pad, ix0 = ox * a.stride - a.pad;
-      base = ((n * a.C * a.H + iy0) * a.W + ix0) * ES;
-      for (int u = 0; u < a.KH; ++u)
-        if ((unsigned)(iy0 + u) < (unsigned)a.H) pm |= 1u << u;
-      for (int v = 0; v < a.KW; ++v)
-        if ((unsigned)(ix0 + v) < (unsigned)a.W) pm |= 1u << (8 + v);
-    }
-    b_base[j] = base;
-    b_mask[j] = pm;
-    b_lds[j] = item ? pi * ROW_BYTES + q * 16 : -1;
-    b_tab[j] = item ? q * EPI : 0;
-  }
   const int a_k = t % KT;
   const int a_row0 = t / KT;
-  unsigned a_off[NIA];    // byte offset of (row, kbeg + a_k), kOutOfRange for rows past c_out
-#pragma unroll
-  for (int j = 0; j < NIA; ++j) {
-    const int m = a_row0 + j * A_ROWS;
-    const int o = o0 + m;
-    a_off[j] = (m < MT && o < a.O) ? (unsigned)(o * a.K + kbeg + a_k) * ES : kOutOfRange;
-  }
+  const int a_frag = (wm * MB * 16 + r) * ROW_BYTES + g4 * 16;
+  const int b_frag = (wn * NB * 16 + r) * ROW_BYTES + g4 * 16;
 
-  auto write_table = [&](int slab, int slot) {
-    if (t < KT) {
-      const int k = kbeg + slab * KT + t;
-      int off = 0;
-      unsigned bits = kOutOfRange;  // never satisfied by a pixel mask
-      if (k < kend) {
-        const unsigned c = fast_div((unsigned)k, a.magic_khw);
-        const unsigned rr = (unsigned)k - c * (unsigned)a.KHW;
-        const unsigned u = fast_div(rr, a.magic_kw);
-        const unsigned v = rr - u * (unsigned)a.KW;
-        off = (int)(c * (unsigned)a.HW + u * (unsigned)a.W + v) * ES;
-        bits = (1u << u) | (1u << (8 + v));
-      }
-      tab_off[slot][t] = off;
-      tab_bits[slot][t] = bits;
-    }
-  };
+  int seg = 0;
+  for (int u = ub; u < ue; ++seg) {
+    const int tile = u / a.slabs;
+    const int s0 = u - tile * a.slabs;
+    const int s1 = min(a.slabs, s0 + (ue - u));
+    u += s1 - s0;
+    const int nslab = s1 - s0;
+    const int tile_m = tile % a.tiles_m;
+    const int tile_p = tile / a.tiles_m;
+    const int o0 = tile_m * MT;
+    const int p0 = tile_p * PT;
+    const int kbeg = s0 * KT;
+    const int kend = min(a.K, s1 * KT);
 
-  raw_t breg[NIB][EPI];
-  raw_t areg[NIA];
-
-  auto gload = [&](int slab, int slot) {
-    const int k0 = kbeg + slab * KT;
-    // offsets of elements that must read as zero get bit 31 set (arithmetic, not a
-    // select of two loads: the loads stay unconditional and issue back to back)
-    const unsigned kinval = (unsigned)(k0 + a_k >= kend) << 31;
-    const unsigned soff = (unsigned)(slab * KT * ES);
-#pragma unroll
-    for (int j = 0; j < NIA; ++j) areg[j] = Elem<T>::load(wr, a_off[j] | kinval, soff);
+    // ---- per-thread staging state for this tile ----
+    int b_base[NIB];        // byte offset of the pixel's window origin (may be negative)
+    unsigned b_mask[NIB];   // taps inside the image: bit u (rows), bit 8+v (columns)
+    int b_lds[NIB];         // byte offset of the item's 16-byte slot in a B buffer, -1 = none
+    int b_tab[NIB];         // first table entry of the item's quad
 #pragma unroll
     for (int j = 0; j < NIB; ++j) {
-#pragma unroll
-      for (int e4 = 0; e4 < EPI; e4 += 4) {
-        const int4 offs = *(const int4*)&tab_off[slot][b_tab[j] + e4];
-        const uint4 bits = *(const uint4*)&tab_bits[slot][b_tab[j] + e4];
-        const unsigned m = b_mask[j];
-        breg[j][e4 + 0] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.x) | ((unsigned)((m & bits.x) != bits.x) << 31), 0);
-        breg[j][e4 + 1] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.y) | ((unsigned)((m & bits.y) != bits.y) << 31), 0);
-        breg[j][e4 + 2] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.z) | ((unsigned)((m & bits.z) != bits.z) << 31), 0);
-        breg[j][e4 + 3] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.w) | ((unsigned)((m & bits.w) != bits.w) << 31), 0);
+      const int idx = t + 256 * j;
+      const int pi = idx % PT, q = idx / PT;
+      const bool item = idx < PT * 4;
+      unsigned pm = 0;
+      int base = 0;
+      const int p = p0 + pi;
+      if (item && p < a.P) {
+        const int n = p / a.HoWo;
+        const int rem = p - n * a.HoWo;
+        const int oy = rem / a.Wo;
+        const int ox = rem - oy * a.Wo;
+        const int iy0 = oy * a.stride - a.pad, ix0 = ox * a.stride - a.pad;
+        base = ((n * a.C * a.H + iy0) * a.W + ix0) * ES;
+        for (int uu = 0; uu < a.KH; ++uu)
+          if ((unsigned)(iy0 + uu) < (unsigned)a.H) pm |= 1u << uu;
+        for (int v = 0; v < a.KW; ++v)
+          if ((unsigned)(ix0 + v) < (unsigned)a.W) pm |= 1u << (8 + v);
       }
+      b_base[j] = base;
+      b_mask[j] = pm;
+      b_lds[j] = item ? pi * ROW_BYTES + q * 16 : -1;
+      b_tab[j] = item ? q * EPI : 0;
     }
-  };
-
-  auto lds_store = [&](int buf) {
+    unsigned a_off[NIA];    // byte offset of (row, kbeg + a_k), kOutOfRange for rows past c_out
 #pragma unroll
     for (int j = 0; j < NIA; ++j) {
       const int m = a_row0 + j * A_ROWS;
-      if (m < MT) *(raw_t*)&sA[buf][m * ROW_BYTES + a_k * ES] = areg[j];
+      const int o = o0 + m;
+      a_off[j] = (m < MT && o < a.O) ? (unsigned)(o * a.K + kbeg + a_k) * ES : kOutOfRange;
     }
-#pragma unroll
-    for (int j = 0; j < NIB; ++j) {
-      if (b_lds[j] >= 0) {
-        uint4 pk;
-        if constexpr (ES == 4) {
-          pk = make_uint4(breg[j][0], breg[j][1], breg[j][2], breg[j][3]);
-        } else {
-          pk = make_uint4((uint32_t)breg[j][0] | ((uint32_t)breg[j][1] << 16),
-                          (uint32_t)breg[j][2] | ((uint32_t)breg[j][3] << 16),
-                          (uint32_t)breg[j][4] | ((uint32_t)breg[j][5] << 16),
-                          (uint32_t)breg[j][6] | ((uint32_t)breg[j][7] << 16));
+
+    auto write_table = [&](int slab, int slot) {
+      if (t < KT) {
+        const int k = kbeg + slab * KT + t;
+        int off = 0;
+        unsigned bits = kOutOfRange;  // never satisfied by a pixel mask
+        if (k < kend) {
+          const unsigned c = fast_div((unsigned)k, a.magic_khw);
+          const unsigned rr = (unsigned)k - c * (unsigned)a.KHW;
+          const unsigned uu = fast_div(rr, a.magic_kw);
+          const unsigned v = rr - uu * (unsigned)a.KW;
+          off = (int)(c * (unsigned)a.HW + uu * (unsigned)a.W + v) * ES;
+          bits = (1u << uu) | (1u << (8 + v));
         }
-        *(uint4*)&sB[buf][b_lds[j]] = pk;
+        tab_off[slot][t] = off;
+        tab_bits[slot][t] = bits;
       }
-    }
-  };
+    };
 
-  // ---- accumulators ----
-  float4_t acc[MB][NB];
+    raw_t breg[NIB][EPI];
+    raw_t areg[NIA];
+
+    auto gload = [&](int slab, int slot) {
+      const int k0 = kbeg + slab * KT;
+      // offsets of elements that must read as zero get bit 31 set (arithmetic, not a
+      // select of two loads: the loads stay unconditional and issue back to back)
+      const unsigned kinval = (unsigned)(k0 + a_k >= kend) << 31;
+      const unsigned soff = (unsigned)(slab * KT * ES);
 #pragma unroll
-  for (int i = 0; i < MB; ++i)
+      for (int j = 0; j < NIA; ++j) areg[j] = Elem<T>::load(wr, a_off[j] | kinval, soff);
 #pragma unroll
-    for (int j = 0; j < NB; ++j) acc[i][j] = (float4_t){0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < NIB; ++j) {
+#pragma unroll
+        for (int e4 = 0; e4 < EPI; e4 += 4) {
+          const int4 offs = *(const int4*)&tab_off[slot][b_tab[j] + e4];
+          const uint4 bits = *(const uint4*)&tab_bits[slot][b_tab[j] + e4];
+          const unsigned m = b_mask[j];
+          breg[j][e4 + 0] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.x) | ((unsigned)((m & bits.x) != bits.x) << 31), 0);
+          breg[j][e4 + 1] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.y) | ((unsigned)((m & bits.y) != bits.y) << 31), 0);
+          breg[j][e4 + 2] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.z) | ((unsigned)((m & bits.z) != bits.z) << 31), 0);
+          breg[j][e4 + 3] = Elem<T>::load(xr, (unsigned)(b_base[j] + offs.w) | ((unsigned)((m & bits.w) != bits.w) << 31), 0);
+        }
+      }
+    };
 
-  // 16-row blocks of this wave that hold at least one real filter
-  const int m_wave = o0 + wm * MB * 16;
-  int mb_count = (a.O - m_wave + 15) / 16;
-  mb_count = mb_count < 0 ? 0 : (mb_count > MB ? MB : mb_count);
+    auto lds_store = [&](int buf) {
+#pragma unroll
+      for (int j = 0; j < NIA; ++j) {
+        const int m = a_row0 + j * A_ROWS;
+        if (m < MT) *(raw_t*)&sA[buf][m * ROW_BYTES + a_k * ES] = areg[j];
+      }
+#pragma unroll
+      for (int j = 0; j < NIB; ++j) {
+        if (b_lds[j] >= 0) {
+          uint4 pk;
+          if constexpr (ES == 4) {
+            pk = make_uint4(breg[j][0], breg[j][1], breg[j][2], breg[j][3]);
+          } else {
+            pk = make_uint4((uint32_t)breg[j][0] | ((uint32_t)breg[j][1] << 16),
+                            (uint32_t)breg[j][2] | ((uint32_t)breg[j][3] << 16),
+                            (uint32_t)breg[j][4] | ((uint32_t)breg[j][5] << 16),
+                            (uint32_t)breg[j][6] | ((uint32_t)breg[j][7] << 16));
+          }
+          *(uint4*)&sB[buf][b_lds[j]] = pk;
+        }
+      }
+    };
 
-  const int a_frag = (wm * MB * 16 + r) * ROW_BYTES + g * 16;
-  const int b_frag = (wn * NB * 16 + r) * ROW_BYTES + g * 16;
+    // ---- accumulators ----
+    float4_t acc[MB][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) acc[i][j] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
-  // ---- pipeline: the loop body is compiled for each possible block count ----
-  auto main_loop = [&](auto mbc_tag) {
-    constexpr int MBC = decltype(mbc_tag)::value;
-    if (nslab > 0) {
+    // 16-row blocks of this wave that hold at least one real filter
+    int mb_count = (a.O - (o0 + wm * MB * 16) + 15) / 16;
+    mb_count = mb_count < 0 ? 0 : (mb_count > MB ? MB : mb_count);
+
+    // ---- pipeline: the loop body is compiled for each possible block count ----
+    auto main_loop = [&](auto mbc_tag) {
+      constexpr int MBC = decltype(mbc_tag)::value;
       write_table(0, 0);
       __syncthreads();
       gload(0, 0);
       if (nslab > 1) write_table(1, 1);
       lds_store(0);
       __syncthreads();
-    }
-    for (int s = 0; s < nslab; ++s) {
-      const int buf = s & 1;
-      // operands of this slab first (their LDS latency overlaps the address work below)
-      uint4 af[MB], bf[NB];
+      for (int s = 0; s < nslab; ++s) {
+        const int buf = s & 1;
+        // operands of this slab first (their LDS latency overlaps the address work below)
+        uint4 af[MB], bf[NB];
 #pragma unroll
-      for (int j = 0; j < NB; ++j) bf[j] = *(const uint4*)&sB[buf][b_frag + j * 16 * ROW_BYTES];
+        for (int j = 0; j < NB; ++j) bf[j] = *(const uint4*)&sB[buf][b_frag + j * 16 * ROW_BYTES];
 #pragma unroll
-      for (int i = 0; i < MBC; ++i) af[i] = *(const uint4*)&sA[buf][a_frag + i * 16 * ROW_BYTES];
-      if (s + 1 < nslab) gload(s + 1, (s + 1) & 1);
-      if (s + 2 < nslab) write_table(s + 2, s & 1);
-      mma_slab<T, MBC, NB, MB>(af, bf, acc);
-      if (s + 1 < nslab) lds_store(buf ^ 1);
-      __syncthreads();
-    }
-  };
-  switch (mb_count) {
+        for (int i = 0; i < MBC; ++i) af[i] = *(const uint4*)&sA[buf][a_frag + i * 16 * ROW_BYTES];
+        if (s + 1 < nslab) gload(s + 1, (s + 1) & 1);
+        if (s + 2 < nslab) write_table(s + 2, s & 1);
+        mma_slab<T, MBC, NB, MB>(af, bf, acc);
+        if (s + 1 < nslab) lds_store(buf ^ 1);
+        __syncthreads();
+      }
+    };
+    switch (mb_count) {
 #define CPRUNE_MBC_CASE(V) \
   case V: if constexpr (MB >= V) main_loop(std::integral_constant<int, V>{}); break;
-    CPRUNE_MBC_CASE(0) CPRUNE_MBC_CASE(1) CPRUNE_MBC_CASE(2) CPRUNE_MBC_CASE(3) CPRUNE_MBC_CASE(4)
-    CPRUNE_MBC_CASE(5) CPRUNE_MBC_CASE(6) CPRUNE_MBC_CASE(7) CPRUNE_MBC_CASE(8)
+      CPRUNE_MBC_CASE(0) CPRUNE_MBC_CASE(1) CPRUNE_MBC_CASE(2) CPRUNE_MBC_CASE(3) CPRUNE_MBC_CASE(4)
+      CPRUNE_MBC_CASE(5) CPRUNE_MBC_CASE(6) CPRUNE_MBC_CASE(7) CPRUNE_MBC_CASE(8)
 #undef CPRUNE_MBC_CASE
-    default: break;
-  }
+      default: break;
+    }
 
-  // ---- epilogue ----
-  // lane holds rows 4g..4g+3 (filters) of column r (pixel) of each block
-  T* __restrict__ yg = (T*)a.y;
-  const T* __restrict__ rg = (const T*)a.res;
-#pragma unroll
-  for (int j = 0; j < NB; ++j) {
-    const int p = p0 + wn * NB * 16 + j * 16 + r;
-    if (p >= a.P) continue;
-    if (a.split_k > 1) {
-#pragma unroll
-      for (int i = 0; i < MB; ++i) {
-        if (i >= mb_count) continue;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int o = m_wave + i * 16 + 4 * g + v;
-          if (o < a.O) a.partial[((size_t)split * a.O + o) * a.P + p] = acc[i][j][v];
-        }
-      }
+    // ---- epilogue: whole tile -> output; piece of a tile -> raw accumulators ----
+    if (s0 == 0 && s1 == a.slabs) {
+      conv_epilogue<T, WM, WN, MB, NB>(a, acc, tile_m, tile_p, wm, wn, r, g4);
     } else {
-      const int n = p / a.HoWo;
-      const int rem = p - n * a.HoWo;
-      const size_t pix = (size_t)n * a.O * a.HoWo + rem;
+      // lane holds rows 4*g4..4*g4+3 of column r of each block; stored in that order
+      float4_t* dst = (float4_t*)(a.partial + (size_t)(2 * g + (seg ? 1 : 0)) * (MT * PT)) + (size_t)wave * (MB * NB * 64) + lane;
 #pragma unroll
-      for (int i = 0; i < MB; ++i) {
-        if (i >= mb_count) continue;
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int o = m_wave + i * 16 + 4 * g + v;
-          if (o < a.O) {
-            float val = acc[i][j][v] + (a.bias ? a.bias[o] : 0.0f);
-            const size_t off = pix + (size_t)o * a.HoWo;
-            if (rg) val += Elem<T>::to_f32(rg[off]);
-            yg[off] = Elem<T>::from_f32(apply_act(val, a.act));
-          }
-        }
-      }
+        for (int j = 0; j < NB; ++j) dst[(i * NB + j) * 64] = acc[i][j];
     }
   }
 }
 
-// Tile table shared by the launchers: wm, wn, mb, nb.
+// Sums the pieces of every output tile that was cut between work-groups, in the
+// order of the runs, and applies the epilogue.  One work-group per run.  A run
+// completes at most one cut tile: the one it starts in the middle of, if the
+// run reaches that tile's last slab.  (Tiles a run starts at slab 0 are either
+// whole, or completed by a later run.)
+template <typename T, int WM, int WN, int MB, int NB>
+__global__ __launch_bounds__(256) void conv_fixup_kernel(ConvArgs a) {
+  constexpr int MT = WM * MB * 16, PT = WN * NB * 16;
+  const int j = blockIdx.x;
+  int ub, ue;
+  unit_range(a, j, ub, ue);
+  if (ub >= ue) return;
+  const int tile = ub / a.slabs;
+  const long first = (long)tile * a.slabs;
+  if (ub == first || ue < first + a.slabs) return;
+  const int g_lo = (int)(first / a.units_per_wg);
+  const int g_hi = j;
+
+  const int t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  float4_t acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int jj = 0; jj < NB; ++jj) acc[i][jj] = (float4_t){0.f, 0.f, 0.f, 0.f};
+  for (int g = g_lo; g <= g_hi; ++g) {
+    int gb, ge;
+    unit_range(a, g, gb, ge);
+    const int slot = 2 * g + ((gb / a.slabs == tile) ? 0 : 1);
+    const float4_t* src = (const float4_t*)(a.partial + (size_t)slot * (MT * PT)) + (size_t)wave * (MB * NB * 64) + lane;
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int jj = 0; jj < NB; ++jj) acc[i][jj] += src[(i * NB + jj) * 64];
+  }
+  conv_epilogue<T, WM, WN, MB, NB>(a, acc, tile % a.tiles_m, tile / a.tiles_m, wm, wn, lane & 15, lane >> 4);
+}
+
+// Tile table shared by the launchers: id, wm, wn, mb, nb.
 #define CPRUNE_TILE_LIST(X) \
   X(0, 1, 4, 4, 4)  /* 64 x 256  */ \
-  X(1, 1, 4, 8, 2)  /* 128 x 128 */ \
-  X(2, 2, 2, 4, 4)  /* 128 x 128 */ \
-  X(3, 1, 4, 2, 4)  /* 32 x 256  */ \
-  X(4, 1, 4, 4, 2)  /* 64 x 128  */ \
-  X(5, 1, 4, 1, 4)  /* 16 x 256  */ \
-  X(6, 1, 4, 3, 4)  /* 48 x 256  */ \
-  X(7, 1, 4, 2, 2)  /* 32 x 128  */ \
-  X(8, 1, 4, 1, 2)  /* 16 x 128  */ \
-  X(9, 1, 4, 4, 1)  /* 64 x 64   */ \
-  X(10, 1, 4, 2, 1) /* 32 x 64   */ \
-  X(11, 1, 4, 8, 1) /* 128 x 64  */ \
-  X(12, 4, 1, 2, 7) /* 128 x 112 */ \
-  X(13, 2, 2, 4, 6) /* 128 x 192 */ \
-  X(14, 1, 4, 6, 3) /* 96 x 192  */ \
-  X(15, 1, 4, 1, 1) /* 16 x 64   */ \
-  X(16, 2, 2, 8, 4) /* 256 x 128 */
+  X(1, 2, 2, 4, 4)  /* 128 x 128 */ \
+  X(2, 1, 4, 2, 4)  /* 32 x 256  */ \
+  X(3, 1, 4, 4, 2)  /* 64 x 128  */ \
+  X(4, 1, 4, 1, 4)  /* 16 x 256  */ \
+  X(5, 1, 4, 3, 4)  /* 48 x 256  */ \
+  X(6, 1, 4, 2, 2)  /* 32 x 128  */ \
+  X(7, 1, 4, 1, 2)  /* 16 x 128  */ \
+  X(8, 1, 4, 4, 1)  /* 64 x 64   */ \
+  X(9, 1, 4, 2, 1)  /* 32 x 64   */ \
+  X(10, 1, 4, 8, 1) /* 128 x 64  */ \
+  X(11, 1, 4, 8, 2) /* 128 x 128 */ \
+  X(12, 1, 4, 6, 2) /* 96 x 128  */ \
+  X(13, 1, 4, 1, 1) /* 16 x 64   */
 
-constexpr int kNumTiles = 17;
+constexpr int kNumTiles = 14;
 
 template <typename T>
-inline void launch_tile(int tile, dim3 grid, hipStream_t s, const ConvArgs& a) {
-#define CPRUNE_TILE_CASE(ID, WM_, WN_, MB_, NB_)                                               \
-  case ID:                                                                                     \
-    hipLaunchKernelGGL((conv_igemm_kernel<T, WM_, WN_, MB_, NB_>), grid, dim3(256), 0, s, a);  \
+inline void launch_tile(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, bool fixup) {
+#define CPRUNE_TILE_CASE(ID, WM_, WN_, MB_, NB_)                                                \
+  case ID:                                                                                      \
+    hipLaunchKernelGGL((conv_igemm_kernel<T, WM_, WN_, MB_, NB_>), grid, dim3(256), 0, s, a);   \
+    if (fixup)                                                                                  \
+      hipLaunchKernelGGL((conv_fixup_kernel<T, WM_, WN_, MB_, NB_>), grid, dim3(256), 0, s, a); \
     break;
   switch (tile) { CPRUNE_TILE_LIST(CPRUNE_TILE_CASE) }
 #undef CPRUNE_TILE_CASE
 }
 
-// Sums the split-K partials in slice order (deterministic), then the epilogue.
-template <typename T>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(ConvArgs a) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  const size_t total = (size_t)a.O * a.P;
-  if (i >= total) return;
-  const int o = (int)(i / a.P);
-  const int p = (int)(i - (size_t)o * a.P);
-  float s = 0.0f;
-  for (int k = 0; k < a.split_k; ++k) s += a.partial[(size_t)k * total + i];
-  s += a.bias ? a.bias[o] : 0.0f;
-  const int n = p / a.HoWo;
-  const int rem = p - n * a.HoWo;
-  const size_t off = ((size_t)n * a.O + o) * a.HoWo + rem;
-  if (a.res) s += Elem<T>::to_f32(((const T*)a.res)[off]);
-  ((T*)a.y)[off] = Elem<T>::from_f32(apply_act(s, a.act));
-}
-
 // Per-dtype launch entry points, one translation unit each.
-void launch_conv_f32(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, dim3 reduce_grid);
-void launch_conv_f16(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, dim3 reduce_grid);
-void launch_conv_bf16(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, dim3 reduce_grid);
+void launch_conv_f32(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, bool fixup);
+void launch_conv_f16(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, bool fixup);
+void launch_conv_bf16(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, bool fixup);
 
 }  // namespace cprune

@@ -1,5 +1,5 @@
-// Host side of the dense convolution: the variant table (tile x reduction
-// split), what each variant supports and needs, and the launch.
+// Host side of the dense convolution: the variant table (tile x scheduling
+// mode), what each variant supports and needs, and the launch.
 #include "conv_kernel.hpp"
 
 namespace cprune {
@@ -11,8 +11,11 @@ const TileVariant kTiles[] = {
 #undef CPRUNE_TILE_ROW
 };
 static_assert(sizeof(kTiles) / sizeof(kTiles[0]) == kNumTiles, "tile table");
-const int kSplits[] = {1, 2, 4, 8, 16};
-constexpr int kNumSplits = sizeof(kSplits) / sizeof(kSplits[0]);
+// Scheduling modes: 0 = one output tile per work-group; n > 0 = the (tile, slab)
+// work line is cut into equal runs for n * 256 resident work-groups.
+const int kScheds[] = {0, 1, 2, 3};
+constexpr int kNumScheds = sizeof(kScheds) / sizeof(kScheds[0]);
+constexpr int kMinUnitsPerGroup = 4;
 
 unsigned magic_for(unsigned d) {
   if (d <= 1) return 0;
@@ -21,18 +24,50 @@ unsigned magic_for(unsigned d) {
 
 int slab_k(int dt) { return dt == CPRUNE_F32 ? 16 : 32; }
 
+struct Plan {
+  int tiles_m, tiles_p, slabs, units, units_per_wg, groups;
+  bool fixup;
+};
+
+Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv) {
+  Plan p;
+  const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
+  const long P = (long)d.n * ho * wo;
+  const int K = d.c_in * d.kh * d.kw;
+  const int kt = slab_k(d.dtype);
+  p.tiles_m = (d.c_out + tv.tile_m() - 1) / tv.tile_m();
+  p.tiles_p = (int)((P + tv.tile_p() - 1) / tv.tile_p());
+  p.slabs = (K + kt - 1) / kt;
+  const long units = (long)p.tiles_m * p.tiles_p * p.slabs;
+  p.units = (int)units;
+  if (tv.sched == 0) {
+    p.units_per_wg = p.slabs;
+    p.groups = p.tiles_m * p.tiles_p;
+    p.fixup = false;
+  } else {
+    long g = (long)tv.sched * 256;
+    const long cap = (units + kMinUnitsPerGroup - 1) / kMinUnitsPerGroup;
+    if (g > cap) g = cap;
+    if (g < 1) g = 1;
+    p.units_per_wg = (int)((units + g - 1) / g);
+    p.groups = (int)((units + p.units_per_wg - 1) / p.units_per_wg);
+    p.fixup = (p.units_per_wg % p.slabs) != 0;
+  }
+  return p;
+}
+
 }  // namespace
 
-int num_variants() { return kNumTiles * kNumSplits; }
+int num_variants() { return kNumTiles * kNumScheds; }
 
 const TileVariant& variant(int id) {
-  static TileVariant table[kNumTiles * kNumSplits];
+  static TileVariant table[kNumTiles * kNumScheds];
   static bool init = false;
   if (!init) {
     for (int t = 0; t < kNumTiles; ++t)
-      for (int s = 0; s < kNumSplits; ++s) {
-        table[t * kNumSplits + s] = kTiles[t];
-        table[t * kNumSplits + s].split_k = kSplits[s];
+      for (int s = 0; s < kNumScheds; ++s) {
+        table[t * kNumScheds + s] = kTiles[t];
+        table[t * kNumScheds + s].sched = kScheds[s];
       }
     init = true;
   }
@@ -43,20 +78,21 @@ bool variant_supports(const cprune_conv_desc& d, int v) {
   if (v < 0 || v >= num_variants()) return false;
   if (d.groups != 1) return false;
   const TileVariant& tv = variant(v);
-  long K = (long)d.c_in * d.kh * d.kw;
-  int kt = slab_k(d.dtype);
-  long slabs = (K + kt - 1) / kt;
-  if (tv.split_k > 1 && slabs < 2L * tv.split_k) return false;  // at least two slabs per slice
-  return true;
+  const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
+  const long P = (long)d.n * ho * wo;
+  const long K = (long)d.c_in * d.kh * d.kw;
+  const long kt = slab_k(d.dtype);
+  const long units = ((d.c_out + tv.tile_m() - 1) / tv.tile_m()) * ((P + tv.tile_p() - 1) / tv.tile_p()) * ((K + kt - 1) / kt);
+  return units < (1L << 30);
 }
 
 size_t conv_ws_bytes(const cprune_conv_desc& d, int v) {
   if (d.groups != 1) return 0;
-  int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
-  size_t op = (size_t)d.c_out * d.n * ho * wo * sizeof(float);
   if (v >= 0) {
-    int sk = variant(v).split_k;
-    return sk > 1 ? op * sk : 0;
+    if (!variant_supports(d, v)) return 0;
+    const TileVariant& tv = variant(v);
+    const Plan p = make_plan(d, tv);
+    return p.fixup ? (size_t)2 * p.groups * tv.tile_m() * tv.tile_p() * sizeof(float) : 0;
   }
   size_t best = 0;
   for (int i = 0; i < num_variants(); ++i)
@@ -71,6 +107,7 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
                       const void* residual, void* y, int v, void* ws, hipStream_t s) {
   const TileVariant& tv = variant(v);
   const size_t es = dtype_size(d.dtype);
+  const Plan p = make_plan(d, tv);
   ConvArgs a;
   a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.partial = (float*)ws;
   a.N = d.n; a.C = d.c_in; a.H = d.h; a.W = d.w; a.O = d.c_out; a.KH = d.kh; a.KW = d.kw;
@@ -87,19 +124,16 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
   a.x_bytes = (unsigned)((size_t)d.n * d.c_in * d.h * d.w * es);
   a.w_bytes = (unsigned)((size_t)d.c_out * a.K * es);
   a.act = d.act;
-  const int mt = tv.tile_m(), pt = tv.tile_p();
-  a.tiles_m = (a.O + mt - 1) / mt;
-  a.tiles_p = (a.P + pt - 1) / pt;
-  const int kt = slab_k(d.dtype);
-  const int slabs = (a.K + kt - 1) / kt;
-  a.split_k = tv.split_k;
-  a.k_per_split = ((slabs + tv.split_k - 1) / tv.split_k) * kt;
-  dim3 grid((unsigned)(a.tiles_m * a.tiles_p), 1, (unsigned)a.split_k);
-  dim3 rgrid((unsigned)(((size_t)a.O * a.P + 255) / 256));
-  const int tile = v / kNumSplits;
-  if (d.dtype == CPRUNE_F32) launch_conv_f32(tile, grid, s, a, rgrid);
-  else if (d.dtype == CPRUNE_F16) launch_conv_f16(tile, grid, s, a, rgrid);
-  else launch_conv_bf16(tile, grid, s, a, rgrid);
+  a.tiles_m = p.tiles_m;
+  a.tiles_p = p.tiles_p;
+  a.slabs = p.slabs;
+  a.units = p.units;
+  a.units_per_wg = p.units_per_wg;
+  dim3 grid((unsigned)p.groups);
+  const int tile = v / kNumScheds;
+  if (d.dtype == CPRUNE_F32) launch_conv_f32(tile, grid, s, a, p.fixup);
+  else if (d.dtype == CPRUNE_F16) launch_conv_f16(tile, grid, s, a, p.fixup);
+  else launch_conv_bf16(tile, grid, s, a, p.fixup);
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }

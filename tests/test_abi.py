@@ -42,7 +42,7 @@ def test_variant_table():
     seen = set()
     for v in range(nv):
         tm, tp, sk = B.cprune_tile_variant_info(v)
-        assert tm % 16 == 0 and tp % 16 == 0 and sk >= 1
+        assert tm % 16 == 0 and tp % 16 == 0 and sk >= 0
         seen.add((tm, tp, sk))
     with pytest.raises(B.CPruneError):
         B.cprune_tile_variant_info(nv)
@@ -83,22 +83,21 @@ def test_conv_rejects_null_and_residual_mismatch_and_variant():
                                    C.c_size_t(0), None) == B.ERR_INVALID_ARG
 
 
-def test_split_k_needs_workspace():
-    d = _desc(c_in=64, c_out=64)
+def test_cut_tiles_need_workspace():
+    d = _desc(c_in=64, c_out=64, h=32, w=32)
     L = B.lib()
-    split_v = next(v for v in range(B.cprune_num_tile_variants())
-                   if B.cprune_tile_variant_info(v)[2] == 2)
-    need = B.cprune_conv_workspace_bytes(d, split_v)
-    assert need == 2 * 64 * 64 * 4
-    assert B.cprune_conv_workspace_bytes(d, -1) >= need
-    assert L.cprune_conv2d_bn_relu(C.byref(d), FAKE, FAKE, None, None, FAKE, C.c_int(split_v), FAKE,
-                                   C.c_size_t(need - 1), None) == B.ERR_WORKSPACE
-    # a reduction too short to split is unsupported for that variant
-    tiny = _desc(c_in=1)
-    big_split = max(range(B.cprune_num_tile_variants()),
-                    key=lambda v: B.cprune_tile_variant_info(v)[2])
-    assert L.cprune_conv2d_bn_relu(C.byref(tiny), FAKE, FAKE, None, None, FAKE, C.c_int(big_split),
-                                   FAKE, C.c_size_t(1 << 30), None) == B.ERR_UNSUPPORTED
+    nv = B.cprune_num_tile_variants()
+    classic = [v for v in range(nv) if B.cprune_tile_variant_info(v)[2] == 0]
+    cut = [v for v in range(nv) if B.cprune_tile_variant_info(v)[2] > 0]
+    assert classic and cut
+    assert all(B.cprune_conv_workspace_bytes(d, v) == 0 for v in classic)
+    needs = {v: B.cprune_conv_workspace_bytes(d, v) for v in cut}
+    v = max(needs, key=needs.get)
+    assert needs[v] > 0 and B.cprune_conv_workspace_bytes(d, -1) == needs[v]
+    tm, tp, _ = B.cprune_tile_variant_info(v)
+    assert needs[v] % (2 * tm * tp * 4) == 0
+    assert L.cprune_conv2d_bn_relu(C.byref(d), FAKE, FAKE, None, None, FAKE, C.c_int(v), FAKE,
+                                   C.c_size_t(needs[v] - 1), None) == B.ERR_WORKSPACE
 
 
 def test_rank_rejects_bad_args():
