@@ -34,6 +34,7 @@ inline int conv_out_dim(int in, int k, int stride, int pad) { return (in + 2 * p
 struct TileVariant {
   int wm, wn;   // waves along output channels / pixels (wm * wn == 4)
   int mb, nb;   // 16x16 MFMA blocks per wave along channels / pixels
+  int kq;       // MFMA rounds (64 bytes of k per row each) per slab
   int sched;  // scheduling mode: 0 = one tile per work-group, n = runs for n * 256 groups
   int tile_m() const { return wm * mb * 16; }
   int tile_p() const { return wn * nb * 16; }

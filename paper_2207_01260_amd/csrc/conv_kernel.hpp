@@ -65,7 +65,6 @@ struct ConvArgs {
 };
 
 constexpr unsigned kOutOfRange = 0x80000000u;  // beyond any buffer this kernel accepts
-constexpr int ROW_BYTES = 80;  // 64 bytes of k per row + 16 so rows rotate across LDS banks
 
 __device__ __forceinline__ unsigned fast_div(unsigned n, unsigned magic) {
   return magic ? __umulhi(n, magic) : n;
@@ -186,15 +185,17 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, const float4_t 
   }
 }
 
-template <typename T, int WM, int WN, int MB, int NB>
+template <typename T, int WM, int WN, int MB, int NB, int KQ>
 __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
   typedef typename Elem<T>::raw_t raw_t;
   constexpr int ES = (int)sizeof(T);
   constexpr int EPI = 16 / ES;               // elements per 16-byte fragment
-  constexpr int KT = 4 * EPI;                // reduction elements per slab
+  constexpr int KT = 4 * EPI * KQ;           // reduction elements per slab (KQ MFMA rounds of 64 bytes)
+  constexpr int ROW_BYTES = 64 * KQ + 16;    // k bytes per LDS row + 16 so rows rotate across banks
+  constexpr int NQ = 4 * KQ;                 // 16-byte quads per row
   constexpr int MT = WM * MB * 16;
   constexpr int PT = WN * NB * 16;
-  constexpr int NIB = (PT * 4 + 255) / 256;  // B staging items (pixel, 16-byte quad) per thread
+  constexpr int NIB = (PT * NQ + 255) / 256; // B staging items (pixel, 16-byte quad) per thread
   constexpr int A_ROWS = 256 / KT;           // A rows staged per pass (KT threads along k)
   constexpr int NIA = (MT + A_ROWS - 1) / A_ROWS;
 
@@ -252,7 +253,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
     for (int j = 0; j < NIB; ++j) {
       const int idx = t + 256 * j;
       const int pi = idx % PT, q = idx / PT;
-      const bool item = idx < PT * 4;
+      const bool item = idx < PT * NQ;
       unsigned pm = 0;
       int base = 0;
       const int p = p0 + pi;
@@ -370,7 +371,8 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
       __syncthreads();
       for (int s = 0; s < nslab; ++s) {
         const int buf = s & 1;
-        // operands of this slab first (their LDS latency overlaps the address work below)
+        // operands of the slab's first round first (their LDS latency overlaps the
+        // address work below)
         uint4 af[MB], bf[NB];
 #pragma unroll
         for (int j = 0; j < NB; ++j) bf[j] = *(const uint4*)&sB[buf][b_frag + j * 16 * ROW_BYTES];
@@ -379,6 +381,14 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
         if (s + 1 < nslab) gload(s + 1, (s + 1) & 1);
         if (s + 2 < nslab) write_table(s + 2, s & 1);
         mma_slab<T, MBC, NB, MB>(af, bf, acc);
+#pragma unroll
+        for (int q4 = 1; q4 < KQ; ++q4) {
+#pragma unroll
+          for (int j = 0; j < NB; ++j) bf[j] = *(const uint4*)&sB[buf][b_frag + j * 16 * ROW_BYTES + q4 * 64];
+#pragma unroll
+          for (int i = 0; i < MBC; ++i) af[i] = *(const uint4*)&sA[buf][a_frag + i * 16 * ROW_BYTES + q4 * 64];
+          mma_slab<T, MBC, NB, MB>(af, bf, acc);
+        }
         if (s + 1 < nslab) lds_store(buf ^ 1);
         __syncthreads();
       }
@@ -407,10 +417,12 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(ConvArgs a) {
 }
 
 // Sums the pieces of every output tile that was cut between work-groups, in the
-// order of the runs, and applies the epilogue.  One work-group per run.  A run
-// completes at most one cut tile: the one it starts in the middle of, if the
-// run reaches that tile's last slab.  (Tiles a run starts at slab 0 are either
-// whole, or completed by a later run.)
+// order of the runs, and applies the epilogue.  grid.x = one work-group per run,
+// grid.y = one per accumulator block of the tile.  A run completes at most one
+// cut tile: the one it starts in the middle of, if the run reaches that tile's
+// last slab.  (Tiles a run starts at slab 0 are either whole, or completed by a
+// later run.)  Pieces are fetched four at a time so their latencies overlap;
+// the additions stay in run order, so the result does not depend on timing.
 template <typename T, int WM, int WN, int MB, int NB>
 __global__ __launch_bounds__(256) void conv_fixup_kernel(ConvArgs a) {
   constexpr int MT = WM * MB * 16, PT = WN * NB * 16;
@@ -427,50 +439,77 @@ __global__ __launch_bounds__(256) void conv_fixup_kernel(ConvArgs a) {
   const int t = threadIdx.x;
   const int lane = t & 63, wave = t >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  float4_t acc[MB][NB];
-#pragma unroll
-  for (int i = 0; i < MB; ++i)
-#pragma unroll
-    for (int jj = 0; jj < NB; ++jj) acc[i][jj] = (float4_t){0.f, 0.f, 0.f, 0.f};
-  for (int g = g_lo; g <= g_hi; ++g) {
+  const int blk = blockIdx.y;  // i * NB + jj
+  const int bi = blk / NB, bj = blk % NB;
+  const size_t elem = (size_t)wave * (MB * NB * 64) + (size_t)blk * 64 + lane;
+  auto piece = [&](int g) -> const float4_t* {
     int gb, ge;
     unit_range(a, g, gb, ge);
     const int slot = 2 * g + ((gb / a.slabs == tile) ? 0 : 1);
-    const float4_t* src = (const float4_t*)(a.partial + (size_t)slot * (MT * PT)) + (size_t)wave * (MB * NB * 64) + lane;
-#pragma unroll
-    for (int i = 0; i < MB; ++i)
-#pragma unroll
-      for (int jj = 0; jj < NB; ++jj) acc[i][jj] += src[(i * NB + jj) * 64];
+    return (const float4_t*)(a.partial + (size_t)slot * (MT * PT)) + elem;
+  };
+  float4_t acc = (float4_t){0.f, 0.f, 0.f, 0.f};
+  int g = g_lo;
+  for (; g + 3 <= g_hi; g += 4) {
+    const float4_t v0 = *piece(g), v1 = *piece(g + 1), v2 = *piece(g + 2), v3 = *piece(g + 3);
+    acc += v0; acc += v1; acc += v2; acc += v3;
   }
-  conv_epilogue<T, WM, WN, MB, NB>(a, acc, tile % a.tiles_m, tile / a.tiles_m, wm, wn, lane & 15, lane >> 4);
+  for (; g <= g_hi; ++g) acc += *piece(g);
+
+  // epilogue of one 16x16 block: lane holds rows 4*g4..4*g4+3 of column r
+  const int r = lane & 15, g4 = lane >> 4;
+  const int tile_m = tile % a.tiles_m, tile_p = tile / a.tiles_m;
+  const int p = tile_p * PT + wn * NB * 16 + bj * 16 + r;
+  if (p >= a.P) return;
+  const int n = p / a.HoWo;
+  const int rem = p - n * a.HoWo;
+  const size_t pix = (size_t)n * a.O * a.HoWo + rem;
+  T* __restrict__ yg = (T*)a.y;
+  const T* __restrict__ rg = (const T*)a.res;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int o = tile_m * MT + wm * MB * 16 + bi * 16 + 4 * g4 + v;
+    if (o < a.O) {
+      float val = acc[v] + (a.bias ? a.bias[o] : 0.0f);
+      const size_t off = pix + (size_t)o * a.HoWo;
+      if (rg) val += Elem<T>::to_f32(rg[off]);
+      yg[off] = Elem<T>::from_f32(apply_act(val, a.act));
+    }
+  }
 }
 
-// Tile table shared by the launchers: id, wm, wn, mb, nb.
+// Tile table shared by the launchers: id, wm, wn, mb, nb, kq.  Small tiles take deeper
+// slabs (kq rounds of 64 bytes of k per barrier): their per-slab MFMA work is short
+// against the latency of the loads that feed the next slab.
 #define CPRUNE_TILE_LIST(X) \
-  X(0, 1, 4, 4, 4)  /* 64 x 256  */ \
-  X(1, 2, 2, 4, 4)  /* 128 x 128 */ \
-  X(2, 1, 4, 2, 4)  /* 32 x 256  */ \
-  X(3, 1, 4, 4, 2)  /* 64 x 128  */ \
-  X(4, 1, 4, 1, 4)  /* 16 x 256  */ \
-  X(5, 1, 4, 3, 4)  /* 48 x 256  */ \
-  X(6, 1, 4, 2, 2)  /* 32 x 128  */ \
-  X(7, 1, 4, 1, 2)  /* 16 x 128  */ \
-  X(8, 1, 4, 4, 1)  /* 64 x 64   */ \
-  X(9, 1, 4, 2, 1)  /* 32 x 64   */ \
-  X(10, 1, 4, 8, 1) /* 128 x 64  */ \
-  X(11, 1, 4, 8, 2) /* 128 x 128 */ \
-  X(12, 1, 4, 6, 2) /* 96 x 128  */ \
-  X(13, 1, 4, 1, 1) /* 16 x 64   */
+  X(0, 1, 4, 4, 4, 1)  /* 64 x 256  */ \
+  X(1, 2, 2, 4, 4, 1)  /* 128 x 128 */ \
+  X(2, 1, 4, 8, 2, 1)  /* 128 x 128 */ \
+  X(3, 1, 4, 2, 4, 1)  /* 32 x 256  */ \
+  X(4, 1, 4, 4, 2, 1)  /* 64 x 128  */ \
+  X(5, 1, 4, 4, 2, 2)  /* 64 x 128, deep */ \
+  X(6, 1, 4, 3, 4, 1)  /* 48 x 256  */ \
+  X(7, 1, 4, 1, 4, 1)  /* 16 x 256  */ \
+  X(8, 1, 4, 2, 2, 2)  /* 32 x 128, deep */ \
+  X(9, 1, 4, 1, 2, 2)  /* 16 x 128, deep */ \
+  X(10, 1, 4, 4, 1, 1) /* 64 x 64   */ \
+  X(11, 1, 4, 4, 1, 2) /* 64 x 64, deep */ \
+  X(12, 1, 4, 2, 1, 4) /* 32 x 64, deep */ \
+  X(13, 1, 4, 8, 1, 1) /* 128 x 64  */ \
+  X(14, 1, 4, 8, 1, 2) /* 128 x 64, deep */ \
+  X(15, 1, 4, 1, 1, 4) /* 16 x 64, deep */ \
+  X(16, 1, 4, 6, 2, 1) /* 96 x 128  */ \
+  X(17, 1, 4, 2, 1, 1) /* 32 x 64   */
 
-constexpr int kNumTiles = 14;
+constexpr int kNumTiles = 18;
 
 template <typename T>
 inline void launch_tile(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, bool fixup) {
-#define CPRUNE_TILE_CASE(ID, WM_, WN_, MB_, NB_)                                                \
-  case ID:                                                                                      \
-    hipLaunchKernelGGL((conv_igemm_kernel<T, WM_, WN_, MB_, NB_>), grid, dim3(256), 0, s, a);   \
-    if (fixup)                                                                                  \
-      hipLaunchKernelGGL((conv_fixup_kernel<T, WM_, WN_, MB_, NB_>), grid, dim3(256), 0, s, a); \
+#define CPRUNE_TILE_CASE(ID, WM_, WN_, MB_, NB_, KQ_)                                                \
+  case ID:                                                                                           \
+    hipLaunchKernelGGL((conv_igemm_kernel<T, WM_, WN_, MB_, NB_, KQ_>), grid, dim3(256), 0, s, a);   \
+    if (fixup)                                                                                       \
+      hipLaunchKernelGGL((conv_fixup_kernel<T, WM_, WN_, MB_, NB_>), dim3(grid.x, MB_ * NB_), dim3(256), 0, s, a); \
     break;
   switch (tile) { CPRUNE_TILE_LIST(CPRUNE_TILE_CASE) }
 #undef CPRUNE_TILE_CASE

@@ -6,14 +6,14 @@ namespace cprune {
 namespace {
 
 const TileVariant kTiles[] = {
-#define CPRUNE_TILE_ROW(ID, WM_, WN_, MB_, NB_) {WM_, WN_, MB_, NB_, 1},
+#define CPRUNE_TILE_ROW(ID, WM_, WN_, MB_, NB_, KQ_) {WM_, WN_, MB_, NB_, KQ_, 1},
     CPRUNE_TILE_LIST(CPRUNE_TILE_ROW)
 #undef CPRUNE_TILE_ROW
 };
 static_assert(sizeof(kTiles) / sizeof(kTiles[0]) == kNumTiles, "tile table");
 // Scheduling modes: 0 = one output tile per work-group; n > 0 = the (tile, slab)
 // work line is cut into equal runs for n * 256 resident work-groups.
-const int kScheds[] = {0, 1, 2, 3};
+const int kScheds[] = {0, 1, 2, 3, 4, 6, 8};
 constexpr int kNumScheds = sizeof(kScheds) / sizeof(kScheds[0]);
 constexpr int kMinUnitsPerGroup = 4;
 
@@ -22,7 +22,7 @@ unsigned magic_for(unsigned d) {
   return (unsigned)((0x100000000ull + d - 1) / d);
 }
 
-int slab_k(int dt) { return dt == CPRUNE_F32 ? 16 : 32; }
+int slab_k(int dt, int kq) { return (dt == CPRUNE_F32 ? 16 : 32) * kq; }
 
 struct Plan {
   int tiles_m, tiles_p, slabs, units, units_per_wg, groups;
@@ -34,7 +34,7 @@ Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv) {
   const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
   const long P = (long)d.n * ho * wo;
   const int K = d.c_in * d.kh * d.kw;
-  const int kt = slab_k(d.dtype);
+  const int kt = slab_k(d.dtype, tv.kq);
   p.tiles_m = (d.c_out + tv.tile_m() - 1) / tv.tile_m();
   p.tiles_p = (int)((P + tv.tile_p() - 1) / tv.tile_p());
   p.slabs = (K + kt - 1) / kt;
@@ -81,7 +81,7 @@ bool variant_supports(const cprune_conv_desc& d, int v) {
   const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
   const long P = (long)d.n * ho * wo;
   const long K = (long)d.c_in * d.kh * d.kw;
-  const long kt = slab_k(d.dtype);
+  const long kt = slab_k(d.dtype, tv.kq);
   const long units = ((d.c_out + tv.tile_m() - 1) / tv.tile_m()) * ((P + tv.tile_p() - 1) / tv.tile_p()) * ((K + kt - 1) / kt);
   return units < (1L << 30);
 }

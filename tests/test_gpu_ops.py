@@ -212,7 +212,7 @@ def test_conv_shapes_every_variant(orc, cfg):
 def test_conv_act_and_residual(orc):
     for act in (B.ACT_NONE, B.ACT_RELU, B.ACT_RELU6):
         for res in (False, True):
-            _conv_case(orc, 2, 19, 10, 10, 23, 3, 1, 1, act=act, residual=res, variants=(-1, 0, 2, 9, 35),
+            _conv_case(orc, 2, 19, 10, 10, 23, 3, 1, 1, act=act, residual=res, variants=(-1, 0, 2, 9, 35, 60, 90, 110),
                        tag=3)
 
 
@@ -230,7 +230,7 @@ def test_conv_repeatable(orc):
     x = dev(synth.tensor_normal((2, 64, 16, 16), 124))
     w = dev(synth.tensor_normal((96, 64, 3, 3), 125, std=0.05))
     d = B.conv_desc(x.shape, w.shape, 1, 1)
-    for v in (0, 3 * 4 + 2, 8 * 4 + 3, -1):
+    for v in (0, 3 * 7 + 2, 8 * 7 + 6, -1):
         a = B.cprune_conv2d_bn_relu(d, x, w, None, None, v)
         b = B.cprune_conv2d_bn_relu(d, x, w, None, None, v)
         assert torch.equal(a, b)
