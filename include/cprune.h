@@ -196,8 +196,10 @@ typedef struct {
 typedef struct cprune_net cprune_net;
 
 /* Builds a handle: copies every layer's weights and bias into memory the handle
- * owns, allocates one activation buffer per layer for `max_batch` images and the
- * conv scratch, and picks a tile variant per conv shape (timing it on the device
+ * owns (repacked channels-last: inside a handle activations are [n][h][w][c'] and weights
+ * [c_out][kh][kw][c'], c' = channels rounded up to one 16-byte vector, pad channels zero;
+ * x and logits at the boundary stay NCHW), allocates one activation buffer per layer for
+ * `max_batch` images and the conv scratch, and picks a tile variant per conv shape (timing it on the device
  * when tune != 0, as cprune_select_tile does, for batch `max_batch`).  `layers` is
  * a host array.  in_c/in_h/in_w: the network input [n][in_c][in_h][in_w]. */
 int cprune_net_create(const cprune_layer_desc* layers, int n_layers, int in_c, int in_h,
@@ -213,7 +215,10 @@ int cprune_net_forward(cprune_net* net, const void* x, int n, void* logits, int 
  * every layer with events on `stream`; ms_out: host [n_layers].  Synchronises. */
 int cprune_net_layer_times(cprune_net* net, const void* x, int n, int iters, float* ms_out,
                            void* stream);
-/* Copies layer `layer`'s activation of the last forward (batch n) to dst (device). */
+/* Writes layer `layer`'s activation of the last forward (batch n) to dst (device) as dense
+ * NCHW [n][c_out][h_out][w_out].  For the last layer of a net whose output map is 1x1 the
+ * values are those of the last cprune_net_layer_times pass (forward writes that layer
+ * straight into `logits`). */
 int cprune_net_copy_activation(cprune_net* net, int layer, int n, void* dst, size_t dst_bytes,
                                void* stream);
 /* The tile variant in use for layer `layer` (-1 for layers without one); host out. */

@@ -40,31 +40,31 @@ int validate_conv_desc(const cprune_conv_desc* d) {
 }
 
 // ---- variant cache -------------------------------------------------------------
-typedef std::array<int, 13> DescKey;
-static DescKey key_of(const cprune_conv_desc& d) {
+typedef std::array<int, 16> DescKey;
+static DescKey key_of(const cprune_conv_desc& d, const ConvLayout& lay) {
   return DescKey{d.n, d.c_in, d.h, d.w, d.c_out, d.kh, d.kw, d.stride, d.pad, d.groups, d.dtype, d.act,
-                 d.has_residual};
+                 d.has_residual, lay.nhwc, lay.cp_in, lay.cp_out};
 }
 static std::mutex g_cache_mutex;
 static std::map<DescKey, int> g_cache;
 
-void remember_variant(const cprune_conv_desc& d, int v) {
+void remember_variant(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
   std::lock_guard<std::mutex> lock(g_cache_mutex);
-  g_cache[key_of(d)] = v;
+  g_cache[key_of(d, lay)] = v;
 }
 
 // Untimed fallback: the tile whose wavefronts reuse their LDS operands most (blocks
 // per operand fetched), discounted by the pixel columns a ragged last tile wastes;
 // work cut into equal runs for 512 resident work-groups, which needs no knowledge
 // of how the tile count divides the chip.  Used only for shapes never timed.
-int heuristic_variant(const cprune_conv_desc& d) {
+int heuristic_variant(const cprune_conv_desc& d, const ConvLayout& lay) {
   const long ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
   const long P = (long)d.n * ho * wo, O = d.c_out;
   double best = -1.0;
   int best_v = 0;
   for (int v = 0; v < num_variants(); ++v) {
     const TileVariant& tv = variant(v);
-    if (tv.sched != 2 || !variant_supports(d, v)) continue;
+    if (tv.sched != 2 || !variant_supports(d, v, lay)) continue;
     const long mt = tv.tile_m(), pt = tv.tile_p();
     const long tm = (O + mt - 1) / mt, tp = (P + pt - 1) / pt;
     double rows16 = std::ceil((double)O / tm / 16.0 / tv.wm);
@@ -77,34 +77,37 @@ int heuristic_variant(const cprune_conv_desc& d) {
   return best_v;
 }
 
-int cached_or_heuristic_variant(const cprune_conv_desc& d, bool* timed) {
+int cached_or_heuristic_variant(const cprune_conv_desc& d, bool* timed, const ConvLayout& lay) {
   {
     std::lock_guard<std::mutex> lock(g_cache_mutex);
-    auto it = g_cache.find(key_of(d));
+    auto it = g_cache.find(key_of(d, lay));
     if (it != g_cache.end()) {
       if (timed) *timed = true;
       return it->second;
     }
   }
   if (timed) *timed = false;
-  return heuristic_variant(d);
+  return heuristic_variant(d, lay);
 }
 
 static int conv_dispatch(const cprune_conv_desc& d, const void* x, const void* w, const float* bias,
-                         const void* residual, void* y, int v, void* ws, size_t ws_bytes, hipStream_t s) {
-  if (d.groups != 1) return launch_conv_depthwise(d, x, w, bias, residual, y, s);
-  if (v < 0) v = cached_or_heuristic_variant(d, nullptr);
-  if (!variant_supports(d, v)) return CPRUNE_ERR_UNSUPPORTED;
-  const size_t need = conv_ws_bytes(d, v);
+                         const void* residual, void* y, int v, void* ws, size_t ws_bytes, hipStream_t s,
+                         const ConvLayout& lay = ConvLayout()) {
+  if (d.groups != 1)
+    return lay.nhwc ? launch_depthwise_nhwc(d, lay.cp_in, x, w, bias, residual, y, s)
+                    : launch_conv_depthwise(d, x, w, bias, residual, y, s);
+  if (v < 0) v = cached_or_heuristic_variant(d, nullptr, lay);
+  if (!variant_supports(d, v, lay)) return CPRUNE_ERR_UNSUPPORTED;
+  const size_t need = conv_ws_bytes(d, v, lay);
   if (need > 0 && (!ws || ws_bytes < need)) return CPRUNE_ERR_WORKSPACE;
-  return launch_conv_dense(d, x, w, bias, residual, y, v, ws, s);
+  return launch_conv_dense(d, x, w, bias, residual, y, v, ws, s, lay);
 }
 
 // Times every supported variant on the given buffers; returns the fastest.
 static int select_tile_impl(const cprune_conv_desc& d, const void* x, const void* w, const float* bias,
                             const void* residual, void* y, void* ws, size_t ws_bytes, int warmup,
                             int iters, int* variant_out, float* best_ms_out, float* all_ms_out,
-                            hipStream_t s) {
+                            hipStream_t s, const ConvLayout& lay = ConvLayout()) {
   hipEvent_t e0, e1;
   CPRUNE_HIP_TRY(hipEventCreate(&e0));
   hipError_t ee = hipEventCreate(&e1);
@@ -116,17 +119,17 @@ static int select_tile_impl(const cprune_conv_desc& d, const void* x, const void
   for (int v = 0; v < nv && rc == CPRUNE_OK; ++v) {
     if (all_ms_out) all_ms_out[v] = -1.0f;
     if (d.groups == 1) {
-      if (!variant_supports(d, v)) continue;
-      if (conv_ws_bytes(d, v) > ws_bytes) continue;  // not timed: the caller's scratch cannot run it
+      if (!variant_supports(d, v, lay)) continue;
+      if (conv_ws_bytes(d, v, lay) > ws_bytes) continue;  // not timed: the caller's scratch cannot run it
     }
-    for (int i = 0; i < warmup && rc == CPRUNE_OK; ++i) rc = conv_dispatch(d, x, w, bias, residual, y, v, ws, ws_bytes, s);
+    for (int i = 0; i < warmup && rc == CPRUNE_OK; ++i) rc = conv_dispatch(d, x, w, bias, residual, y, v, ws, ws_bytes, s, lay);
     if (rc != CPRUNE_OK) break;
     // two timed passes, the faster one counts: a pass disturbed by another process's
     // burst or a clock change must not decide the choice
     float ms = 0.0f;
     for (int pass = 0; pass < 2 && rc == CPRUNE_OK; ++pass) {
       hipError_t e = hipEventRecord(e0, s);
-      for (int i = 0; i < iters && rc == CPRUNE_OK; ++i) rc = conv_dispatch(d, x, w, bias, residual, y, v, ws, ws_bytes, s);
+      for (int i = 0; i < iters && rc == CPRUNE_OK; ++i) rc = conv_dispatch(d, x, w, bias, residual, y, v, ws, ws_bytes, s, lay);
       if (e == hipSuccess) e = hipEventRecord(e1, s);
       if (e == hipSuccess) e = hipEventSynchronize(e1);
       float t = 0.0f;
@@ -143,7 +146,7 @@ static int select_tile_impl(const cprune_conv_desc& d, const void* x, const void
   hipEventDestroy(e1);
   if (rc != CPRUNE_OK) return rc;
   if (best_v < 0) return CPRUNE_ERR_WORKSPACE;
-  if (d.groups == 1) remember_variant(d, best_v);
+  if (d.groups == 1) remember_variant(d, best_v, lay);
   if (variant_out) *variant_out = best_v;
   if (best_ms_out) *best_ms_out = best_ms;
   return CPRUNE_OK;
@@ -276,13 +279,18 @@ extern "C" int cprune_fc(const void* x, const void* w, const float* bias, int n,
 }
 
 // ---- network handle ------------------------------------------------------------
+// Inside a handle everything is channels-last: activations [n][h][w][cp], dense weights
+// [c_out][kh][kw][cp], depthwise weights [kh][kw][cp], with cp the channel count rounded up
+// to one 16-byte vector (pad channels are zero and stay zero through every layer).  The
+// boundary stays NCHW: the input is converted on the way in, activations on the way out.
 struct NetLayer {
   cprune_layer_desc d;
   int h_in, w_in, h_out, w_out;
+  int cp_in = 0, cp_out = 0;  // channel strides of the input / output buffers
   void* w = nullptr;
   float* b = nullptr;
-  void* act = nullptr;        // [max_batch][c_out][h_out][w_out]
-  size_t per_image = 0;       // elements per image of the output
+  void* act = nullptr;        // [max_batch][h_out][w_out][cp_out]
+  size_t per_image = 0;       // elements per image of the output buffer
   int variant = -1;           // dense conv / fc: variant for max_batch
 };
 
@@ -297,8 +305,9 @@ struct GraphKey {
 
 struct cprune_net {
   std::vector<NetLayer> layers;
-  int in_c, in_h, in_w, max_batch, dtype;
+  int in_c, in_h, in_w, in_cp, max_batch, dtype;
   std::vector<void*> allocs;
+  void* x_cl = nullptr;       // the network input, channels-last
   void* ws = nullptr;
   size_t ws_bytes = 0;
   std::map<GraphKey, hipGraphExec_t> graphs;
@@ -306,18 +315,24 @@ struct cprune_net {
   int last_n = 0;
 };
 
+// A fully connected layer is a convolution whose kernel covers its whole input map.
 static cprune_conv_desc layer_conv_desc(const cprune_net& net, const NetLayer& L, int n) {
   cprune_conv_desc d;
   d.n = n; d.c_in = L.d.c_in; d.c_out = L.d.c_out; d.dtype = net.dtype; d.act = L.d.act;
   d.has_residual = L.d.residual >= 0 ? 1 : 0;
+  d.h = L.h_in; d.w = L.w_in;
   if (L.d.kind == CPRUNE_LAYER_FC) {
-    d.c_in = L.d.c_in * L.h_in * L.w_in;
-    d.h = d.w = 1; d.kh = d.kw = 1; d.stride = 1; d.pad = 0; d.groups = 1;
+    d.kh = L.h_in; d.kw = L.w_in; d.stride = 1; d.pad = 0; d.groups = 1;
   } else {
-    d.h = L.h_in; d.w = L.w_in; d.kh = d.kw = L.d.k; d.stride = L.d.stride; d.pad = L.d.pad;
-    d.groups = L.d.groups;
+    d.kh = d.kw = L.d.k; d.stride = L.d.stride; d.pad = L.d.pad; d.groups = L.d.groups;
   }
   return d;
+}
+
+static ConvLayout layer_layout(const NetLayer& L) {
+  ConvLayout lay;
+  lay.nhwc = 1; lay.cp_in = L.cp_in; lay.cp_out = L.cp_out;
+  return lay;
 }
 
 static void net_free(cprune_net* net) {
@@ -327,34 +342,43 @@ static void net_free(cprune_net* net) {
   delete net;
 }
 
-static int net_run_layer(cprune_net* net, int i, const void* x, int n, void* out_override, hipStream_t s) {
+static int net_run_layer(cprune_net* net, int i, int n, void* out_override, hipStream_t s) {
   NetLayer& L = net->layers[i];
-  const void* src = L.d.input < 0 ? x : net->layers[L.d.input].act;
+  const void* src = L.d.input < 0 ? net->x_cl : net->layers[L.d.input].act;
   void* dst = out_override ? out_override : L.act;
   switch (L.d.kind) {
     case CPRUNE_LAYER_CONV:
     case CPRUNE_LAYER_FC: {
       cprune_conv_desc d = layer_conv_desc(*net, L, n);
+      const ConvLayout lay = layer_layout(L);
       const void* res = L.d.residual >= 0 ? net->layers[L.d.residual].act : nullptr;
       int v = -1;
-      if (d.groups == 1) v = (n == net->max_batch) ? L.variant : cached_or_heuristic_variant(d, nullptr);
-      return conv_dispatch(d, src, L.w, L.b, res, dst, v, net->ws, net->ws_bytes, s);
+      if (d.groups == 1) v = (n == net->max_batch) ? L.variant : cached_or_heuristic_variant(d, nullptr, lay);
+      return conv_dispatch(d, src, L.w, L.b, res, dst, v, net->ws, net->ws_bytes, s, lay);
     }
     case CPRUNE_LAYER_MAXPOOL:
-      return launch_maxpool(src, n, L.d.c_in, L.h_in, L.w_in, L.d.k, L.d.stride, L.d.pad, net->dtype, dst, s);
+      return launch_maxpool_nhwc(src, n, L.cp_in, L.h_in, L.w_in, L.d.k, L.d.stride, L.d.pad, net->dtype, dst, s);
     case CPRUNE_LAYER_GAVGPOOL:
-      return launch_gavgpool(src, n, L.d.c_in, L.h_in * L.w_in, net->dtype, dst, s);
+      return launch_gavgpool_nhwc(src, n, L.cp_in, L.h_in * L.w_in, net->dtype, dst, s);
   }
   return CPRUNE_ERR_INVALID_ARG;
 }
 
+// The last layer writes straight into the caller's buffer when its map is 1x1 (its
+// channel stride is then the dense channel count); otherwise its buffer is converted.
 static int net_enqueue(cprune_net* net, const void* x, int n, void* logits, hipStream_t s) {
   const int nl = (int)net->layers.size();
+  int rc = launch_nchw_to_nhwc(x, n, net->in_c, net->in_h * net->in_w, net->in_cp, net->dtype, net->x_cl, s);
+  if (rc != CPRUNE_OK) return rc;
+  const NetLayer& last = net->layers[nl - 1];
+  const bool direct = last.h_out * last.w_out == 1;
   for (int i = 0; i < nl; ++i) {
-    int rc = net_run_layer(net, i, x, n, (i == nl - 1) ? logits : nullptr, s);
+    rc = net_run_layer(net, i, n, (i == nl - 1 && direct) ? logits : nullptr, s);
     if (rc != CPRUNE_OK) return rc;
   }
-  return CPRUNE_OK;
+  if (!direct)
+    rc = launch_nhwc_to_nchw(last.act, n, last.d.c_out, last.h_out * last.w_out, last.cp_out, net->dtype, logits, s);
+  return rc;
 }
 
 extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, int in_c, int in_h,
@@ -365,8 +389,10 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
   hipStream_t s = (hipStream_t)stream;
   cprune_net* net = new cprune_net();
   net->in_c = in_c; net->in_h = in_h; net->in_w = in_w; net->max_batch = max_batch; net->dtype = dtype;
+  net->in_cp = round_up_vec(in_c, dtype);
   net->layers.resize(n_layers);
   const size_t es = dtype_size(dtype);
+  const long lim = 1L << 31;
   int rc = CPRUNE_OK;
   // shapes and validation
   for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
@@ -375,11 +401,12 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     const cprune_layer_desc& d = L.d;
     if (d.input < -1 || d.input >= i || d.residual < -1 || d.residual >= i) { rc = CPRUNE_ERR_INVALID_ARG; break; }
     int c, h, w;
-    if (d.input < 0) { c = in_c; h = in_h; w = in_w; }
-    else { const NetLayer& S = net->layers[d.input]; c = S.d.c_out; h = S.h_out; w = S.w_out; }
+    if (d.input < 0) { c = in_c; h = in_h; w = in_w; L.cp_in = net->in_cp; }
+    else { const NetLayer& S = net->layers[d.input]; c = S.d.c_out; h = S.h_out; w = S.w_out; L.cp_in = S.cp_out; }
     L.h_in = h; L.w_in = w;
     if (d.kind == CPRUNE_LAYER_FC) {
       if (d.c_in != c || d.c_out < 1 || !d.weight || !act_ok(d.act) || d.residual >= 0) { rc = CPRUNE_ERR_INVALID_ARG; break; }
+      if (h > 7 || w > 7) { rc = CPRUNE_ERR_UNSUPPORTED; break; }
       L.h_out = L.w_out = 1;
     } else if (d.kind == CPRUNE_LAYER_GAVGPOOL) {
       if (d.c_in != c || d.c_out != c) { rc = CPRUNE_ERR_INVALID_ARG; break; }
@@ -390,18 +417,25 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
       L.w_out = conv_out_dim(w, d.k, d.stride, d.pad);
       if (d.kind == CPRUNE_LAYER_MAXPOOL) {
         if (d.c_out != c || d.pad >= d.k) { rc = CPRUNE_ERR_INVALID_ARG; break; }
-      } else {
-        if (!d.weight) { rc = CPRUNE_ERR_INVALID_ARG; break; }
-        cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
-        rc = validate_conv_desc(&cd);
-        if (rc != CPRUNE_OK) break;
-      }
+      } else if (!d.weight) { rc = CPRUNE_ERR_INVALID_ARG; break; }
     } else { rc = CPRUNE_ERR_INVALID_ARG; break; }
+    if (d.kind == CPRUNE_LAYER_CONV || d.kind == CPRUNE_LAYER_FC) {
+      cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
+      rc = validate_conv_desc(&cd);
+      if (rc != CPRUNE_OK) break;
+    }
+    // pools keep their input's stride; a final 1x1 map is written dense for the caller
+    const bool last_dense = (i == n_layers - 1) && L.h_out * L.w_out == 1;
+    if (d.kind == CPRUNE_LAYER_MAXPOOL || d.kind == CPRUNE_LAYER_GAVGPOOL) L.cp_out = L.cp_in;
+    else L.cp_out = last_dense ? d.c_out : round_up_vec(d.c_out, dtype);
+    if (last_dense && L.cp_out != d.c_out) { rc = CPRUNE_ERR_UNSUPPORTED; break; }  // a pool cannot end a net densely
     if (d.residual >= 0) {
       const NetLayer& R = net->layers[d.residual];
-      if (d.kind != CPRUNE_LAYER_CONV || R.d.c_out != d.c_out || R.h_out != L.h_out || R.w_out != L.w_out) { rc = CPRUNE_ERR_INVALID_ARG; break; }
+      if (d.kind != CPRUNE_LAYER_CONV || R.d.c_out != d.c_out || R.h_out != L.h_out || R.w_out != L.w_out ||
+          R.cp_out != L.cp_out) { rc = CPRUNE_ERR_INVALID_ARG; break; }
     }
-    L.per_image = (size_t)d.c_out * L.h_out * L.w_out;
+    L.per_image = (size_t)L.cp_out * L.h_out * L.w_out;
+    if ((long)L.per_image * max_batch * (long)es >= lim || (long)L.cp_in * h * w * max_batch * (long)es >= lim) { rc = CPRUNE_ERR_UNSUPPORTED; break; }
   }
   if (rc != CPRUNE_OK) { net_free(net); return rc; }
 
@@ -411,26 +445,28 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     net->allocs.push_back(*p);
     return CPRUNE_OK;
   };
-  // weights, biases, activations, scratch
+  // weights (repacked channels-last), biases, activations, scratch
   for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
     NetLayer& L = net->layers[i];
     const cprune_layer_desc& d = L.d;
     if (d.kind == CPRUNE_LAYER_CONV || d.kind == CPRUNE_LAYER_FC) {
-      size_t nw;
-      if (d.kind == CPRUNE_LAYER_FC) nw = (size_t)d.c_out * d.c_in * L.h_in * L.w_in;
-      else nw = (size_t)d.c_out * (d.c_in / d.groups) * d.k * d.k;
+      const int khw = d.kind == CPRUNE_LAYER_FC ? L.h_in * L.w_in : d.k * d.k;
+      const bool dw = d.kind == CPRUNE_LAYER_CONV && d.groups != 1;
+      const size_t nw = (size_t)(dw ? 1 : d.c_out) * khw * L.cp_in;
+      if ((long)nw * (long)es >= lim) { rc = CPRUNE_ERR_UNSUPPORTED; break; }
       rc = dev_alloc(nw * es, &L.w);
       if (rc != CPRUNE_OK) break;
-      hipError_t e = hipMemcpyAsync(L.w, d.weight, nw * es, hipMemcpyDeviceToDevice, s);
-      if (e == hipSuccess && d.bias) {
+      rc = launch_repack_weights(d.weight, dw ? 1 : d.c_out, d.c_in, khw, L.cp_in, dtype, L.w, s);
+      if (rc != CPRUNE_OK) break;
+      if (d.bias) {
         rc = dev_alloc((size_t)d.c_out * sizeof(float), (void**)&L.b);
         if (rc != CPRUNE_OK) break;
-        e = hipMemcpyAsync(L.b, d.bias, (size_t)d.c_out * sizeof(float), hipMemcpyDeviceToDevice, s);
+        hipError_t e = hipMemcpyAsync(L.b, d.bias, (size_t)d.c_out * sizeof(float), hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
       }
-      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
-      if (d.groups == 1 || d.kind == CPRUNE_LAYER_FC) {
+      if (!dw) {
         cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
-        size_t need = conv_ws_bytes(cd, -1);
+        size_t need = conv_ws_bytes(cd, -1, layer_layout(L));
         if (need > net->ws_bytes) net->ws_bytes = need;
       }
     }
@@ -440,13 +476,12 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     hipError_t e = hipMemsetAsync(L.act, 0, abytes, s);
     if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
   }
-  void* scratch_in = nullptr;
   if (rc == CPRUNE_OK && net->ws_bytes) rc = dev_alloc(net->ws_bytes, &net->ws);
   if (rc == CPRUNE_OK) {
-    size_t ib = (size_t)max_batch * in_c * in_h * in_w * es;
-    rc = dev_alloc(ib, &scratch_in);
+    size_t ib = (size_t)max_batch * net->in_cp * in_h * in_w * es;
+    rc = dev_alloc(ib, &net->x_cl);
     if (rc == CPRUNE_OK) {
-      hipError_t e = hipMemsetAsync(scratch_in, 0, ib, s);
+      hipError_t e = hipMemsetAsync(net->x_cl, 0, ib, s);
       if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
     }
   }
@@ -455,12 +490,13 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     NetLayer& L = net->layers[i];
     if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) continue;
     cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
+    const ConvLayout lay = layer_layout(L);
     bool timed = false;
-    int v = cached_or_heuristic_variant(cd, &timed);
+    int v = cached_or_heuristic_variant(cd, &timed, lay);
     if (tune && !timed) {
-      const void* src = L.d.input < 0 ? scratch_in : net->layers[L.d.input].act;
+      const void* src = L.d.input < 0 ? net->x_cl : net->layers[L.d.input].act;
       const void* res = L.d.residual >= 0 ? net->layers[L.d.residual].act : nullptr;
-      rc = select_tile_impl(cd, src, L.w, L.b, res, L.act, net->ws, net->ws_bytes, 2, 6, &v, nullptr, nullptr, s);
+      rc = select_tile_impl(cd, src, L.w, L.b, res, L.act, net->ws, net->ws_bytes, 2, 6, &v, nullptr, nullptr, s, lay);
     }
     L.variant = v;
   }
@@ -515,11 +551,12 @@ extern "C" int cprune_net_layer_times(cprune_net* net, const void* x, int n, int
   }
   for (int i = 0; i < nl; ++i) ms_out[i] = 0.0f;
   net->last_n = n;
+  rc = rc == CPRUNE_OK ? launch_nchw_to_nhwc(x, n, net->in_c, net->in_h * net->in_w, net->in_cp, net->dtype, net->x_cl, s) : rc;
   for (int it = 0; it < iters && rc == CPRUNE_OK; ++it) {
     for (int i = 0; i < nl && rc == CPRUNE_OK; ++i) {
       hipError_t e = hipEventRecord(ev[i], s);
       if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
-      rc = net_run_layer(net, i, x, n, nullptr, s);
+      rc = net_run_layer(net, i, n, nullptr, s);
     }
     if (rc != CPRUNE_OK) break;
     hipError_t e = hipEventRecord(ev[nl], s);
@@ -540,10 +577,9 @@ extern "C" int cprune_net_copy_activation(cprune_net* net, int layer, int n, voi
   if (!net || !dst || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
   if (n < 1 || n > net->max_batch) return CPRUNE_ERR_INVALID_ARG;
   const NetLayer& L = net->layers[layer];
-  const size_t bytes = L.per_image * n * dtype_size(net->dtype);
+  const size_t bytes = (size_t)L.d.c_out * L.h_out * L.w_out * n * dtype_size(net->dtype);
   if (dst_bytes < bytes) return CPRUNE_ERR_INVALID_ARG;
-  CPRUNE_HIP_TRY(hipMemcpyAsync(dst, L.act, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream));
-  return CPRUNE_OK;
+  return launch_nhwc_to_nchw(L.act, n, L.d.c_out, L.h_out * L.w_out, L.cp_out, net->dtype, dst, (hipStream_t)stream);
 }
 
 extern "C" int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out) {

@@ -42,20 +42,43 @@ struct TileVariant {
 int num_variants();
 const TileVariant& variant(int id);
 
+// Memory layout a dense conv runs in.  nhwc = 0: NCHW activations / OIHW weights (the
+// boundary's layout).  nhwc = 1: channels-last inside a network handle, channel strides
+// cp_in / cp_out in elements (counts rounded up to one 16-byte vector, except a final
+// dense output), weights [c_out][kh][kw][cp_in].
+struct ConvLayout {
+  int nhwc = 0;
+  int cp_in = 0;
+  int cp_out = 0;
+};
+inline int round_up_vec(int c, int dt) { const int v = dt == CPRUNE_F32 ? 4 : 8; return (c + v - 1) / v * v; }
+
 int validate_conv_desc(const cprune_conv_desc* d);
-bool variant_supports(const cprune_conv_desc& d, int v);
-size_t conv_ws_bytes(const cprune_conv_desc& d, int v);
-int heuristic_variant(const cprune_conv_desc& d);
-int cached_or_heuristic_variant(const cprune_conv_desc& d, bool* timed);
-void remember_variant(const cprune_conv_desc& d, int v);
+bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay = ConvLayout());
+size_t conv_ws_bytes(const cprune_conv_desc& d, int v, const ConvLayout& lay = ConvLayout());
+int heuristic_variant(const cprune_conv_desc& d, const ConvLayout& lay = ConvLayout());
+int cached_or_heuristic_variant(const cprune_conv_desc& d, bool* timed, const ConvLayout& lay = ConvLayout());
+void remember_variant(const cprune_conv_desc& d, int v, const ConvLayout& lay = ConvLayout());
 
 // Launchers (no argument validation: callers have validated).
 int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, const float* bias,
-                      const void* residual, void* y, int v, void* ws, hipStream_t s);
+                      const void* residual, void* y, int v, void* ws, hipStream_t s,
+                      const ConvLayout& lay = ConvLayout());
 int launch_conv_depthwise(const cprune_conv_desc& d, const void* x, const void* w,
                           const float* bias, const void* residual, void* y, hipStream_t s);
 int launch_maxpool(const void* x, int n, int c, int h, int w, int k, int stride, int pad, int dt,
                    void* y, hipStream_t s);
 int launch_gavgpool(const void* x, int n, int c, int hw, int dt, void* y, hipStream_t s);
+
+// Channels-last layers of the network handle (cp = channel stride in elements).
+int launch_depthwise_nhwc(const cprune_conv_desc& d, int cp, const void* x, const void* w_khwc,
+                          const float* bias, const void* residual, void* y, hipStream_t s);
+int launch_maxpool_nhwc(const void* x, int n, int cp, int h, int w, int k, int stride, int pad, int dt,
+                        void* y, hipStream_t s);
+int launch_gavgpool_nhwc(const void* x, int n, int cp, int hw, int dt, void* y, hipStream_t s);
+int launch_nchw_to_nhwc(const void* x, int n, int c, int hw, int cp, int dt, void* y, hipStream_t s);
+int launch_nhwc_to_nchw(const void* x, int n, int c, int hw, int cp, int dt, void* y, hipStream_t s);
+// w [o][c][khw] -> [o][khw][cp] (zero pad); depthwise: o = 1 and c = channels gives [khw][cp]
+int launch_repack_weights(const void* w, int o, int c, int khw, int cp, int dt, void* y, hipStream_t s);
 
 }  // namespace cprune

@@ -59,6 +59,9 @@ struct ConvArgs {
   unsigned x_bytes, w_bytes;     // sizes of the x and w tensors (< 2^31)
   int act;
   int tiles_m, tiles_p;
+  int Cp, Cop;        // channels-last kernels: channel stride of x / of y (elements)
+  unsigned magic_cp;  // division by Cp
+  int vec_out;        // channels-last: y may be written 4 channels at a time
   int slabs;          // reduction slabs per output tile
   int units;          // tiles * slabs: the work, in slab iterations
   int units_per_wg;   // contiguous run of units each work-group takes

@@ -1,6 +1,6 @@
 // Host side of the dense convolution: the variant table (tile x scheduling
 // mode), what each variant supports and needs, and the launch.
-#include "conv_kernel.hpp"
+#include "conv_nhwc_kernel.hpp"
 
 namespace cprune {
 namespace {
@@ -29,11 +29,11 @@ struct Plan {
   bool fixup;
 };
 
-Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv) {
+Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv, const ConvLayout& lay) {
   Plan p;
   const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
   const long P = (long)d.n * ho * wo;
-  const int K = d.c_in * d.kh * d.kw;
+  const int K = (lay.nhwc ? lay.cp_in : d.c_in) * d.kh * d.kw;
   const int kt = slab_k(d.dtype, tv.kq);
   p.tiles_m = (d.c_out + tv.tile_m() - 1) / tv.tile_m();
   p.tiles_p = (int)((P + tv.tile_p() - 1) / tv.tile_p());
@@ -74,54 +74,58 @@ const TileVariant& variant(int id) {
   return table[id];
 }
 
-bool variant_supports(const cprune_conv_desc& d, int v) {
+bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
   if (v < 0 || v >= num_variants()) return false;
   if (d.groups != 1) return false;
   const TileVariant& tv = variant(v);
   const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
   const long P = (long)d.n * ho * wo;
-  const long K = (long)d.c_in * d.kh * d.kw;
+  const long K = (long)(lay.nhwc ? lay.cp_in : d.c_in) * d.kh * d.kw;
   const long kt = slab_k(d.dtype, tv.kq);
   const long units = ((d.c_out + tv.tile_m() - 1) / tv.tile_m()) * ((P + tv.tile_p() - 1) / tv.tile_p()) * ((K + kt - 1) / kt);
   return units < (1L << 30);
 }
 
-size_t conv_ws_bytes(const cprune_conv_desc& d, int v) {
+size_t conv_ws_bytes(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
   if (d.groups != 1) return 0;
   if (v >= 0) {
-    if (!variant_supports(d, v)) return 0;
+    if (!variant_supports(d, v, lay)) return 0;
     const TileVariant& tv = variant(v);
-    const Plan p = make_plan(d, tv);
+    const Plan p = make_plan(d, tv, lay);
     return p.fixup ? (size_t)2 * p.groups * tv.tile_m() * tv.tile_p() * sizeof(float) : 0;
   }
   size_t best = 0;
   for (int i = 0; i < num_variants(); ++i)
-    if (variant_supports(d, i)) {
-      size_t b = conv_ws_bytes(d, i);
+    if (variant_supports(d, i, lay)) {
+      size_t b = conv_ws_bytes(d, i, lay);
       if (b > best) best = b;
     }
   return best;
 }
 
 int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, const float* bias,
-                      const void* residual, void* y, int v, void* ws, hipStream_t s) {
+                      const void* residual, void* y, int v, void* ws, hipStream_t s, const ConvLayout& lay) {
   const TileVariant& tv = variant(v);
   const size_t es = dtype_size(d.dtype);
-  const Plan p = make_plan(d, tv);
+  const Plan p = make_plan(d, tv, lay);
   ConvArgs a;
   a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.partial = (float*)ws;
   a.N = d.n; a.C = d.c_in; a.H = d.h; a.W = d.w; a.O = d.c_out; a.KH = d.kh; a.KW = d.kw;
   a.stride = d.stride; a.pad = d.pad;
   a.Ho = conv_out_dim(d.h, d.kh, d.stride, d.pad);
   a.Wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
-  a.K = d.c_in * d.kh * d.kw;
+  a.K = (lay.nhwc ? lay.cp_in : d.c_in) * d.kh * d.kw;
+  a.Cp = lay.cp_in;
+  a.Cop = lay.cp_out;
+  a.magic_cp = magic_for((unsigned)lay.cp_in);
+  a.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
   a.HoWo = a.Ho * a.Wo;
   a.P = d.n * a.HoWo;
   a.HW = d.h * d.w;
   a.KHW = d.kh * d.kw;
   a.magic_khw = magic_for((unsigned)a.KHW);
   a.magic_kw = magic_for((unsigned)a.KW);
-  a.x_bytes = (unsigned)((size_t)d.n * d.c_in * d.h * d.w * es);
+  a.x_bytes = (unsigned)((size_t)d.n * (lay.nhwc ? lay.cp_in : d.c_in) * d.h * d.w * es);
   a.w_bytes = (unsigned)((size_t)d.c_out * a.K * es);
   a.act = d.act;
   a.tiles_m = p.tiles_m;
@@ -131,9 +135,15 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
   a.units_per_wg = p.units_per_wg;
   dim3 grid((unsigned)p.groups);
   const int tile = v / kNumScheds;
-  if (d.dtype == CPRUNE_F32) launch_conv_f32(tile, grid, s, a, p.fixup);
-  else if (d.dtype == CPRUNE_F16) launch_conv_f16(tile, grid, s, a, p.fixup);
-  else launch_conv_bf16(tile, grid, s, a, p.fixup);
+  if (lay.nhwc) {
+    if (d.dtype == CPRUNE_F32) launch_conv_nhwc_f32(tile, grid, s, a, p.fixup);
+    else if (d.dtype == CPRUNE_F16) launch_conv_nhwc_f16(tile, grid, s, a, p.fixup);
+    else launch_conv_nhwc_bf16(tile, grid, s, a, p.fixup);
+  } else {
+    if (d.dtype == CPRUNE_F32) launch_conv_f32(tile, grid, s, a, p.fixup);
+    else if (d.dtype == CPRUNE_F16) launch_conv_f16(tile, grid, s, a, p.fixup);
+    else launch_conv_bf16(tile, grid, s, a, p.fixup);
+  }
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }

@@ -1,0 +1,10 @@
+// Instantiations of the channels-last implicit-GEMM convolution kernel for float data.
+#include "conv_nhwc_kernel.hpp"
+
+namespace cprune {
+
+void launch_conv_nhwc_f32(int tile, dim3 grid, hipStream_t s, const ConvArgs& a, bool fixup) {
+  launch_tile_nhwc<float>(tile, grid, s, a, fixup);
+}
+
+}  // namespace cprune

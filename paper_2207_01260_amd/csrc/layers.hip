@@ -96,6 +96,124 @@ __global__ __launch_bounds__(256) void gavgpool_kernel(const T* __restrict__ x, 
   if (lane == 0) st(y + plane, s / (float)hw);
 }
 
+// ---- channels-last twins used inside the network handle ------------------------
+// One thread per output element, consecutive threads on consecutive channels of a
+// pixel (the contiguous direction of [n][h][w][cp]); pad channels carry zeros.
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                           long total, int cp, int h, int wd, int ho, int wo,
+                                                           int k, int stride, int pad) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % cp);
+  long pix = i / cp;
+  const int ox = (int)(pix % wo); pix /= wo;
+  const int oy = (int)(pix % ho);
+  const long n = pix / ho;
+  const int iy0 = oy * stride - pad, ix0 = ox * stride - pad;
+  float m = 0.0f;
+  bool have = false;
+  for (int u = 0; u < k; ++u) {
+    const int iy = iy0 + u;
+    if ((unsigned)iy >= (unsigned)h) continue;
+    for (int v = 0; v < k; ++v) {
+      const int ix = ix0 + v;
+      if ((unsigned)ix >= (unsigned)wd) continue;
+      const float val = ld(x + ((n * h + iy) * wd + ix) * cp + c);
+      if (!have || val > m) { m = val; have = true; }
+    }
+  }
+  st(y + i, m);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gavgpool_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                            int total, int cp, int hw) {
+  const int i = blockIdx.x * 256 + threadIdx.x;  // (n, c)
+  if (i >= total) return;
+  const int c = i % cp;
+  const long n = i / cp;
+  const T* xp = x + n * hw * cp + c;
+  float s = 0.0f;
+  for (int p = 0; p < hw; ++p) s += ld(xp + (long)p * cp);
+  st(y + i, s / (float)hw);
+}
+
+template <typename T, int K>
+__global__ __launch_bounds__(256) void depthwise_nhwc_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                             const float* __restrict__ bias,
+                                                             const T* __restrict__ res, T* __restrict__ y,
+                                                             long total, int c_real, int cp, int h, int wd,
+                                                             int ho, int wo, int stride, int pad, int act) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % cp);
+  long pix = i / cp;
+  const int ox = (int)(pix % wo); pix /= wo;
+  const int oy = (int)(pix % ho);
+  const long n = pix / ho;
+  const int iy0 = oy * stride - pad, ix0 = ox * stride - pad;
+  float acc = 0.0f;
+#pragma unroll
+  for (int u = 0; u < K; ++u) {
+    const int iy = iy0 + u;
+    if ((unsigned)iy >= (unsigned)h) continue;
+#pragma unroll
+    for (int v = 0; v < K; ++v) {
+      const int ix = ix0 + v;
+      if ((unsigned)ix < (unsigned)wd)
+        acc += ld(x + ((n * h + iy) * wd + ix) * cp + c) * ld(w + (u * K + v) * cp + c);
+    }
+  }
+  if (bias && c < c_real) acc += bias[c];
+  if (res) acc += ld(res + i);
+  st(y + i, act_f(acc, act));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void nchw_to_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                           long total, int c, int hw, int cp) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int ch = (int)(i % cp);
+  const long pix = i / cp;
+  const long n = pix / hw;
+  const int p = (int)(pix - n * hw);
+  T v = (T)0.0f;
+  if (ch < c) v = x[(n * c + ch) * hw + p];
+  y[i] = v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void nhwc_to_nchw_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                           long total, int c, int hw, int cp) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;  // index into dense [n][c][hw]
+  if (i >= total) return;
+  const int p = (int)(i % hw);
+  const long nc = i / hw;
+  const int ch = (int)(nc % c);
+  const long n = nc / c;
+  y[i] = x[(n * hw + p) * cp + ch];
+}
+
+// [o][c][khw] -> [o][khw][cp], zero in the pad channels
+template <typename T>
+__global__ __launch_bounds__(256) void repack_weights_kernel(const T* __restrict__ w, T* __restrict__ y,
+                                                             long total, int c, int khw, int cp) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int ch = (int)(i % cp);
+  const long ot = i / cp;
+  const int tpos = (int)(ot % khw);
+  const long o = ot / khw;
+  T v = (T)0.0f;
+  if (ch < c) v = w[(o * c + ch) * khw + tpos];
+  y[i] = v;
+}
+
+inline dim3 blocks_for(long total) { return dim3((unsigned)((total + 255) / 256)); }
+
 int plane_slices(int total) {
   int s = (total + 1023) / 1024;
   return s < 1 ? 1 : (s > 64 ? 64 : s);
@@ -160,6 +278,84 @@ int launch_gavgpool(const void* x, int n, int c, int hw, int dt, void* y, hipStr
   else
     hipLaunchKernelGGL(gavgpool_kernel<__bf16>, grid, dim3(256), 0, s, (const __bf16*)x, (__bf16*)y,
                        planes, hw);
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+#define CPRUNE_BY_DTYPE(DT, CALL)                      \
+  do {                                                  \
+    if ((DT) == CPRUNE_F32) { typedef float T; CALL; }  \
+    else if ((DT) == CPRUNE_F16) { typedef _Float16 T; CALL; } \
+    else { typedef __bf16 T; CALL; }                    \
+  } while (0)
+
+int launch_maxpool_nhwc(const void* x, int n, int cp, int h, int w, int k, int stride, int pad, int dt,
+                        void* y, hipStream_t s) {
+  const int ho = conv_out_dim(h, k, stride, pad), wo = conv_out_dim(w, k, stride, pad);
+  const long total = (long)n * ho * wo * cp;
+  CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(maxpool_nhwc_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)x,
+                                         (T*)y, total, cp, h, w, ho, wo, k, stride, pad));
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+int launch_gavgpool_nhwc(const void* x, int n, int cp, int hw, int dt, void* y, hipStream_t s) {
+  const int total = n * cp;
+  CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(gavgpool_nhwc_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)x,
+                                         (T*)y, total, cp, hw));
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+template <typename T>
+static int depthwise_nhwc_dispatch(const cprune_conv_desc& d, int cp, const void* x, const void* w,
+                                   const float* bias, const void* res, void* y, hipStream_t s) {
+  const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
+  const long total = (long)d.n * ho * wo * cp;
+#define GO(K)                                                                                          \
+  hipLaunchKernelGGL((depthwise_nhwc_kernel<T, K>), blocks_for(total), dim3(256), 0, s, (const T*)x,   \
+                     (const T*)w, bias, (const T*)res, (T*)y, total, d.c_in, cp, d.h, d.w, ho, wo,     \
+                     d.stride, d.pad, d.act)
+  switch (d.kh) {
+    case 1: GO(1); break;
+    case 3: GO(3); break;
+    case 5: GO(5); break;
+    case 7: GO(7); break;
+    default: return CPRUNE_ERR_UNSUPPORTED;
+  }
+#undef GO
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+int launch_depthwise_nhwc(const cprune_conv_desc& d, int cp, const void* x, const void* w, const float* bias,
+                          const void* residual, void* y, hipStream_t s) {
+  if (d.kh != d.kw) return CPRUNE_ERR_UNSUPPORTED;
+  if (d.dtype == CPRUNE_F32) return depthwise_nhwc_dispatch<float>(d, cp, x, w, bias, residual, y, s);
+  if (d.dtype == CPRUNE_F16) return depthwise_nhwc_dispatch<_Float16>(d, cp, x, w, bias, residual, y, s);
+  return depthwise_nhwc_dispatch<__bf16>(d, cp, x, w, bias, residual, y, s);
+}
+
+int launch_nchw_to_nhwc(const void* x, int n, int c, int hw, int cp, int dt, void* y, hipStream_t s) {
+  const long total = (long)n * hw * cp;
+  CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(nchw_to_nhwc_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)x,
+                                         (T*)y, total, c, hw, cp));
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+int launch_nhwc_to_nchw(const void* x, int n, int c, int hw, int cp, int dt, void* y, hipStream_t s) {
+  const long total = (long)n * c * hw;
+  CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(nhwc_to_nchw_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)x,
+                                         (T*)y, total, c, hw, cp));
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+int launch_repack_weights(const void* w, int o, int c, int khw, int cp, int dt, void* y, hipStream_t s) {
+  const long total = (long)o * khw * cp;
+  CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_weights_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w,
+                                         (T*)y, total, c, khw, cp));
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }
