@@ -119,7 +119,10 @@ typedef struct {
  * output pixels) and a scheduling mode.  sched 0: one output tile per work-group.
  * sched n > 0: the (tile, reduction slab) work is laid out in one line and cut
  * into equal runs for n * 256 work-groups; tiles cut between runs go through the
- * caller's scratch and are summed in run order (deterministic).  Ids are 0..n-1
+ * caller's scratch and are summed in run order (deterministic).  sched -1: kernels that
+ * exist only for the channels-last layout inside a network handle (3x3 stride-1 layers,
+ * one tile_p-pixel spatial block per work-group); unsupported through this NCHW call.
+ * Ids are 0..n-1
  * and the same for every shape; a variant that cannot run a given shape is
  * CPRUNE_ERR_UNSUPPORTED. */
 int cprune_num_tile_variants(void);

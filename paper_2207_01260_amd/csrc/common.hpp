@@ -35,7 +35,9 @@ struct TileVariant {
   int wm, wn;   // waves along output channels / pixels (wm * wn == 4)
   int mb, nb;   // 16x16 MFMA blocks per wave along channels / pixels
   int kq;       // MFMA rounds (64 bytes of k per row each) per slab
-  int sched;  // scheduling mode: 0 = one tile per work-group, n = runs for n * 256 groups
+  int sched;    // scheduling mode: 0 = one tile per work-group, n = runs for n * 256 groups,
+                // -1 = 3x3 spatial-patch kernel (one th x tw pixel block per work-group)
+  int th = 0, tw = 0, patch_id = -1;
   int tile_m() const { return wm * mb * 16; }
   int tile_p() const { return wn * nb * 16; }
 };

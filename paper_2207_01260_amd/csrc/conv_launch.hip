@@ -1,6 +1,6 @@
 // Host side of the dense convolution: the variant table (tile x scheduling
 // mode), what each variant supports and needs, and the launch.
-#include "conv_nhwc_kernel.hpp"
+#include "conv_patch_kernel.hpp"
 
 namespace cprune {
 namespace {
@@ -58,12 +58,20 @@ Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv, const ConvLayou
 
 }  // namespace
 
-int num_variants() { return kNumTiles * kNumScheds; }
+int num_variants() { return kNumTiles * kNumScheds + kNumPatch; }
 
 const TileVariant& variant(int id) {
-  static TileVariant table[kNumTiles * kNumScheds];
+  static TileVariant table[kNumTiles * kNumScheds + kNumPatch];
   static bool init = false;
   if (!init) {
+#define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_)                                   \
+    {                                                                         \
+      TileVariant& pv = table[kNumTiles * kNumScheds + ID];                   \
+      pv.wm = 1; pv.wn = 4; pv.mb = MB_; pv.nb = (TH_ * TW_) / 64; pv.kq = 1; \
+      pv.sched = -1; pv.th = TH_; pv.tw = TW_; pv.patch_id = ID;              \
+    }
+    CPRUNE_PATCH_LIST(CPRUNE_PATCH_ROW)
+#undef CPRUNE_PATCH_ROW
     for (int t = 0; t < kNumTiles; ++t)
       for (int s = 0; s < kNumScheds; ++s) {
         table[t * kNumScheds + s] = kTiles[t];
@@ -78,6 +86,8 @@ bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
   if (v < 0 || v >= num_variants()) return false;
   if (d.groups != 1) return false;
   const TileVariant& tv = variant(v);
+  if (tv.sched < 0)
+    return lay.nhwc && d.kh == 3 && d.kw == 3 && d.stride == 1 && d.pad == 1;
   const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
   const long P = (long)d.n * ho * wo;
   const long K = (long)(lay.nhwc ? lay.cp_in : d.c_in) * d.kh * d.kw;
@@ -91,6 +101,7 @@ size_t conv_ws_bytes(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
   if (v >= 0) {
     if (!variant_supports(d, v, lay)) return 0;
     const TileVariant& tv = variant(v);
+    if (tv.sched < 0) return 0;
     const Plan p = make_plan(d, tv, lay);
     return p.fixup ? (size_t)2 * p.groups * tv.tile_m() * tv.tile_p() * sizeof(float) : 0;
   }
@@ -107,6 +118,24 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
                       const void* residual, void* y, int v, void* ws, hipStream_t s, const ConvLayout& lay) {
   const TileVariant& tv = variant(v);
   const size_t es = dtype_size(d.dtype);
+  if (tv.sched < 0) {
+    PatchArgs pa;
+    pa.x = x; pa.w = w; pa.bias = bias; pa.res = residual; pa.y = y;
+    pa.N = d.n; pa.H = d.h; pa.W = d.w; pa.O = d.c_out; pa.Cp = lay.cp_in; pa.Cop = lay.cp_out;
+    pa.tiles_y = (d.h + tv.th - 1) / tv.th;
+    pa.tiles_x = (d.w + tv.tw - 1) / tv.tw;
+    pa.tiles_m = (d.c_out + tv.tile_m() - 1) / tv.tile_m();
+    pa.x_bytes = (unsigned)((size_t)d.n * lay.cp_in * d.h * d.w * es);
+    pa.w_bytes = (unsigned)((size_t)d.c_out * 9 * lay.cp_in * es);
+    pa.act = d.act;
+    pa.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
+    dim3 pgrid((unsigned)(d.n * pa.tiles_y * pa.tiles_x * pa.tiles_m));
+    if (d.dtype == CPRUNE_F32) launch_conv_patch_f32(tv.patch_id, pgrid, s, pa);
+    else if (d.dtype == CPRUNE_F16) launch_conv_patch_f16(tv.patch_id, pgrid, s, pa);
+    else launch_conv_patch_bf16(tv.patch_id, pgrid, s, pa);
+    CPRUNE_LAUNCH_CHECK();
+    return CPRUNE_OK;
+  }
   const Plan p = make_plan(d, tv, lay);
   ConvArgs a;
   a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.partial = (float*)ws;
@@ -134,7 +163,7 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
   a.units = p.units;
   a.units_per_wg = p.units_per_wg;
   dim3 grid((unsigned)p.groups);
-  const int tile = v / kNumScheds;
+  const int tile = v / kNumScheds;  // implicit-GEMM variants come first in the table
   if (lay.nhwc) {
     if (d.dtype == CPRUNE_F32) launch_conv_nhwc_f32(tile, grid, s, a, p.fixup);
     else if (d.dtype == CPRUNE_F16) launch_conv_nhwc_f16(tile, grid, s, a, p.fixup);

@@ -1,0 +1,225 @@
+// 3x3 / stride 1 / pad 1 convolution, channels-last, with the input staged as a
+// spatial patch: the shape almost every layer of the evaluated networks has
+// (all of VGG-16, the 3x3 layers of ResNet-18, the channel-sweep layer).
+//
+// In the implicit-GEMM kernel the B tile is an im2col tile, so every input
+// element crosses L2 -> LDS nine times (once per tap).  Here a work-group owns a
+// TH x TW block of output pixels of one image and MT filters; per chunk of 16
+// bytes x 4 of channels it stages the (TH+2) x (TW+2) input patch ONCE, plus the
+// [MT][9 taps][chunk] slice of the weights, and the nine taps are nine shifted
+// views of the same patch: the B operand of tap (u, v) for output pixel (y, x)
+// is the 16-byte quad at patch pixel (y + u, x + v), a compile-time offset from
+// the lane's own pixel.  Staged bytes per MFMA drop ~3x against 64x64 im2col
+// tiles, which is what small pruned filter counts need (few filters = little
+// reuse of each staged input element).
+//
+// Same MFMA blocks and k-permutation as conv_nhwc_kernel (lane group g4 holds
+// channels 4*g4..4*g4+3 of the chunk for both operands).  4 wavefronts split the
+// pixels; each owns MB x NB accumulator blocks (NB blocks of 16 pixels = rows of
+// the tile when TW = 16, row pairs when TW = 8).  One LDS buffer: while a chunk
+// is multiplied, the next one is already in flight into registers.
+#pragma once
+#include "conv_nhwc_kernel.hpp"
+
+namespace cprune {
+
+struct PatchArgs {
+  const void* x;
+  const void* w;
+  const float* bias;
+  const void* res;
+  void* y;
+  int N, H, W, O, Cp, Cop;
+  int tiles_y, tiles_x, tiles_m;
+  unsigned x_bytes, w_bytes;
+  int act, vec_out;
+};
+
+template <typename T, int MB, int TH, int TW>
+__global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
+  constexpr int ES = (int)sizeof(T);
+  constexpr int EPI = 16 / ES;            // elements per quad
+  constexpr int CC = 4 * EPI;             // channels per chunk (64 bytes)
+  constexpr int PT = TH * TW;             // output pixels per tile
+  constexpr int NB = PT / 64;             // 16-pixel blocks per wave
+  constexpr int MT = MB * 16;
+  constexpr int PW = TW + 2, PH = TH + 2;
+  constexpr int NPATCH = PH * PW;
+  constexpr int BROW = 80;                // patch pixel: 64 bytes of channels + 16 pad
+  constexpr int AROW = 9 * 64 + 16;       // filter row: 9 taps x 64 bytes + 16 pad
+  constexpr int NIB = (NPATCH * 4 + 255) / 256;
+  constexpr int NIA = (MT * 36 + 255) / 256;
+  static_assert(PT % 64 == 0 && (TW == 8 || TW == 16), "tile shape");
+
+  __shared__ __attribute__((aligned(16))) unsigned char sA[MT * AROW];
+  __shared__ __attribute__((aligned(16))) unsigned char sB[NPATCH * BROW];
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = t >> 6;
+  const int r = lane & 15, g4 = lane >> 4;
+
+  // tile decode: filters fastest, so neighbouring groups share the patch in L2
+  int tile;
+  {
+    const int G = gridDim.x;
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int q = G >> 3, rem = G & 7;
+    tile = xcd * q + (xcd < rem ? xcd : rem) + local;
+  }
+  const int tile_m = tile % a.tiles_m;
+  int rest = tile / a.tiles_m;
+  const int tx0 = (rest % a.tiles_x) * TW;
+  rest /= a.tiles_x;
+  const int ty0 = (rest % a.tiles_y) * TH;
+  const int n = rest / a.tiles_y;
+  const int o0 = tile_m * MT;
+
+  const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);
+  const __amdgpu_buffer_rsrc_t wr = make_rsrc(a.w, a.w_bytes);
+
+  // ---- staging items ----
+  unsigned b_off[NIB];   // byte offset of (patch pixel, quad) at chunk 0, kOutOfRange outside the image
+  int b_lds[NIB], b_q[NIB];
+#pragma unroll
+  for (int j = 0; j < NIB; ++j) {
+    const int idx = t + 256 * j;
+    const int q = idx & 3, pp = idx >> 2;
+    const bool item = pp < NPATCH;
+    const int py = pp / PW, px = pp - py * PW;
+    const int iy = ty0 + py - 1, ix = tx0 + px - 1;
+    const bool inside = item && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+    b_off[j] = inside ? (unsigned)(((n * a.H + iy) * a.W + ix) * a.Cp + q * EPI) * ES : kOutOfRange;
+    b_lds[j] = item ? pp * BROW + q * 16 : -1;
+    b_q[j] = q;
+  }
+  unsigned a_off[NIA];   // byte offset of (filter, tap, quad) at chunk 0
+  int a_lds[NIA], a_q[NIA];
+#pragma unroll
+  for (int j = 0; j < NIA; ++j) {
+    const int idx = t + 256 * j;
+    const int q = idx & 3;
+    const int tap = (idx >> 2) % 9;
+    const int m = (idx >> 2) / 9;
+    const bool item = m < MT;
+    const int o = o0 + m;
+    a_off[j] = (item && o < a.O) ? (unsigned)((o * 9 + tap) * a.Cp + q * EPI) * ES : kOutOfRange;
+    a_lds[j] = item ? m * AROW + tap * 64 + q * 16 : -1;
+    a_q[j] = q;
+  }
+
+  uint4 breg[NIB], areg[NIA];
+  auto gload = [&](int c0) {   // c0: first channel of the chunk
+    const unsigned soff = (unsigned)(c0 * ES);
+#pragma unroll
+    for (int j = 0; j < NIA; ++j) {
+      const unsigned inval = (unsigned)(c0 + a_q[j] * EPI >= a.Cp) << 31;
+      areg[j] = load_b128(wr, a_off[j] | inval, soff);
+    }
+#pragma unroll
+    for (int j = 0; j < NIB; ++j) {
+      const unsigned inval = (unsigned)(c0 + b_q[j] * EPI >= a.Cp) << 31;
+      breg[j] = load_b128(xr, b_off[j] | inval, soff);
+    }
+  };
+  auto lds_store = [&]() {
+#pragma unroll
+    for (int j = 0; j < NIA; ++j)
+      if (a_lds[j] >= 0) *(uint4*)&sA[a_lds[j]] = areg[j];
+#pragma unroll
+    for (int j = 0; j < NIB; ++j)
+      if (b_lds[j] >= 0) *(uint4*)&sB[b_lds[j]] = breg[j];
+  };
+
+  // ---- fragment addresses: lane's pixel inside the patch (tap (0,0) corner) ----
+  int b_frag[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int id = wave * (NB * 16) + j * 16 + r;
+    const int ty = id / TW, tx = id % TW;
+    b_frag[j] = (ty * PW + tx) * BROW + g4 * 16;
+  }
+  const int a_frag = r * AROW + g4 * 16;
+
+  float4_t acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) acc[i][j] = (float4_t){0.f, 0.f, 0.f, 0.f};
+
+  int mb_count = (a.O - o0 + 15) / 16;
+  mb_count = mb_count > MB ? MB : mb_count;
+
+  const int nchunk = (a.Cp + CC - 1) / CC;
+  auto main_loop = [&](auto mbc_tag) {
+    constexpr int MBC = decltype(mbc_tag)::value;
+    gload(0);
+    for (int c = 0; c < nchunk; ++c) {
+      __syncthreads();            // everyone is done reading the previous chunk
+      lds_store();
+      __syncthreads();
+      if (c + 1 < nchunk) gload((c + 1) * CC);
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        constexpr int dummy = 0; (void)dummy;
+        const int boff = ((tap / 3) * PW + (tap % 3)) * BROW;
+        uint4 af[MB], bf[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) bf[j] = *(const uint4*)&sB[b_frag[j] + boff];
+#pragma unroll
+        for (int i = 0; i < MBC; ++i) af[i] = *(const uint4*)&sA[a_frag + i * 16 * AROW + tap * 64];
+        mma_slab<T, MBC, NB, MB>(af, bf, acc);
+      }
+    }
+  };
+  switch (mb_count) {
+#define CPRUNE_MBC_CASE(V) \
+  case V: if constexpr (MB >= V) main_loop(std::integral_constant<int, V>{}); break;
+    CPRUNE_MBC_CASE(1) CPRUNE_MBC_CASE(2) CPRUNE_MBC_CASE(3) CPRUNE_MBC_CASE(4)
+    CPRUNE_MBC_CASE(5) CPRUNE_MBC_CASE(6) CPRUNE_MBC_CASE(7) CPRUNE_MBC_CASE(8)
+#undef CPRUNE_MBC_CASE
+    default: break;
+  }
+
+  // ---- epilogue ----
+  ConvArgs e;
+  e.bias = a.bias; e.res = a.res; e.y = a.y; e.O = a.O; e.Cop = a.Cop; e.act = a.act; e.vec_out = a.vec_out;
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int id = wave * (NB * 16) + j * 16 + r;
+    const int oy = ty0 + id / TW, ox = tx0 + id % TW;
+    if (oy >= a.H || ox >= a.W) continue;
+    const int p = (n * a.H + oy) * a.W + ox;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) nhwc_store4<T>(e, acc[i][j], p, o0 + i * 16 + 4 * g4);
+  }
+}
+
+// Patch variants: id, mb, th, tw
+#define CPRUNE_PATCH_LIST(X) \
+  X(0, 1, 8, 8)   \
+  X(1, 2, 8, 8)   \
+  X(2, 4, 8, 8)   \
+  X(3, 2, 8, 16)  \
+  X(4, 4, 8, 16)  \
+  X(5, 2, 16, 16) \
+  X(6, 4, 16, 16) \
+  X(7, 1, 16, 16)
+
+constexpr int kNumPatch = 8;
+
+template <typename T>
+inline void launch_patch(int id, dim3 grid, hipStream_t s, const PatchArgs& a) {
+#define CPRUNE_PATCH_CASE(ID, MB_, TH_, TW_)                                                  \
+  case ID:                                                                                    \
+    hipLaunchKernelGGL((conv_patch_kernel<T, MB_, TH_, TW_>), grid, dim3(256), 0, s, a);      \
+    break;
+  switch (id) { CPRUNE_PATCH_LIST(CPRUNE_PATCH_CASE) }
+#undef CPRUNE_PATCH_CASE
+}
+
+void launch_conv_patch_f32(int id, dim3 grid, hipStream_t s, const PatchArgs& a);
+void launch_conv_patch_f16(int id, dim3 grid, hipStream_t s, const PatchArgs& a);
+void launch_conv_patch_bf16(int id, dim3 grid, hipStream_t s, const PatchArgs& a);
+
+}  // namespace cprune
