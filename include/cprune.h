@@ -221,7 +221,8 @@ int cprune_net_layer_times(cprune_net* net, const void* x, int n, int iters, flo
 /* Writes layer `layer`'s activation of the last forward (batch n) to dst (device) as dense
  * NCHW [n][c_out][h_out][w_out].  For the last layer of a net whose output map is 1x1 the
  * values are those of the last cprune_net_layer_times pass (forward writes that layer
- * straight into `logits`). */
+ * straight into `logits`).  A conv layer whose following 2x2 max-pool was fused into its
+ * epilogue has no activation of its own: CPRUNE_ERR_UNSUPPORTED (ask for the pool layer). */
 int cprune_net_copy_activation(cprune_net* net, int layer, int n, void* dst, size_t dst_bytes,
                                void* stream);
 /* The tile variant in use for layer `layer` (-1 for layers without one); host out. */

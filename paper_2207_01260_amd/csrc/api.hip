@@ -40,10 +40,10 @@ int validate_conv_desc(const cprune_conv_desc* d) {
 }
 
 // ---- variant cache -------------------------------------------------------------
-typedef std::array<int, 16> DescKey;
+typedef std::array<int, 17> DescKey;
 static DescKey key_of(const cprune_conv_desc& d, const ConvLayout& lay) {
   return DescKey{d.n, d.c_in, d.h, d.w, d.c_out, d.kh, d.kw, d.stride, d.pad, d.groups, d.dtype, d.act,
-                 d.has_residual, lay.nhwc, lay.cp_in, lay.cp_out};
+                 d.has_residual, lay.nhwc, lay.cp_in, lay.cp_out, lay.pool};
 }
 static std::mutex g_cache_mutex;
 static std::map<DescKey, int> g_cache;
@@ -74,6 +74,9 @@ int heuristic_variant(const cprune_conv_desc& d, const ConvLayout& lay) {
     const double score = reuse * fill;
     if (score > best) { best = score; best_v = v; }
   }
+  if (best < 0.0)  // nothing among the cut-run variants (a fused pool needs a patch kernel): first that runs
+    for (int v = 0; v < num_variants(); ++v)
+      if (variant_supports(d, v, lay)) return v;
   return best_v;
 }
 
@@ -292,6 +295,8 @@ struct NetLayer {
   void* act = nullptr;        // [max_batch][h_out][w_out][cp_out]
   size_t per_image = 0;       // elements per image of the output buffer
   int variant = -1;           // dense conv / fc: variant for max_batch
+  bool fused_pool = false;    // conv: the 2x2 max-pool that follows runs in its epilogue; act is the pooled map
+  bool alias = false;         // max-pool folded into its producer: no kernel, act is the producer's buffer
 };
 
 struct GraphKey {
@@ -331,7 +336,7 @@ static cprune_conv_desc layer_conv_desc(const cprune_net& net, const NetLayer& L
 
 static ConvLayout layer_layout(const NetLayer& L) {
   ConvLayout lay;
-  lay.nhwc = 1; lay.cp_in = L.cp_in; lay.cp_out = L.cp_out;
+  lay.nhwc = 1; lay.cp_in = L.cp_in; lay.cp_out = L.cp_out; lay.pool = L.fused_pool ? 1 : 0;
   return lay;
 }
 
@@ -357,6 +362,7 @@ static int net_run_layer(cprune_net* net, int i, int n, void* out_override, hipS
       return conv_dispatch(d, src, L.w, L.b, res, dst, v, net->ws, net->ws_bytes, s, lay);
     }
     case CPRUNE_LAYER_MAXPOOL:
+      if (L.alias) return CPRUNE_OK;
       return launch_maxpool_nhwc(src, n, L.cp_in, L.h_in, L.w_in, L.d.k, L.d.stride, L.d.pad, net->dtype, dst, s);
     case CPRUNE_LAYER_GAVGPOOL:
       return launch_gavgpool_nhwc(src, n, L.cp_in, L.h_in * L.w_in, net->dtype, dst, s);
@@ -439,6 +445,25 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
   }
   if (rc != CPRUNE_OK) { net_free(net); return rc; }
 
+  // A 2x2 / stride 2 max-pool whose only producer is a plain 3x3 stride-1 conv that nobody
+  // else reads runs in that conv's epilogue: one launch and one round trip through HBM less.
+  for (int i = 0; i < n_layers; ++i) {
+    NetLayer& Pl = net->layers[i];
+    const cprune_layer_desc& pd = Pl.d;
+    if (pd.kind != CPRUNE_LAYER_MAXPOOL || pd.k != 2 || pd.stride != 2 || pd.pad != 0 || pd.input < 0) continue;
+    NetLayer& Cv = net->layers[pd.input];
+    const cprune_layer_desc& cd = Cv.d;
+    if (cd.kind != CPRUNE_LAYER_CONV || cd.groups != 1 || cd.k != 3 || cd.stride != 1 || cd.pad != 1 || cd.residual >= 0) continue;
+    if ((Cv.h_out & 1) || (Cv.w_out & 1) || i == n_layers - 1) continue;
+    bool shared = false;
+    for (int j = 0; j < n_layers; ++j)
+      if (j != i && (net->layers[j].d.input == pd.input || net->layers[j].d.residual == pd.input)) shared = true;
+    if (shared) continue;
+    Cv.fused_pool = true;
+    Cv.per_image = (size_t)Cv.cp_out * Pl.h_out * Pl.w_out;
+    Pl.alias = true;
+  }
+
   auto dev_alloc = [&](size_t bytes, void** p) -> int {
     hipError_t e = hipMalloc(p, bytes ? bytes : 16);
     if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
@@ -470,6 +495,7 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
         if (need > net->ws_bytes) net->ws_bytes = need;
       }
     }
+    if (L.alias) { L.act = net->layers[d.input].act; continue; }
     const size_t abytes = L.per_image * max_batch * es;
     rc = dev_alloc(abytes, &L.act);
     if (rc != CPRUNE_OK) break;
@@ -577,6 +603,7 @@ extern "C" int cprune_net_copy_activation(cprune_net* net, int layer, int n, voi
   if (!net || !dst || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
   if (n < 1 || n > net->max_batch) return CPRUNE_ERR_INVALID_ARG;
   const NetLayer& L = net->layers[layer];
+  if (L.fused_pool) return CPRUNE_ERR_UNSUPPORTED;  // only the pooled map exists: ask for the pool layer
   const size_t bytes = (size_t)L.d.c_out * L.h_out * L.w_out * n * dtype_size(net->dtype);
   if (dst_bytes < bytes) return CPRUNE_ERR_INVALID_ARG;
   return launch_nhwc_to_nchw(L.act, n, L.d.c_out, L.h_out * L.w_out, L.cp_out, net->dtype, dst, (hipStream_t)stream);

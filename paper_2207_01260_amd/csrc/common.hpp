@@ -37,7 +37,7 @@ struct TileVariant {
   int kq;       // MFMA rounds (64 bytes of k per row each) per slab
   int sched;    // scheduling mode: 0 = one tile per work-group, n = runs for n * 256 groups,
                 // -1 = 3x3 spatial-patch kernel (one th x tw pixel block per work-group)
-  int th = 0, tw = 0, patch_id = -1;
+  int th = 0, tw = 0, ni = 1, patch_id = -1;
   int tile_m() const { return wm * mb * 16; }
   int tile_p() const { return wn * nb * 16; }
 };
@@ -52,6 +52,7 @@ struct ConvLayout {
   int nhwc = 0;
   int cp_in = 0;
   int cp_out = 0;
+  int pool = 0;  // channels-last 3x3 layers: a 2x2/2 max-pool fused behind the activation
 };
 inline int round_up_vec(int c, int dt) { const int v = dt == CPRUNE_F32 ? 4 : 8; return (c + v - 1) / v * v; }
 

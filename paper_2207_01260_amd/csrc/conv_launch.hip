@@ -64,10 +64,10 @@ const TileVariant& variant(int id) {
   static TileVariant table[kNumTiles * kNumScheds + kNumPatch];
   static bool init = false;
   if (!init) {
-#define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_)                                   \
+#define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_)                                 \
     {                                                                         \
       TileVariant& pv = table[kNumTiles * kNumScheds + ID];                   \
-      pv.wm = 1; pv.wn = 4; pv.mb = MB_; pv.nb = (TH_ * TW_) / 64; pv.kq = 1; \
+      pv.wm = 1; pv.wn = 4; pv.mb = MB_; pv.nb = (TH_ * TW_ * NI_) / 64; pv.kq = 1; pv.ni = NI_; \
       pv.sched = -1; pv.th = TH_; pv.tw = TW_; pv.patch_id = ID;              \
     }
     CPRUNE_PATCH_LIST(CPRUNE_PATCH_ROW)
@@ -86,8 +86,14 @@ bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
   if (v < 0 || v >= num_variants()) return false;
   if (d.groups != 1) return false;
   const TileVariant& tv = variant(v);
-  if (tv.sched < 0)
-    return lay.nhwc && d.kh == 3 && d.kw == 3 && d.stride == 1 && d.pad == 1;
+  if (tv.sched < 0) {
+    if (!(lay.nhwc && d.kh == 3 && d.kw == 3 && d.stride == 1 && d.pad == 1)) return false;
+    if (lay.pool && ((d.h | d.w) & 1)) return false;
+    // multi-image tiles are for maps that fit one tile; single-image tiles for the rest
+    if (tv.ni > 1) return d.h <= tv.th && d.w <= tv.tw;
+    return d.h * 2 > tv.th && d.w * 2 > tv.tw;
+  }
+  if (lay.pool) return false;  // only the patch kernels fuse the pool
   const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
   const long P = (long)d.n * ho * wo;
   const long K = (long)(lay.nhwc ? lay.cp_in : d.c_in) * d.kh * d.kw;
@@ -122,6 +128,8 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     PatchArgs pa;
     pa.x = x; pa.w = w; pa.bias = bias; pa.res = residual; pa.y = y;
     pa.N = d.n; pa.H = d.h; pa.W = d.w; pa.O = d.c_out; pa.Cp = lay.cp_in; pa.Cop = lay.cp_out;
+    pa.tiles_n = (d.n + tv.ni - 1) / tv.ni;
+    pa.pool = lay.pool;
     pa.tiles_y = (d.h + tv.th - 1) / tv.th;
     pa.tiles_x = (d.w + tv.tw - 1) / tv.tw;
     pa.tiles_m = (d.c_out + tv.tile_m() - 1) / tv.tile_m();
@@ -129,7 +137,7 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     pa.w_bytes = (unsigned)((size_t)d.c_out * 9 * lay.cp_in * es);
     pa.act = d.act;
     pa.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
-    dim3 pgrid((unsigned)(d.n * pa.tiles_y * pa.tiles_x * pa.tiles_m));
+    dim3 pgrid((unsigned)(pa.tiles_n * pa.tiles_y * pa.tiles_x * pa.tiles_m));
     if (d.dtype == CPRUNE_F32) launch_conv_patch_f32(tv.patch_id, pgrid, s, pa);
     else if (d.dtype == CPRUNE_F16) launch_conv_patch_f16(tv.patch_id, pgrid, s, pa);
     else launch_conv_patch_bf16(tv.patch_id, pgrid, s, pa);

@@ -30,26 +30,27 @@ struct PatchArgs {
   const void* res;
   void* y;
   int N, H, W, O, Cp, Cop;
-  int tiles_y, tiles_x, tiles_m;
+  int tiles_n, tiles_y, tiles_x, tiles_m;
   unsigned x_bytes, w_bytes;
   int act, vec_out;
+  int pool;   // 1: 2x2 / stride 2 max-pool fused behind the activation; y is [n][h/2][w/2][cop]
 };
 
-template <typename T, int MB, int TH, int TW>
+template <typename T, int MB, int TH, int TW, int NI>
 __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
   constexpr int ES = (int)sizeof(T);
   constexpr int EPI = 16 / ES;            // elements per quad
   constexpr int CC = 4 * EPI;             // channels per chunk (64 bytes)
-  constexpr int PT = TH * TW;             // output pixels per tile
+  constexpr int PT = TH * TW * NI;        // output pixels per tile (NI images x TH x TW)
   constexpr int NB = PT / 64;             // 16-pixel blocks per wave
   constexpr int MT = MB * 16;
   constexpr int PW = TW + 2, PH = TH + 2;
-  constexpr int NPATCH = PH * PW;
+  constexpr int NPATCH = NI * PH * PW;
   constexpr int BROW = 80;                // patch pixel: 64 bytes of channels + 16 pad
   constexpr int AROW = 9 * 64 + 16;       // filter row: 9 taps x 64 bytes + 16 pad
   constexpr int NIB = (NPATCH * 4 + 255) / 256;
   constexpr int NIA = (MT * 36 + 255) / 256;
-  static_assert(PT % 64 == 0 && (TW == 8 || TW == 16), "tile shape");
+  static_assert(PT % 64 == 0 && (TW == 2 || TW == 4 || TW == 8 || TW == 16) && (16 % TW == 0), "tile shape");
 
   __shared__ __attribute__((aligned(16))) unsigned char sA[MT * AROW];
   __shared__ __attribute__((aligned(16))) unsigned char sB[NPATCH * BROW];
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
   const int tx0 = (rest % a.tiles_x) * TW;
   rest /= a.tiles_x;
   const int ty0 = (rest % a.tiles_y) * TH;
-  const int n = rest / a.tiles_y;
+  const int n0 = (rest / a.tiles_y) * NI;
   const int o0 = tile_m * MT;
 
   const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);
@@ -86,9 +87,10 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
     const int idx = t + 256 * j;
     const int q = idx & 3, pp = idx >> 2;
     const bool item = pp < NPATCH;
-    const int py = pp / PW, px = pp - py * PW;
-    const int iy = ty0 + py - 1, ix = tx0 + px - 1;
-    const bool inside = item && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+    const int img = pp / (PH * PW), pr = pp - img * (PH * PW);
+    const int py = pr / PW, px = pr - py * PW;
+    const int iy = ty0 + py - 1, ix = tx0 + px - 1, n = n0 + img;
+    const bool inside = item && n < a.N && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
     b_off[j] = inside ? (unsigned)(((n * a.H + iy) * a.W + ix) * a.Cp + q * EPI) * ES : kOutOfRange;
     b_lds[j] = item ? pp * BROW + q * 16 : -1;
     b_q[j] = q;
@@ -136,8 +138,9 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
     const int id = wave * (NB * 16) + j * 16 + r;
-    const int ty = id / TW, tx = id % TW;
-    b_frag[j] = (ty * PW + tx) * BROW + g4 * 16;
+    const int img = id / (TH * TW), ir = id % (TH * TW);
+    const int ty = ir / TW, tx = ir % TW;
+    b_frag[j] = ((img * PH + ty) * PW + tx) * BROW + g4 * 16;
   }
   const int a_frag = r * AROW + g4 * 16;
 
@@ -184,35 +187,81 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
   // ---- epilogue ----
   ConvArgs e;
   e.bias = a.bias; e.res = a.res; e.y = a.y; e.O = a.O; e.Cop = a.Cop; e.act = a.act; e.vec_out = a.vec_out;
+  if (!a.pool) {
 #pragma unroll
-  for (int j = 0; j < NB; ++j) {
-    const int id = wave * (NB * 16) + j * 16 + r;
-    const int oy = ty0 + id / TW, ox = tx0 + id % TW;
-    if (oy >= a.H || ox >= a.W) continue;
-    const int p = (n * a.H + oy) * a.W + ox;
+    for (int j = 0; j < NB; ++j) {
+      const int id = wave * (NB * 16) + j * 16 + r;
+      const int img = id / (TH * TW), ir = id % (TH * TW);
+      const int oy = ty0 + ir / TW, ox = tx0 + ir % TW, n = n0 + img;
+      if (n >= a.N || oy >= a.H || ox >= a.W) continue;
+      const int p = (n * a.H + oy) * a.W + ox;
 #pragma unroll
-    for (int i = 0; i < MB; ++i) nhwc_store4<T>(e, acc[i][j], p, o0 + i * 16 + 4 * g4);
+      for (int i = 0; i < MB; ++i) nhwc_store4<T>(e, acc[i][j], p, o0 + i * 16 + 4 * g4);
+    }
+  } else {
+    // bias + activation, then the max over each 2x2 window.  Horizontal partner: lane
+    // r ^ 1.  Vertical partner: lane r ^ TW when a 16-pixel block holds several rows,
+    // else the same lane of the neighbouring block.  The activation is monotone, so
+    // max(act(.)) equals act-then-pool.  The even/even corner of each window stores.
+    e.act = CPRUNE_ACT_NONE;
+    e.bias = nullptr;
+    const int hp = a.H >> 1, wp = a.W >> 1;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      const int o = o0 + i * 16 + 4 * g4;
+      float4_t v[NB];
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          float x = acc[i][j][c] + ((a.bias && o + c < a.O) ? a.bias[o + c] : 0.0f);
+          x = apply_act(x, a.act);
+          x = fmaxf(x, __shfl_xor(x, 1, 64));
+          if constexpr (TW < 16) x = fmaxf(x, __shfl_xor(x, TW, 64));
+          v[j][c] = x;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        float4_t m = v[j];
+        if constexpr (TW == 16) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) m[c] = fmaxf(m[c], v[j ^ 1][c]);
+        }
+        const int id = wave * (NB * 16) + j * 16 + r;
+        const int img = id / (TH * TW), ir = id % (TH * TW);
+        const int ty = ir / TW, tx = ir % TW;
+        const int oy = ty0 + ty, ox = tx0 + tx, n = n0 + img;
+        if ((ty & 1) || (tx & 1) || n >= a.N || oy >= a.H || ox >= a.W) continue;
+        const int p = (n * hp + (oy >> 1)) * wp + (ox >> 1);
+        nhwc_store4<T>(e, m, p, o);
+      }
+    }
   }
 }
 
-// Patch variants: id, mb, th, tw
+// Patch variants: id, mb, th, tw, ni (ni images per tile for maps smaller than the tile)
 #define CPRUNE_PATCH_LIST(X) \
-  X(0, 1, 8, 8)   \
-  X(1, 2, 8, 8)   \
-  X(2, 4, 8, 8)   \
-  X(3, 2, 8, 16)  \
-  X(4, 4, 8, 16)  \
-  X(5, 2, 16, 16) \
-  X(6, 4, 16, 16) \
-  X(7, 1, 16, 16)
+  X(0, 1, 8, 8, 1)    \
+  X(1, 2, 8, 8, 1)    \
+  X(2, 4, 8, 8, 1)    \
+  X(3, 2, 8, 16, 1)   \
+  X(4, 4, 8, 16, 1)   \
+  X(5, 2, 16, 16, 1)  \
+  X(6, 4, 16, 16, 1)  \
+  X(7, 1, 16, 16, 1)  \
+  X(8, 1, 4, 4, 4)    \
+  X(9, 2, 4, 4, 4)    \
+  X(10, 1, 2, 2, 16)  \
+  X(11, 2, 2, 2, 16)
 
-constexpr int kNumPatch = 8;
+constexpr int kNumPatch = 12;
 
 template <typename T>
 inline void launch_patch(int id, dim3 grid, hipStream_t s, const PatchArgs& a) {
-#define CPRUNE_PATCH_CASE(ID, MB_, TH_, TW_)                                                  \
-  case ID:                                                                                    \
-    hipLaunchKernelGGL((conv_patch_kernel<T, MB_, TH_, TW_>), grid, dim3(256), 0, s, a);      \
+#define CPRUNE_PATCH_CASE(ID, MB_, TH_, TW_, NI_)                                                  \
+  case ID:                                                                                         \
+    hipLaunchKernelGGL((conv_patch_kernel<T, MB_, TH_, TW_, NI_>), grid, dim3(256), 0, s, a);      \
     break;
   switch (id) { CPRUNE_PATCH_LIST(CPRUNE_PATCH_CASE) }
 #undef CPRUNE_PATCH_CASE

@@ -44,7 +44,11 @@ def _run(orc, net, cid, batch, dtype, tune, check_layers=True, use_graph=False):
     tol = TOL[dtype]
     if check_layers:
         for i, r in enumerate(ref_acts[:-1]):
-            a = handle.activation(i, batch, r.shape[1:]).float().cpu().numpy()
+            try:
+                a = handle.activation(i, batch, r.shape[1:]).float().cpu().numpy()
+            except B.CPruneError as e:     # conv whose max-pool runs in its epilogue: checked at the pool
+                assert e.status == B.ERR_UNSUPPORTED and net.layers[i + 1].kind == "maxpool"
+                continue
             e = nmax(a, r)
             assert e < tol, (net.layers[i].name, e)
     err = nmax(logits.float().cpu().numpy(), ref_acts[-1])
