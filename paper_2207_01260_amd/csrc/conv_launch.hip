@@ -64,10 +64,10 @@ const TileVariant& variant(int id) {
   static TileVariant table[kNumTiles * kNumScheds + kNumPatch];
   static bool init = false;
   if (!init) {
-#define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_)                                 \
+#define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_, KQ_)                                 \
     {                                                                         \
       TileVariant& pv = table[kNumTiles * kNumScheds + ID];                   \
-      pv.wm = 1; pv.wn = 4; pv.mb = MB_; pv.nb = (TH_ * TW_ * NI_) / 64; pv.kq = 1; pv.ni = NI_; \
+      pv.wm = 1; pv.wn = 4; pv.mb = MB_; pv.nb = (TH_ * TW_ * NI_) / 64; pv.kq = KQ_; pv.ni = NI_; \
       pv.sched = -1; pv.th = TH_; pv.tw = TW_; pv.patch_id = ID;              \
     }
     CPRUNE_PATCH_LIST(CPRUNE_PATCH_ROW)

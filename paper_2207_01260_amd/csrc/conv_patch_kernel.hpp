@@ -36,20 +36,59 @@ struct PatchArgs {
   int pool;   // 1: 2x2 / stride 2 max-pool fused behind the activation; y is [n][h/2][w/2][cop]
 };
 
-template <typename T, int MB, int TH, int TW, int NI>
+// One 64-byte round of MFMAs on NS accumulator sets.  A tile with fewer than four
+// accumulator blocks per wave would issue back-to-back MFMAs into the same block, each
+// waiting for the one before; spreading consecutive instructions over NS sets (summed at
+// the end) keeps them independent.
+template <typename T, int MBC, int NB, int MB, int NS>
+__device__ __forceinline__ void mma_round(const uint4 (&af)[MB], const uint4 (&bf)[NB],
+                                          float4_t (&acc)[NS][MB][NB], int round) {
+  if constexpr (sizeof(T) == 4) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int set = NS == 1 ? 0 : (NS >= 4 ? e : ((round * 4 + e) % NS));
+#pragma unroll
+      for (int i = 0; i < MBC; ++i) {
+        const uint32_t av = e == 0 ? af[i].x : e == 1 ? af[i].y : e == 2 ? af[i].z : af[i].w;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const uint32_t bv = e == 0 ? bf[j].x : e == 1 ? bf[j].y : e == 2 ? bf[j].z : bf[j].w;
+          acc[set][i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(av), __uint_as_float(bv), acc[set][i][j], 0, 0, 0);
+        }
+      }
+    }
+  } else {
+    const int set = round % NS;
+#pragma unroll
+    for (int i = 0; i < MBC; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        if constexpr (std::is_same<T, _Float16>::value)
+          acc[set][i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, af[i]),
+                                                                  __builtin_bit_cast(half8_t, bf[j]), acc[set][i][j], 0, 0, 0);
+        else
+          acc[set][i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, af[i]),
+                                                                   __builtin_bit_cast(bf16x8_t, bf[j]), acc[set][i][j], 0, 0, 0);
+      }
+  }
+}
+
+template <typename T, int MB, int TH, int TW, int NI, int KQ>
 __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
   constexpr int ES = (int)sizeof(T);
   constexpr int EPI = 16 / ES;            // elements per quad
-  constexpr int CC = 4 * EPI;             // channels per chunk (64 bytes)
+  constexpr int CC = 4 * EPI * KQ;        // channels per chunk (KQ rounds of 64 bytes)
+  constexpr int NQ = 4 * KQ;              // quads per pixel per chunk
   constexpr int PT = TH * TW * NI;        // output pixels per tile (NI images x TH x TW)
   constexpr int NB = PT / 64;             // 16-pixel blocks per wave
   constexpr int MT = MB * 16;
   constexpr int PW = TW + 2, PH = TH + 2;
   constexpr int NPATCH = NI * PH * PW;
-  constexpr int BROW = 80;                // patch pixel: 64 bytes of channels + 16 pad
-  constexpr int AROW = 9 * 64 + 16;       // filter row: 9 taps x 64 bytes + 16 pad
-  constexpr int NIB = (NPATCH * 4 + 255) / 256;
-  constexpr int NIA = (MT * 36 + 255) / 256;
+  constexpr int BROW = 64 * KQ + 16;      // patch pixel: the chunk's channels + 16 pad
+  constexpr int AROW = 9 * 64 * KQ + 16;  // filter row: 9 taps x chunk + 16 pad
+  constexpr int NIB = (NPATCH * NQ + 255) / 256;
+  constexpr int NIA = (MT * 9 * NQ + 255) / 256;
+  constexpr int NS = (MB * (PT / 64) >= 4) ? 1 : 4 / (MB * (PT / 64));  // accumulator sets
   static_assert(PT % 64 == 0 && (TW == 2 || TW == 4 || TW == 8 || TW == 16) && (16 % TW == 0), "tile shape");
 
   __shared__ __attribute__((aligned(16))) unsigned char sA[MT * AROW];
@@ -85,7 +124,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
 #pragma unroll
   for (int j = 0; j < NIB; ++j) {
     const int idx = t + 256 * j;
-    const int q = idx & 3, pp = idx >> 2;
+    const int q = idx % NQ, pp = idx / NQ;
     const bool item = pp < NPATCH;
     const int img = pp / (PH * PW), pr = pp - img * (PH * PW);
     const int py = pr / PW, px = pr - py * PW;
@@ -100,13 +139,13 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
 #pragma unroll
   for (int j = 0; j < NIA; ++j) {
     const int idx = t + 256 * j;
-    const int q = idx & 3;
-    const int tap = (idx >> 2) % 9;
-    const int m = (idx >> 2) / 9;
+    const int q = idx % NQ;
+    const int tap = (idx / NQ) % 9;
+    const int m = (idx / NQ) / 9;
     const bool item = m < MT;
     const int o = o0 + m;
     a_off[j] = (item && o < a.O) ? (unsigned)((o * 9 + tap) * a.Cp + q * EPI) * ES : kOutOfRange;
-    a_lds[j] = item ? m * AROW + tap * 64 + q * 16 : -1;
+    a_lds[j] = item ? m * AROW + tap * (64 * KQ) + q * 16 : -1;
     a_q[j] = q;
   }
 
@@ -144,11 +183,13 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
   }
   const int a_frag = r * AROW + g4 * 16;
 
-  float4_t acc[MB][NB];
+  float4_t accs[NS][MB][NB];
 #pragma unroll
-  for (int i = 0; i < MB; ++i)
+  for (int q = 0; q < NS; ++q)
 #pragma unroll
-    for (int j = 0; j < NB; ++j) acc[i][j] = (float4_t){0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) accs[q][i][j] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
   int mb_count = (a.O - o0 + 15) / 16;
   mb_count = mb_count > MB ? MB : mb_count;
@@ -162,16 +203,22 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
       lds_store();
       __syncthreads();
       if (c + 1 < nchunk) gload((c + 1) * CC);
+      // the operands of round r + 1 are fetched from LDS while round r is multiplied
+      constexpr int NR = 9 * KQ;
+      uint4 af[2][MB], bf[2][NB];
+      auto fetch = [&](int rnd, uint4 (&fa)[MB], uint4 (&fb)[NB]) {
+        const int tap = rnd / KQ, q4 = rnd % KQ;
+        const int boff = ((tap / 3) * PW + (tap % 3)) * BROW + q4 * 64;
 #pragma unroll
-      for (int tap = 0; tap < 9; ++tap) {
-        constexpr int dummy = 0; (void)dummy;
-        const int boff = ((tap / 3) * PW + (tap % 3)) * BROW;
-        uint4 af[MB], bf[NB];
+        for (int j = 0; j < NB; ++j) fb[j] = *(const uint4*)&sB[b_frag[j] + boff];
 #pragma unroll
-        for (int j = 0; j < NB; ++j) bf[j] = *(const uint4*)&sB[b_frag[j] + boff];
+        for (int i = 0; i < MBC; ++i) fa[i] = *(const uint4*)&sA[a_frag + i * 16 * AROW + tap * (64 * KQ) + q4 * 64];
+      };
+      fetch(0, af[0], bf[0]);
 #pragma unroll
-        for (int i = 0; i < MBC; ++i) af[i] = *(const uint4*)&sA[a_frag + i * 16 * AROW + tap * 64];
-        mma_slab<T, MBC, NB, MB>(af, bf, acc);
+      for (int rnd = 0; rnd < NR; ++rnd) {
+        if (rnd + 1 < NR) fetch(rnd + 1, af[(rnd + 1) & 1], bf[(rnd + 1) & 1]);
+        mma_round<T, MBC, NB, MB, NS>(af[rnd & 1], bf[rnd & 1], accs, rnd);
       }
     }
   };
@@ -183,6 +230,16 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
 #undef CPRUNE_MBC_CASE
     default: break;
   }
+
+  float4_t acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      acc[i][j] = accs[0][i][j];
+#pragma unroll
+      for (int q = 1; q < NS; ++q) acc[i][j] += accs[q][i][j];
+    }
 
   // ---- epilogue ----
   ConvArgs e;
@@ -240,28 +297,36 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
   }
 }
 
-// Patch variants: id, mb, th, tw, ni (ni images per tile for maps smaller than the tile)
+// Patch variants: id, mb, th, tw, ni (images per tile, for maps smaller than the tile),
+// kq (64-byte channel rounds per chunk: deeper chunks for the small tiles, whose per-chunk
+// MFMA work is short against the latency of the next chunk's loads)
 #define CPRUNE_PATCH_LIST(X) \
-  X(0, 1, 8, 8, 1)    \
-  X(1, 2, 8, 8, 1)    \
-  X(2, 4, 8, 8, 1)    \
-  X(3, 2, 8, 16, 1)   \
-  X(4, 4, 8, 16, 1)   \
-  X(5, 2, 16, 16, 1)  \
-  X(6, 4, 16, 16, 1)  \
-  X(7, 1, 16, 16, 1)  \
-  X(8, 1, 4, 4, 4)    \
-  X(9, 2, 4, 4, 4)    \
-  X(10, 1, 2, 2, 16)  \
-  X(11, 2, 2, 2, 16)
+  X(0, 1, 8, 8, 1, 1)    \
+  X(1, 2, 8, 8, 1, 1)    \
+  X(2, 4, 8, 8, 1, 1)    \
+  X(3, 2, 8, 16, 1, 1)   \
+  X(4, 4, 8, 16, 1, 1)   \
+  X(5, 2, 16, 16, 1, 1)  \
+  X(6, 4, 16, 16, 1, 1)  \
+  X(7, 1, 16, 16, 1, 1)  \
+  X(8, 1, 4, 4, 4, 1)    \
+  X(9, 2, 4, 4, 4, 2)    \
+  X(10, 1, 2, 2, 16, 1)  \
+  X(11, 2, 2, 2, 16, 1)  \
+  X(12, 1, 8, 8, 1, 2)   \
+  X(13, 2, 8, 8, 1, 2)   \
+  X(14, 1, 4, 4, 4, 2)   \
+  X(15, 1, 2, 2, 16, 2)  \
+  X(16, 1, 8, 8, 1, 3)   \
+  X(17, 1, 4, 4, 4, 3)
 
-constexpr int kNumPatch = 12;
+constexpr int kNumPatch = 18;
 
 template <typename T>
 inline void launch_patch(int id, dim3 grid, hipStream_t s, const PatchArgs& a) {
-#define CPRUNE_PATCH_CASE(ID, MB_, TH_, TW_, NI_)                                                  \
-  case ID:                                                                                         \
-    hipLaunchKernelGGL((conv_patch_kernel<T, MB_, TH_, TW_, NI_>), grid, dim3(256), 0, s, a);      \
+#define CPRUNE_PATCH_CASE(ID, MB_, TH_, TW_, NI_, KQ_)                                                  \
+  case ID:                                                                                              \
+    hipLaunchKernelGGL((conv_patch_kernel<T, MB_, TH_, TW_, NI_, KQ_>), grid, dim3(256), 0, s, a);      \
     break;
   switch (id) { CPRUNE_PATCH_LIST(CPRUNE_PATCH_CASE) }
 #undef CPRUNE_PATCH_CASE
