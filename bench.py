@@ -30,7 +30,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--dtype", default="f32", choices=["f32", "f16", "bf16"])
-    ap.add_argument("--no-graph", action="store_true", help="launch layer by layer, no HIP graph")
+    ap.add_argument("--graph", type=int, default=-1, choices=[-1, 0, 1],
+                    help="0 layer-by-layer launches, 1 HIP graph replay, -1 (default) the faster of "
+                         "the two by a short untimed trial")
     ap.add_argument("--no-tune", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip batch-1 and fp16 side figures")
@@ -85,10 +87,14 @@ def main():
     prune_ms = (time.perf_counter() - t0) / reps * 1e3
 
     # ---- main measurement -------------------------------------------------------------
-    graph = not args.no_graph
     handle, layers, kept, tune_s = build(dt, args.batch, not args.no_tune)
     kept_counts = {i: int(k.numel()) for i, k in kept.items()}
     x = torch.from_numpy(synth.net_input(net, cid, args.batch)).cuda().to(B.TORCH_DTYPE[dt])
+    graph = args.graph
+    if graph < 0:
+        trial = {g: time_forward(handle, x, 30, 10, g) for g in (0, 1)}
+        graph = min(trial, key=trial.get)
+    graph = bool(graph)
     ms = time_forward(handle, x, args.steps, args.warmup, graph)
     value = args.batch / (ms * 1e-3)
 

@@ -64,7 +64,7 @@ const TileVariant& variant(int id) {
   static TileVariant table[kNumTiles * kNumScheds + kNumPatch];
   static bool init = false;
   if (!init) {
-#define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_, KQ_)                                 \
+#define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_, KQ_, KS_)                                 \
     {                                                                         \
       TileVariant& pv = table[kNumTiles * kNumScheds + ID];                   \
       pv.wm = 1; pv.wn = 4; pv.mb = MB_; pv.nb = (TH_ * TW_ * NI_) / 64; pv.kq = KQ_; pv.ni = NI_; \

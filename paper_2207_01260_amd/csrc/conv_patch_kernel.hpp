@@ -73,8 +73,9 @@ __device__ __forceinline__ void mma_round(const uint4 (&af)[MB], const uint4 (&b
   }
 }
 
-template <typename T, int MB, int TH, int TW, int NI, int KQ>
-__global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
+template <typename T, int MB, int TH, int TW, int NI, int KQ, int KS>
+__global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
+  constexpr int NT = 256 * KS;            // KS groups of 4 wavefronts share a tile: each takes 1/KS of the rounds
   constexpr int ES = (int)sizeof(T);
   constexpr int EPI = 16 / ES;            // elements per quad
   constexpr int CC = 4 * EPI * KQ;        // channels per chunk (KQ rounds of 64 bytes)
@@ -86,8 +87,8 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
   constexpr int NPATCH = NI * PH * PW;
   constexpr int BROW = 64 * KQ + 16;      // patch pixel: the chunk's channels + 16 pad
   constexpr int AROW = 9 * 64 * KQ + 16;  // filter row: 9 taps x chunk + 16 pad
-  constexpr int NIB = (NPATCH * NQ + 255) / 256;
-  constexpr int NIA = (MT * 9 * NQ + 255) / 256;
+  constexpr int NIB = (NPATCH * NQ + NT - 1) / NT;
+  constexpr int NIA = (MT * 9 * NQ + NT - 1) / NT;
   constexpr int NS = (MB * (PT / 64) >= 4) ? 1 : 4 / (MB * (PT / 64));  // accumulator sets
   static_assert(PT % 64 == 0 && (TW == 2 || TW == 4 || TW == 8 || TW == 16) && (16 % TW == 0), "tile shape");
 
@@ -96,7 +97,8 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
 
   const int t = threadIdx.x;
   const int lane = t & 63;
-  const int wave = t >> 6;
+  const int wave = (t >> 6) & 3;          // pixel group of this wavefront
+  const int kgrp = t >> 8;                // which share of the rounds it multiplies
   const int r = lane & 15, g4 = lane >> 4;
 
   // tile decode: filters fastest, so neighbouring groups share the patch in L2
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
   int b_lds[NIB], b_q[NIB];
 #pragma unroll
   for (int j = 0; j < NIB; ++j) {
-    const int idx = t + 256 * j;
+    const int idx = t + NT * j;
     const int q = idx % NQ, pp = idx / NQ;
     const bool item = pp < NPATCH;
     const int img = pp / (PH * PW), pr = pp - img * (PH * PW);
@@ -138,7 +140,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
   int a_lds[NIA], a_q[NIA];
 #pragma unroll
   for (int j = 0; j < NIA; ++j) {
-    const int idx = t + 256 * j;
+    const int idx = t + NT * j;
     const int q = idx % NQ;
     const int tap = (idx / NQ) % 9;
     const int m = (idx / NQ) / 9;
@@ -203,22 +205,33 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
       lds_store();
       __syncthreads();
       if (c + 1 < nchunk) gload((c + 1) * CC);
-      // the operands of round r + 1 are fetched from LDS while round r is multiplied
+      // the operands of round r + 1 are fetched from LDS while round r is multiplied;
+      // wave group kgrp takes rounds [kgrp * NR / KS, (kgrp + 1) * NR / KS)
       constexpr int NR = 9 * KQ;
-      uint4 af[2][MB], bf[2][NB];
-      auto fetch = [&](int rnd, uint4 (&fa)[MB], uint4 (&fb)[NB]) {
-        const int tap = rnd / KQ, q4 = rnd % KQ;
-        const int boff = ((tap / 3) * PW + (tap % 3)) * BROW + q4 * 64;
+      auto rounds = [&](auto lo_tag, auto hi_tag) {
+        constexpr int LO = decltype(lo_tag)::value, HI = decltype(hi_tag)::value;
+        uint4 af[2][MB], bf[2][NB];
+        auto fetch = [&](int rnd, uint4 (&fa)[MB], uint4 (&fb)[NB]) {
+          const int tap = rnd / KQ, q4 = rnd % KQ;
+          const int boff = ((tap / 3) * PW + (tap % 3)) * BROW + q4 * 64;
 #pragma unroll
-        for (int j = 0; j < NB; ++j) fb[j] = *(const uint4*)&sB[b_frag[j] + boff];
+          for (int j = 0; j < NB; ++j) fb[j] = *(const uint4*)&sB[b_frag[j] + boff];
 #pragma unroll
-        for (int i = 0; i < MBC; ++i) fa[i] = *(const uint4*)&sA[a_frag + i * 16 * AROW + tap * (64 * KQ) + q4 * 64];
+          for (int i = 0; i < MBC; ++i) fa[i] = *(const uint4*)&sA[a_frag + i * 16 * AROW + tap * (64 * KQ) + q4 * 64];
+        };
+        fetch(LO, af[0], bf[0]);
+#pragma unroll
+        for (int rnd = LO; rnd < HI; ++rnd) {
+          if (rnd + 1 < HI) fetch(rnd + 1, af[(rnd + 1 - LO) & 1], bf[(rnd + 1 - LO) & 1]);
+          mma_round<T, MBC, NB, MB, NS>(af[(rnd - LO) & 1], bf[(rnd - LO) & 1], accs, rnd);
+        }
       };
-      fetch(0, af[0], bf[0]);
-#pragma unroll
-      for (int rnd = 0; rnd < NR; ++rnd) {
-        if (rnd + 1 < NR) fetch(rnd + 1, af[(rnd + 1) & 1], bf[(rnd + 1) & 1]);
-        mma_round<T, MBC, NB, MB, NS>(af[rnd & 1], bf[rnd & 1], accs, rnd);
+      if constexpr (KS == 1) {
+        rounds(std::integral_constant<int, 0>{}, std::integral_constant<int, NR>{});
+      } else {
+        constexpr int MID = (NR + 1) / 2;
+        if (kgrp == 0) rounds(std::integral_constant<int, 0>{}, std::integral_constant<int, MID>{});
+        else rounds(std::integral_constant<int, MID>{}, std::integral_constant<int, NR>{});
       }
     }
   };
@@ -240,6 +253,25 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
 #pragma unroll
       for (int q = 1; q < NS; ++q) acc[i][j] += accs[q][i][j];
     }
+
+  if constexpr (KS > 1) {
+    // the second wave group hands its sums over through LDS (the staging buffers are free now)
+    __syncthreads();
+    float4_t* xch = (float4_t*)sA + (size_t)wave * (MB * NB * 64) + lane;
+    static_assert(4 * MB * NB * 64 * 16 <= MT * AROW, "exchange fits the weight buffer");
+    if (kgrp == 1) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) xch[(i * NB + j) * 64] = acc[i][j];
+    }
+    __syncthreads();
+    if (kgrp == 1) return;
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) acc[i][j] += xch[(i * NB + j) * 64];
+  }
 
   // ---- epilogue ----
   ConvArgs e;
@@ -298,35 +330,41 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(PatchArgs a) {
 }
 
 // Patch variants: id, mb, th, tw, ni (images per tile, for maps smaller than the tile),
-// kq (64-byte channel rounds per chunk: deeper chunks for the small tiles, whose per-chunk
-// MFMA work is short against the latency of the next chunk's loads)
+// kq (64-byte channel rounds per chunk), ks (wave groups per tile: 2 = eight wavefronts,
+// each group multiplying half of every chunk's rounds; for layers with about as many
+// tiles as compute units, where one group per unit leaves the MFMA pipe waiting)
 #define CPRUNE_PATCH_LIST(X) \
-  X(0, 1, 8, 8, 1, 1)    \
-  X(1, 2, 8, 8, 1, 1)    \
-  X(2, 4, 8, 8, 1, 1)    \
-  X(3, 2, 8, 16, 1, 1)   \
-  X(4, 4, 8, 16, 1, 1)   \
-  X(5, 2, 16, 16, 1, 1)  \
-  X(6, 4, 16, 16, 1, 1)  \
-  X(7, 1, 16, 16, 1, 1)  \
-  X(8, 1, 4, 4, 4, 1)    \
-  X(9, 2, 4, 4, 4, 2)    \
-  X(10, 1, 2, 2, 16, 1)  \
-  X(11, 2, 2, 2, 16, 1)  \
-  X(12, 1, 8, 8, 1, 2)   \
-  X(13, 2, 8, 8, 1, 2)   \
-  X(14, 1, 4, 4, 4, 2)   \
-  X(15, 1, 2, 2, 16, 2)  \
-  X(16, 1, 8, 8, 1, 3)   \
-  X(17, 1, 4, 4, 4, 3)
+  X(0, 1, 8, 8, 1, 1, 1)    \
+  X(1, 2, 8, 8, 1, 1, 1)    \
+  X(2, 4, 8, 8, 1, 1, 1)    \
+  X(3, 2, 8, 16, 1, 1, 1)   \
+  X(4, 4, 8, 16, 1, 1, 1)   \
+  X(5, 2, 16, 16, 1, 1, 1)  \
+  X(6, 4, 16, 16, 1, 1, 1)  \
+  X(7, 1, 16, 16, 1, 1, 1)  \
+  X(8, 1, 4, 4, 4, 1, 1)    \
+  X(9, 2, 4, 4, 4, 2, 1)    \
+  X(10, 1, 2, 2, 16, 1, 1)  \
+  X(11, 2, 2, 2, 16, 1, 1)  \
+  X(12, 1, 8, 8, 1, 2, 1)   \
+  X(13, 2, 8, 8, 1, 2, 1)   \
+  X(14, 1, 4, 4, 4, 2, 1)   \
+  X(15, 1, 2, 2, 16, 2, 1)  \
+  X(16, 1, 8, 8, 1, 2, 2)   \
+  X(17, 1, 4, 4, 4, 2, 2)   \
+  X(18, 2, 8, 8, 1, 2, 2)   \
+  X(19, 2, 4, 4, 4, 2, 2)   \
+  X(20, 1, 2, 2, 16, 2, 2)  \
+  X(21, 4, 8, 8, 1, 1, 2)   \
+  X(22, 2, 8, 16, 1, 1, 2)
 
-constexpr int kNumPatch = 18;
+constexpr int kNumPatch = 23;
 
 template <typename T>
 inline void launch_patch(int id, dim3 grid, hipStream_t s, const PatchArgs& a) {
-#define CPRUNE_PATCH_CASE(ID, MB_, TH_, TW_, NI_, KQ_)                                                  \
-  case ID:                                                                                              \
-    hipLaunchKernelGGL((conv_patch_kernel<T, MB_, TH_, TW_, NI_, KQ_>), grid, dim3(256), 0, s, a);      \
+#define CPRUNE_PATCH_CASE(ID, MB_, TH_, TW_, NI_, KQ_, KS_)                                                      \
+  case ID:                                                                                                       \
+    hipLaunchKernelGGL((conv_patch_kernel<T, MB_, TH_, TW_, NI_, KQ_, KS_>), grid, dim3(256 * KS_), 0, s, a);    \
     break;
   switch (id) { CPRUNE_PATCH_LIST(CPRUNE_PATCH_CASE) }
 #undef CPRUNE_PATCH_CASE
