@@ -62,11 +62,14 @@ def test_mobilenetv2_batch64(orc):
     _net_case(orc, synth.mobilenetv2(1000, 224), 4, 64, B.F32, [0, 37, 63])
 
 
+@pytest.mark.parametrize("path", ["entry_point", "handle"])
 @pytest.mark.parametrize("c_out", [1, 15, 16, 17, 45, 100, 128])
-def test_channel_sweep_points(orc, c_out):
+def test_channel_sweep_points(orc, c_out, path):
     """3x3 conv at 56x56, C_in 128, batch 8, filters pruned from 128 to c_out by L1 rank;
-    the variant is the one cprune_select_tile picks; outputs checked at sampled positions."""
-    print("sweep c_out", c_out, flush=True)
+    run through the NCHW entry point with the variant cprune_select_tile picks, and through a
+    tuned one-layer inference handle (channels-last kernels); outputs checked at sampled
+    positions."""
+    print("sweep c_out", c_out, path, flush=True)
     net = synth.single_conv(128, 128, 56)
     params = synth.layer_params(net, 5)
     params[0]["keep"] = c_out
@@ -76,9 +79,15 @@ def test_channel_sweep_points(orc, c_out):
     assert np.array_equal(kept[0].cpu().numpy(), ref_kept[0])
     assert np.array_equal(layers[0]["w"].cpu().numpy(), ref_layers[0]["w"])
     xd = torch.from_numpy(x).cuda()
-    d = B.conv_desc(x.shape, layers[0]["w"].shape, 1, 1)
-    v, best_ms, _ = B.cprune_select_tile(d, xd, layers[0]["w"], layers[0]["b"], warmup=1, iters=3)
-    y = B.cprune_conv2d_bn_relu(d, xd, layers[0]["w"], layers[0]["b"]).cpu().numpy()
+    if path == "handle":
+        handle = pipeline.build_net(net, layers, 8, tune=True)
+        y = handle.forward(xd, use_graph=True).cpu().numpy()
+        v = handle.layer_variant(0)
+        handle.close()
+    else:
+        d = B.conv_desc(x.shape, layers[0]["w"].shape, 1, 1)
+        v, best_ms, _ = B.cprune_select_tile(d, xd, layers[0]["w"], layers[0]["b"], warmup=1, iters=3)
+        y = B.cprune_conv2d_bn_relu(d, xd, layers[0]["w"], layers[0]["b"]).cpu().numpy()
     wref, bref = ref_layers[0]["w"], ref_layers[0]["b"]
     rng = np.random.RandomState(c_out)
     pts = [(0, 0, 0, 0), (7, c_out - 1, 55, 55), (3, c_out // 2, 0, 55), (4, 0, 55, 0)]
