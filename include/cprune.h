@@ -208,7 +208,9 @@ typedef struct cprune_net cprune_net;
 int cprune_net_create(const cprune_layer_desc* layers, int n_layers, int in_c, int in_h,
                       int in_w, int max_batch, cprune_dtype dtype, int tune, void* stream,
                       cprune_net** out);
-/* logits: [n][c_out of the last layer] in the net's dtype.  1 <= n <= max_batch.
+/* logits: the last layer's output, dense NCHW [n][c_out][h_out][w_out] in the net's dtype
+ * ([n][classes] for a net that ends in a fully connected layer); device memory of at
+ * least n times the element count cprune_net_output_shape reports.  1 <= n <= max_batch.
  * use_graph != 0 replays a HIP graph of the layer sequence on `stream`; the graph is
  * recorded (on a stream the handle owns, nothing executes while recording) the
  * first time a given (n, x, logits) triple is seen and kept until destroy. */
@@ -225,6 +227,8 @@ int cprune_net_layer_times(cprune_net* net, const void* x, int n, int iters, flo
  * epilogue has no activation of its own: CPRUNE_ERR_UNSUPPORTED (ask for the pool layer). */
 int cprune_net_copy_activation(cprune_net* net, int layer, int n, void* dst, size_t dst_bytes,
                                void* stream);
+/* Shape of one image's output (the last layer's c_out, h_out, w_out); host outs. */
+int cprune_net_output_shape(const cprune_net* net, int* c_out, int* h_out, int* w_out);
 /* The tile variant in use for layer `layer` (-1 for layers without one); host out. */
 int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out);
 int cprune_net_destroy(cprune_net* net);

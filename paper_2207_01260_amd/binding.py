@@ -46,7 +46,8 @@ EXPORTS = [
     "cprune_cached_tile", "cprune_maxpool2d", "cprune_global_avgpool",
     "cprune_fc_workspace_bytes", "cprune_fc",
     "cprune_net_create", "cprune_net_forward", "cprune_net_layer_times",
-    "cprune_net_copy_activation", "cprune_net_layer_variant", "cprune_net_destroy",
+    "cprune_net_copy_activation", "cprune_net_output_shape", "cprune_net_layer_variant",
+    "cprune_net_destroy",
 ]
 
 _lib = None
@@ -269,7 +270,6 @@ class Net:
         arr = (LayerDesc * len(layer_descs))(*layer_descs)
         self._h = C.c_void_p(None)
         self.n_layers = len(layer_descs)
-        self.out_features = layer_descs[-1].c_out
         self.dtype = dtype
         self.max_batch = max_batch
         st = lib().cprune_net_create(arr, C.c_int(len(layer_descs)), C.c_int(in_chw[0]),
@@ -277,12 +277,18 @@ class Net:
                                      C.c_int(dtype), C.c_int(1 if tune else 0), _stream(stream),
                                      C.byref(self._h))
         _check(st, "cprune_net_create")
+        c, h, w = C.c_int(0), C.c_int(0), C.c_int(0)
+        _check(lib().cprune_net_output_shape(self._h, C.byref(c), C.byref(h), C.byref(w)),
+               "cprune_net_output_shape")
+        self.out_shape = (c.value,) if h.value * w.value == 1 else (c.value, h.value, w.value)
+        self.out_features = c.value * h.value * w.value
 
     def forward(self, x, logits=None, use_graph=False, stream=None):
         n = x.shape[0]
         if logits is None:
-            logits = torch.empty((n, self.out_features), dtype=TORCH_DTYPE[self.dtype],
-                                 device=x.device)
+            logits = torch.empty((n,) + self.out_shape, dtype=TORCH_DTYPE[self.dtype], device=x.device)
+        elif logits.numel() < n * self.out_features or logits.dtype != TORCH_DTYPE[self.dtype]:
+            raise ValueError("logits buffer too small or of the wrong dtype for this net")
         st = lib().cprune_net_forward(self._h, _ptr(x), C.c_int(n), _ptr(logits),
                                       C.c_int(1 if use_graph else 0), _stream(stream))
         _check(st, "cprune_net_forward")

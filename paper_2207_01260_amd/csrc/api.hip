@@ -297,6 +297,7 @@ struct NetLayer {
   int variant = -1;           // dense conv / fc: variant for max_batch
   bool fused_pool = false;    // conv: the 2x2 max-pool that follows runs in its epilogue; act is the pooled map
   bool alias = false;         // max-pool folded into its producer: no kernel, act is the producer's buffer
+  bool map2x2 = false;        // 3x3 / stride 1 / pad 1 conv on a 2x2 map, run as one matrix over the whole map
 };
 
 struct GraphKey {
@@ -326,6 +327,12 @@ static cprune_conv_desc layer_conv_desc(const cprune_net& net, const NetLayer& L
   d.n = n; d.c_in = L.d.c_in; d.c_out = L.d.c_out; d.dtype = net.dtype; d.act = L.d.act;
   d.has_residual = L.d.residual >= 0 ? 1 : 0;
   d.h = L.h_in; d.w = L.w_in;
+  if (L.map2x2) {
+    // channels-last, a 2x2 map of cp channels is one vector of 4 * cp values per image
+    d.c_in = 4 * L.cp_in; d.c_out = 4 * round_up_vec(L.d.c_out, net.dtype);
+    d.h = d.w = 1; d.kh = d.kw = 1; d.stride = 1; d.pad = 0; d.groups = 1;
+    return d;
+  }
   if (L.d.kind == CPRUNE_LAYER_FC) {
     d.kh = L.h_in; d.kw = L.w_in; d.stride = 1; d.pad = 0; d.groups = 1;
   } else {
@@ -337,6 +344,11 @@ static cprune_conv_desc layer_conv_desc(const cprune_net& net, const NetLayer& L
 static ConvLayout layer_layout(const NetLayer& L) {
   ConvLayout lay;
   lay.nhwc = 1; lay.cp_in = L.cp_in; lay.cp_out = L.cp_out; lay.pool = L.fused_pool ? 1 : 0;
+  if (L.map2x2) {
+    lay.cp_in = 4 * L.cp_in;
+    if (L.fused_pool) lay.pool = 2;   // rows ordered (channel, pixel); cp_out stays the pooled map's stride
+    else lay.cp_out = 4 * L.cp_out;
+  }
   return lay;
 }
 
@@ -464,6 +476,17 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     Pl.alias = true;
   }
 
+  // A 3x3 / stride 1 / pad 1 conv on a 2x2 map reads the whole input map for every output pixel:
+  // it runs as one matrix product per image, 4/9 of the multiply-adds of the nine-tap form
+  // (the other 5/9 would multiply padding).
+  for (int i = 0; i < n_layers; ++i) {
+    NetLayer& L = net->layers[i];
+    const cprune_layer_desc& d = L.d;
+    if (d.kind == CPRUNE_LAYER_CONV && d.groups == 1 && d.k == 3 && d.stride == 1 && d.pad == 1 &&
+        L.h_in == 2 && L.w_in == 2 && L.cp_out == round_up_vec(d.c_out, dtype))
+      L.map2x2 = true;
+  }
+
   auto dev_alloc = [&](size_t bytes, void** p) -> int {
     hipError_t e = hipMalloc(p, bytes ? bytes : 16);
     if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
@@ -474,7 +497,19 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
   for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
     NetLayer& L = net->layers[i];
     const cprune_layer_desc& d = L.d;
-    if (d.kind == CPRUNE_LAYER_CONV || d.kind == CPRUNE_LAYER_FC) {
+    if (L.map2x2) {
+      const int cpo = round_up_vec(d.c_out, dtype);
+      const size_t nw = (size_t)16 * cpo * L.cp_in;
+      if ((long)nw * (long)es >= lim) { rc = CPRUNE_ERR_UNSUPPORTED; break; }
+      rc = dev_alloc(nw * es, &L.w);
+      if (rc == CPRUNE_OK) rc = dev_alloc((size_t)4 * cpo * sizeof(float), (void**)&L.b);
+      if (rc != CPRUNE_OK) break;
+      rc = launch_repack_map2x2(d.weight, d.bias, d.c_out, d.c_in, L.cp_in, cpo, L.fused_pool ? 1 : 0, dtype, L.w, L.b, s);
+      if (rc != CPRUNE_OK) break;
+      cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
+      size_t need = conv_ws_bytes(cd, -1, layer_layout(L));
+      if (need > net->ws_bytes) net->ws_bytes = need;
+    } else if (d.kind == CPRUNE_LAYER_CONV || d.kind == CPRUNE_LAYER_FC) {
       const int khw = d.kind == CPRUNE_LAYER_FC ? L.h_in * L.w_in : d.k * d.k;
       const bool dw = d.kind == CPRUNE_LAYER_CONV && d.groups != 1;
       const size_t nw = (size_t)(dw ? 1 : d.c_out) * khw * L.cp_in;
@@ -607,6 +642,13 @@ extern "C" int cprune_net_copy_activation(cprune_net* net, int layer, int n, voi
   const size_t bytes = (size_t)L.d.c_out * L.h_out * L.w_out * n * dtype_size(net->dtype);
   if (dst_bytes < bytes) return CPRUNE_ERR_INVALID_ARG;
   return launch_nhwc_to_nchw(L.act, n, L.d.c_out, L.h_out * L.w_out, L.cp_out, net->dtype, dst, (hipStream_t)stream);
+}
+
+extern "C" int cprune_net_output_shape(const cprune_net* net, int* c_out, int* h_out, int* w_out) {
+  if (!net || !c_out || !h_out || !w_out) return CPRUNE_ERR_INVALID_ARG;
+  const NetLayer& L = net->layers.back();
+  *c_out = L.d.c_out; *h_out = L.h_out; *w_out = L.w_out;
+  return CPRUNE_OK;
 }
 
 extern "C" int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out) {

@@ -52,7 +52,9 @@ struct ConvLayout {
   int nhwc = 0;
   int cp_in = 0;
   int cp_out = 0;
-  int pool = 0;  // channels-last 3x3 layers: a 2x2/2 max-pool fused behind the activation
+  int pool = 0;  // 1: channels-last 3x3 layer with a 2x2/2 max-pool fused behind the activation (patch kernels);
+                 // 2: rows are (channel, position of a 2x2 map) and each group of four rows is reduced to its
+                 //    maximum behind the activation; cp_out is the stride of the pooled output
 };
 inline int round_up_vec(int c, int dt) { const int v = dt == CPRUNE_F32 ? 4 : 8; return (c + v - 1) / v * v; }
 
@@ -83,5 +85,10 @@ int launch_nchw_to_nhwc(const void* x, int n, int c, int hw, int cp, int dt, voi
 int launch_nhwc_to_nchw(const void* x, int n, int c, int hw, int cp, int dt, void* y, hipStream_t s);
 // w [o][c][khw] -> [o][khw][cp] (zero pad); depthwise: o = 1 and c = channels gives [khw][cp]
 int launch_repack_weights(const void* w, int o, int c, int khw, int cp, int dt, void* y, hipStream_t s);
+// 3x3 / stride 1 / pad 1 on a 2x2 map as one matrix over the whole map: w [o][c][3][3] ->
+// [rows][4 * cp_in], column (input pixel, channel), row (output pixel, channel) with channel
+// stride cp_out, or (channel, output pixel) when rows_by_channel; bias [o] -> [4 * cp_out] alike
+int launch_repack_map2x2(const void* w, const float* bias, int o, int c, int cp_in, int cp_out,
+                         int rows_by_channel, int dt, void* w_out, float* bias_out, hipStream_t s);
 
 }  // namespace cprune

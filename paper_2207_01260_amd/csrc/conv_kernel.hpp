@@ -62,6 +62,8 @@ struct ConvArgs {
   int Cp, Cop;        // channels-last kernels: channel stride of x / of y (elements)
   unsigned magic_cp;  // division by Cp
   int vec_out;        // channels-last: y may be written 4 channels at a time
+  int pool4 = 0;      // channels-last: rows 4c..4c+3 are the four positions of channel c of a 2x2 map;
+                      // their maximum (behind bias and activation) is stored as y[p][c] (Cop = stride of y)
   int slabs;          // reduction slabs per output tile
   int units;          // tiles * slabs: the work, in slab iterations
   int units_per_wg;   // contiguous run of units each work-group takes

@@ -88,12 +88,13 @@ bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
   const TileVariant& tv = variant(v);
   if (tv.sched < 0) {
     if (!(lay.nhwc && d.kh == 3 && d.kw == 3 && d.stride == 1 && d.pad == 1)) return false;
-    if (lay.pool && ((d.h | d.w) & 1)) return false;
+    if (lay.pool == 2 || (lay.pool && ((d.h | d.w) & 1))) return false;
     // multi-image tiles are for maps that fit one tile; single-image tiles for the rest
     if (tv.ni > 1) return d.h <= tv.th && d.w <= tv.tw;
     return d.h * 2 > tv.th && d.w * 2 > tv.tw;
   }
-  if (lay.pool) return false;  // only the patch kernels fuse the pool
+  if (lay.pool == 1) return false;                // only the patch kernels fuse a spatial pool
+  if (lay.pool == 2 && !(lay.nhwc && (d.c_out & 3) == 0)) return false;
   const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
   const long P = (long)d.n * ho * wo;
   const long K = (long)(lay.nhwc ? lay.cp_in : d.c_in) * d.kh * d.kw;
@@ -156,6 +157,7 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
   a.Cop = lay.cp_out;
   a.magic_cp = magic_for((unsigned)lay.cp_in);
   a.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
+  a.pool4 = lay.pool == 2 ? 1 : 0;
   a.HoWo = a.Ho * a.Wo;
   a.P = d.n * a.HoWo;
   a.HW = d.h * d.w;

@@ -27,6 +27,14 @@ __device__ __forceinline__ uint4 load_b128(__amdgpu_buffer_rsrc_t r, unsigned vo
 // a lane holds 4 consecutive channels of one pixel.
 template <typename T>
 __device__ __forceinline__ void nhwc_store4(const ConvArgs& a, const float4_t& acc, int p, int o) {
+  if (a.pool4) {
+    if (o >= a.O) return;
+    float m = apply_act(acc[0] + (a.bias ? a.bias[o] : 0.0f), a.act);
+#pragma unroll
+    for (int i = 1; i < 4; ++i) m = fmaxf(m, apply_act(acc[i] + (a.bias ? a.bias[o + i] : 0.0f), a.act));
+    ((T*)a.y)[(size_t)p * a.Cop + (o >> 2)] = Elem<T>::from_f32(m);
+    return;
+  }
   if (o >= a.Cop) return;
   float v[4];
 #pragma unroll

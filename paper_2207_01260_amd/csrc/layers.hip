@@ -212,6 +212,30 @@ __global__ __launch_bounds__(256) void repack_weights_kernel(const T* __restrict
   y[i] = v;
 }
 
+// Every input pixel of a 2x2 map lies inside the 3x3 window (pad 1) of every output pixel, so
+// the layer is one dense matrix from the whole input map to the whole output map: the tap that
+// links input pixel (iy, ix) to output pixel (oy, ox) is (iy - oy + 1, ix - ox + 1).
+template <typename T>
+__global__ __launch_bounds__(256) void repack_map2x2_kernel(const T* __restrict__ w, const float* __restrict__ bias,
+                                                            T* __restrict__ y, float* __restrict__ bias_out, int o_count,
+                                                            int c, int cp_in, int cp_out, int rows_by_channel) {
+  const long total = (long)16 * cp_out * cp_in;
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int col = (int)(i % (4 * cp_in));
+  const int row = (int)(i / (4 * cp_in));
+  const int pi = col / cp_in, ch = col % cp_in;
+  const int po = rows_by_channel ? (row & 3) : row / cp_out;
+  const int o = rows_by_channel ? (row >> 2) : row % cp_out;
+  T v = (T)0.0f;
+  if (o < o_count && ch < c) {
+    const int u = (pi >> 1) - (po >> 1) + 1, t = (pi & 1) - (po & 1) + 1;
+    v = w[((long)o * c + ch) * 9 + u * 3 + t];
+  }
+  y[i] = v;
+  if (col == 0) bias_out[row] = (bias && o < o_count) ? bias[o] : 0.0f;
+}
+
 inline dim3 blocks_for(long total) { return dim3((unsigned)((total + 255) / 256)); }
 
 int plane_slices(int total) {
@@ -356,6 +380,15 @@ int launch_repack_weights(const void* w, int o, int c, int khw, int cp, int dt, 
   const long total = (long)o * khw * cp;
   CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_weights_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w,
                                          (T*)y, total, c, khw, cp));
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+int launch_repack_map2x2(const void* w, const float* bias, int o, int c, int cp_in, int cp_out,
+                         int rows_by_channel, int dt, void* w_out, float* bias_out, hipStream_t s) {
+  const long total = (long)16 * cp_out * cp_in;
+  CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_map2x2_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w, bias,
+                                         (T*)w_out, bias_out, o, c, cp_in, cp_out, rows_by_channel));
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }

@@ -82,6 +82,7 @@ def test_channel_sweep_points(orc, c_out, path):
     if path == "handle":
         handle = pipeline.build_net(net, layers, 8, tune=True)
         y = handle.forward(xd, use_graph=True).cpu().numpy()
+        assert y.shape == (8, c_out, 56, 56)
         v = handle.layer_variant(0)
         handle.close()
     else:
