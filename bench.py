@@ -106,6 +106,7 @@ def main():
     total_flops = pipeline.useful_flops(net, kept_counts, args.batch)
     achieved = conv_flops / (conv_ms * 1e-3) / 1e12
     per_layer = []
+    kernels = set()
     shp = synth.shapes(net, kept_counts)
     for i, (L, m) in enumerate(zip(net.layers, layer_ms)):
         if L.kind != "conv":
@@ -113,8 +114,13 @@ def main():
         cin, cout, ho, wo = shp[i]
         fl = 2.0 * args.batch * cout * cin * 9 * ho * wo
         tm, tp, sk = B.cprune_tile_variant_info(handle.layer_variant(i))
+        kern = "conv_patch_kernel" if sk < 0 else ("conv_nhwc_kernel" + ("+fixup" if sk > 0 else ""))
+        if ho == 2 and sk >= 0:
+            kern += " (2x2 map as one matrix)"
+        kernels.add(kern.split(" ")[0])
         per_layer.append({"layer": L.name, "c_in": cin, "c_out": cout, "hw": ho, "us": round(m * 1e3, 2),
-                          "tflops": round(fl / (m * 1e-3) / 1e12, 2), "tile": f"{tm}x{tp}/s{sk}"})
+                          "tflops": round(fl / (m * 1e-3) / 1e12, 2), "tile": f"{tm}x{tp}/s{sk}",
+                          "kernel": kern})
 
     out = {
         "metric": "images/sec pruned VGG-16 32x32",
@@ -128,7 +134,7 @@ def main():
         "useful_gflop_per_step": round(total_flops / 1e9, 3),
         "whole_net_tflops": round(total_flops / (ms * 1e-3) / 1e12, 2),
         "prune_ms": round(prune_ms, 3), "tune_s": round(tune_s, 2),
-        "roofline": {"bound": "mfma", "kernel": "conv_igemm_kernel (all conv layers of one step)",
+        "roofline": {"bound": "mfma", "kernel": " / ".join(sorted(kernels)) + " (the 13 conv layers of one step)",
                      "achieved": round(achieved, 2), "peak": PEAK[args.dtype], "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK[args.dtype], 4), "traffic": None,
                      "launches_per_step": n_conv, "avg_launch_us": round(conv_ms / n_conv * 1e3, 2),

@@ -216,8 +216,10 @@ int cprune_net_create(const cprune_layer_desc* layers, int n_layers, int in_c, i
  * first time a given (n, x, logits) triple is seen and kept until destroy. */
 int cprune_net_forward(cprune_net* net, const void* x, int n, void* logits, int use_graph,
                        void* stream);
-/* Per-layer device time of one forward, averaged over `iters` runs, bracketing
- * every layer with events on `stream`; ms_out: host [n_layers].  Synchronises. */
+/* Per-layer device time: after one untimed pass that gives every layer its inputs, each
+ * layer is launched `iters` times back to back between two events on `stream`; ms_out
+ * (host, [n_layers]) gets the time per launch (0 for a pool folded into its producer).
+ * Synchronises. */
 int cprune_net_layer_times(cprune_net* net, const void* x, int n, int iters, float* ms_out,
                            void* stream);
 /* Writes layer `layer`'s activation of the last forward (batch n) to dst (device) as dense

@@ -5,6 +5,7 @@
 #include <map>
 #include <mutex>
 #include <vector>
+#include <algorithm>
 #include <array>
 #include <cmath>
 #include <cstring>
@@ -106,7 +107,9 @@ static int conv_dispatch(const cprune_conv_desc& d, const void* x, const void* w
   return launch_conv_dense(d, x, w, bias, residual, y, v, ws, s, lay);
 }
 
-// Times every supported variant on the given buffers; returns the fastest.
+// Times every supported variant on the given buffers; returns the fastest.  Two stages: every
+// variant briefly, then the few best again with more repetitions, so that a short disturbance
+// (another process's burst, a clock change) during one measurement does not decide the choice.
 static int select_tile_impl(const cprune_conv_desc& d, const void* x, const void* w, const float* bias,
                             const void* residual, void* y, void* ws, size_t ws_bytes, int warmup,
                             int iters, int* variant_out, float* best_ms_out, float* all_ms_out,
@@ -115,9 +118,27 @@ static int select_tile_impl(const cprune_conv_desc& d, const void* x, const void
   CPRUNE_HIP_TRY(hipEventCreate(&e0));
   hipError_t ee = hipEventCreate(&e1);
   if (ee != hipSuccess) { hipEventDestroy(e0); set_last_hip_error(ee); return CPRUNE_ERR_DEVICE; }
-  int best_v = -1;
-  float best_ms = 0.0f;
   int rc = CPRUNE_OK;
+  // fastest of `passes` timed passes of `n` launches each, per launch
+  auto time_variant = [&](int v, int n, int passes, float* ms_out) -> int {
+    float ms = 0.0f;
+    for (int pass = 0; pass < passes; ++pass) {
+      int r = CPRUNE_OK;
+      hipError_t e = hipEventRecord(e0, s);
+      for (int i = 0; i < n && r == CPRUNE_OK; ++i) r = conv_dispatch(d, x, w, bias, residual, y, v, ws, ws_bytes, s, lay);
+      if (r != CPRUNE_OK) return r;
+      if (e == hipSuccess) e = hipEventRecord(e1, s);
+      if (e == hipSuccess) e = hipEventSynchronize(e1);
+      float t = 0.0f;
+      if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+      if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
+      t /= (float)n;
+      if (pass == 0 || t < ms) ms = t;
+    }
+    *ms_out = ms;
+    return CPRUNE_OK;
+  };
+  std::vector<std::pair<float, int>> timed;
   const int nv = d.groups == 1 ? num_variants() : 1;
   for (int v = 0; v < nv && rc == CPRUNE_OK; ++v) {
     if (all_ms_out) all_ms_out[v] = -1.0f;
@@ -127,31 +148,32 @@ static int select_tile_impl(const cprune_conv_desc& d, const void* x, const void
     }
     for (int i = 0; i < warmup && rc == CPRUNE_OK; ++i) rc = conv_dispatch(d, x, w, bias, residual, y, v, ws, ws_bytes, s, lay);
     if (rc != CPRUNE_OK) break;
-    // two timed passes, the faster one counts: a pass disturbed by another process's
-    // burst or a clock change must not decide the choice
     float ms = 0.0f;
-    for (int pass = 0; pass < 2 && rc == CPRUNE_OK; ++pass) {
-      hipError_t e = hipEventRecord(e0, s);
-      for (int i = 0; i < iters && rc == CPRUNE_OK; ++i) rc = conv_dispatch(d, x, w, bias, residual, y, v, ws, ws_bytes, s, lay);
-      if (e == hipSuccess) e = hipEventRecord(e1, s);
-      if (e == hipSuccess) e = hipEventSynchronize(e1);
-      float t = 0.0f;
-      if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
-      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
-      t /= (float)iters;
-      if (pass == 0 || t < ms) ms = t;
-    }
+    rc = time_variant(v, iters, 2, &ms);
     if (rc != CPRUNE_OK) break;
     if (all_ms_out) all_ms_out[v] = ms;
-    if (best_v < 0 || ms < best_ms) { best_v = v; best_ms = ms; }
+    timed.emplace_back(ms, v);
+  }
+  if (rc == CPRUNE_OK && timed.size() > 1) {
+    std::sort(timed.begin(), timed.end());
+    const size_t finalists = timed.size() < 4 ? timed.size() : 4;
+    for (size_t k = 0; k < finalists && rc == CPRUNE_OK; ++k) {
+      float ms = 0.0f;
+      rc = time_variant(timed[k].second, 3 * iters, 3, &ms);
+      if (rc != CPRUNE_OK) break;
+      timed[k].first = ms;
+      if (all_ms_out) all_ms_out[timed[k].second] = timed[k].first;
+    }
+    std::sort(timed.begin(), timed.begin() + finalists);
   }
   hipEventDestroy(e0);
   hipEventDestroy(e1);
   if (rc != CPRUNE_OK) return rc;
-  if (best_v < 0) return CPRUNE_ERR_WORKSPACE;
+  if (timed.empty()) return CPRUNE_ERR_WORKSPACE;
+  const int best_v = timed[0].second;
   if (d.groups == 1) remember_variant(d, best_v, lay);
   if (variant_out) *variant_out = best_v;
-  if (best_ms_out) *best_ms_out = best_ms;
+  if (best_ms_out) *best_ms_out = timed[0].first;
   return CPRUNE_OK;
 }
 
@@ -604,32 +626,29 @@ extern "C" int cprune_net_layer_times(cprune_net* net, const void* x, int n, int
   if (n < 1 || n > net->max_batch) return CPRUNE_ERR_INVALID_ARG;
   hipStream_t s = (hipStream_t)stream;
   const int nl = (int)net->layers.size();
-  std::vector<hipEvent_t> ev(nl + 1, nullptr);
-  int rc = CPRUNE_OK;
-  for (int i = 0; i <= nl; ++i) {
-    hipError_t e = hipEventCreate(&ev[i]);
-    if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
-  }
-  for (int i = 0; i < nl; ++i) ms_out[i] = 0.0f;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  CPRUNE_HIP_TRY(hipEventCreate(&e0));
+  hipError_t ec = hipEventCreate(&e1);
+  if (ec != hipSuccess) { hipEventDestroy(e0); set_last_hip_error(ec); return CPRUNE_ERR_DEVICE; }
   net->last_n = n;
-  rc = rc == CPRUNE_OK ? launch_nchw_to_nhwc(x, n, net->in_c, net->in_h * net->in_w, net->in_cp, net->dtype, net->x_cl, s) : rc;
-  for (int it = 0; it < iters && rc == CPRUNE_OK; ++it) {
-    for (int i = 0; i < nl && rc == CPRUNE_OK; ++i) {
-      hipError_t e = hipEventRecord(ev[i], s);
-      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
-      rc = net_run_layer(net, i, n, nullptr, s);
-    }
-    if (rc != CPRUNE_OK) break;
-    hipError_t e = hipEventRecord(ev[nl], s);
-    if (e == hipSuccess) e = hipEventSynchronize(ev[nl]);
-    for (int i = 0; i < nl && e == hipSuccess; ++i) {
-      float ms = 0.0f;
-      e = hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
-      ms_out[i] += ms / (float)iters;
-    }
-    if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
+  int rc = launch_nchw_to_nhwc(x, n, net->in_c, net->in_h * net->in_w, net->in_cp, net->dtype, net->x_cl, s);
+  // layer by layer, in order (so every layer finds its inputs): `iters` launches back to
+  // back between two events, which is how the layer runs inside a forward pass
+  for (int i = 0; i < nl && rc == CPRUNE_OK; ++i) {
+    ms_out[i] = 0.0f;
+    rc = net_run_layer(net, i, n, nullptr, s);   // untimed first run
+    if (rc != CPRUNE_OK || net->layers[i].alias) continue;
+    hipError_t e = hipEventRecord(e0, s);
+    for (int it = 0; it < iters && rc == CPRUNE_OK && e == hipSuccess; ++it) rc = net_run_layer(net, i, n, nullptr, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
+    ms_out[i] = ms / (float)iters;
   }
-  for (int i = 0; i <= nl; ++i) if (ev[i]) hipEventDestroy(ev[i]);
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
   return rc;
 }
 
