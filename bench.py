@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip batch-1 and fp16 side figures")
     ap.add_argument("--cpu-images", type=int, default=0, help="oracle sample size (0 = auto)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB channel copy (gather_channels_kernel with the identity "
+                         "list) three times, as the known-size reference for HBM traffic counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -142,6 +145,16 @@ def main():
         "layers": per_layer,
     }
     handle.close()
+
+    if args.copy_calibration:
+        big = torch.zeros((1, 64, 1024, 1024), dtype=torch.float32, device="cuda")
+        ident = torch.arange(64, dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            B.cprune_gather_channels(big, ident)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"kernel": "gather_channels_kernel", "bytes_read": big.numel() * 4,
+                                   "bytes_written": big.numel() * 4, "launches": 3}
+        del big
 
     if not args.no_extras:
         extras = {}

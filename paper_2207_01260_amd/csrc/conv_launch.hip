@@ -138,6 +138,7 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     pa.w_bytes = (unsigned)((size_t)d.c_out * 9 * lay.cp_in * es);
     pa.act = d.act;
     pa.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
+    pa.m_major = pa.w_bytes > pa.x_bytes ? 1 : 0;
     dim3 pgrid((unsigned)(pa.tiles_n * pa.tiles_y * pa.tiles_x * pa.tiles_m));
     if (d.dtype == CPRUNE_F32) launch_conv_patch_f32(tv.patch_id, pgrid, s, pa);
     else if (d.dtype == CPRUNE_F16) launch_conv_patch_f16(tv.patch_id, pgrid, s, pa);

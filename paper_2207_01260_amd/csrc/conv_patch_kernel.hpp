@@ -34,6 +34,9 @@ struct PatchArgs {
   unsigned x_bytes, w_bytes;
   int act, vec_out;
   int pool;   // 1: 2x2 / stride 2 max-pool fused behind the activation; y is [n][h/2][w/2][cop]
+  int m_major;  // tile order: 0 = filter tiles fastest (each chip quarter's L2 sees few input patches, all
+                // weights), 1 = pixel tiles fastest (few filters, all patches): whichever operand is larger
+                // is the one split between the L2s
 };
 
 // One 64-byte round of MFMAs on NS accumulator sets.  A tile with fewer than four
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
   const int kgrp = t >> 8;                // which share of the rounds it multiplies
   const int r = lane & 15, g4 = lane >> 4;
 
-  // tile decode: filters fastest, so neighbouring groups share the patch in L2
+  // tile decode; each XCD (own L2) gets one contiguous stretch of the tile order
   int tile;
   {
     const int G = gridDim.x;
@@ -109,8 +112,9 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
     const int q = G >> 3, rem = G & 7;
     tile = xcd * q + (xcd < rem ? xcd : rem) + local;
   }
-  const int tile_m = tile % a.tiles_m;
-  int rest = tile / a.tiles_m;
+  const int tiles_s = a.tiles_n * a.tiles_y * a.tiles_x;
+  const int tile_m = a.m_major ? tile / tiles_s : tile % a.tiles_m;
+  int rest = a.m_major ? tile % tiles_s : tile / a.tiles_m;
   const int tx0 = (rest % a.tiles_x) * TW;
   rest /= a.tiles_x;
   const int ty0 = (rest % a.tiles_y) * TH;
