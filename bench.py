@@ -21,6 +21,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}   # dense MFMA TFLOP/s, MI355X
+# Bytes between L2 and fabric per conv layer launch (FETCH_SIZE + WRITE_SIZE of all conv kernels of a
+# step, scaled by a copy kernel of known size, / 13) for the default workload, from the rocprofv3
+# counter runs summarised in profiles/vgg16_b64_f32_hbm_traffic.md.  Valid for that workload only.
+TRAFFIC_F32_B64 = 10.05 * 2 ** 20
 
 
 def main():
@@ -34,6 +38,10 @@ def main():
                     help="0 layer-by-layer launches, 1 HIP graph replay, -1 (default) the faster of "
                          "the two by a short untimed trial")
     ap.add_argument("--no-tune", action="store_true")
+    ap.add_argument("--variants", default="",
+                    help="comma-separated tile variants of the dense layers in network order (the "
+                         "`variants` list an earlier run printed): applied instead of timing, so that a run "
+                         "under a profiler, which disturbs the timing, executes the same kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip batch-1 and fp16 side figures")
     ap.add_argument("--cpu-images", type=int, default=0, help="oracle sample size (0 = auto)")
@@ -90,7 +98,14 @@ def main():
     prune_ms = (time.perf_counter() - t0) / reps * 1e3
 
     # ---- main measurement -------------------------------------------------------------
-    handle, layers, kept, tune_s = build(dt, args.batch, not args.no_tune)
+    pinned = [int(v) for v in args.variants.split(",") if v != ""]
+    handle, layers, kept, tune_s = build(dt, args.batch, not (args.no_tune or pinned))
+    dense = [i for i, L in enumerate(net.layers) if L.kind in ("conv", "fc")]
+    if pinned:
+        assert len(pinned) == len(dense), "--variants needs one entry per conv / fc layer"
+        for i, v in zip(dense, pinned):
+            handle.set_layer_variant(i, v)
+    variants = [handle.layer_variant(i) for i in dense]
     kept_counts = {i: int(k.numel()) for i, k in kept.items()}
     x = torch.from_numpy(synth.net_input(net, cid, args.batch)).cuda().to(B.TORCH_DTYPE[dt])
     graph = args.graph
@@ -136,10 +151,12 @@ def main():
                    "kept_filters": [kept_counts[i] for i in sorted(kept_counts)]},
         "useful_gflop_per_step": round(total_flops / 1e9, 3),
         "whole_net_tflops": round(total_flops / (ms * 1e-3) / 1e12, 2),
-        "prune_ms": round(prune_ms, 3), "tune_s": round(tune_s, 2),
+        "prune_ms": round(prune_ms, 3), "tune_s": round(tune_s, 2), "variants": variants,
         "roofline": {"bound": "mfma", "kernel": " / ".join(sorted(kernels)) + " (the 13 conv layers of one step)",
                      "achieved": round(achieved, 2), "peak": PEAK[args.dtype], "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK[args.dtype], 4), "traffic": None,
+                     "frac": round(achieved / PEAK[args.dtype], 4),
+                     "traffic": (round(TRAFFIC_F32_B64) if (args.dtype == "f32" and args.batch == 64) else None),
+                     "traffic_unit": "bytes per conv layer (FETCH_SIZE + WRITE_SIZE, scaled; algorithmic: 5.29e6)",
                      "launches_per_step": n_conv, "avg_launch_us": round(conv_ms / n_conv * 1e3, 2),
                      "useful_gflop_per_launch_avg": round(conv_flops / n_conv / 1e9, 3)},
         "layers": per_layer,

@@ -233,6 +233,11 @@ int cprune_net_copy_activation(cprune_net* net, int layer, int n, void* dst, siz
 int cprune_net_output_shape(const cprune_net* net, int* c_out, int* h_out, int* w_out);
 /* The tile variant in use for layer `layer` (-1 for layers without one); host out. */
 int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out);
+/* Pins the tile variant of a dense conv / fully connected layer (what a stored tuning result
+ * is applied with).  CPRUNE_ERR_INVALID_ARG for a layer without variants,
+ * CPRUNE_ERR_UNSUPPORTED when the variant cannot run that layer's shape.  Recorded graphs
+ * are dropped (they hold the old choice).  Not to be called while a forward is in flight. */
+int cprune_net_set_layer_variant(cprune_net* net, int layer, int variant);
 int cprune_net_destroy(cprune_net* net);
 
 #ifdef __cplusplus

@@ -47,7 +47,7 @@ EXPORTS = [
     "cprune_fc_workspace_bytes", "cprune_fc",
     "cprune_net_create", "cprune_net_forward", "cprune_net_layer_times",
     "cprune_net_copy_activation", "cprune_net_output_shape", "cprune_net_layer_variant",
-    "cprune_net_destroy",
+    "cprune_net_set_layer_variant", "cprune_net_destroy",
 ]
 
 _lib = None
@@ -308,6 +308,10 @@ class Net:
                                               _stream(stream))
         _check(st, "cprune_net_copy_activation")
         return out
+
+    def set_layer_variant(self, layer: int, variant: int):
+        _check(lib().cprune_net_set_layer_variant(self._h, C.c_int(layer), C.c_int(variant)),
+               "cprune_net_set_layer_variant")
 
     def layer_variant(self, layer: int) -> int:
         v = C.c_int()

@@ -676,6 +676,21 @@ extern "C" int cprune_net_layer_variant(const cprune_net* net, int layer, int* v
   return CPRUNE_OK;
 }
 
+extern "C" int cprune_net_set_layer_variant(cprune_net* net, int layer, int variant) {
+  if (!net || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
+  NetLayer& L = net->layers[layer];
+  if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) return CPRUNE_ERR_INVALID_ARG;
+  const cprune_conv_desc cd = layer_conv_desc(*net, L, net->max_batch);
+  const ConvLayout lay = layer_layout(L);
+  if (!variant_supports(cd, variant, lay)) return CPRUNE_ERR_UNSUPPORTED;
+  if (conv_ws_bytes(cd, variant, lay) > net->ws_bytes) return CPRUNE_ERR_WORKSPACE;
+  CPRUNE_HIP_TRY(hipDeviceSynchronize());
+  for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
+  net->graphs.clear();
+  L.variant = variant;
+  return CPRUNE_OK;
+}
+
 extern "C" int cprune_net_destroy(cprune_net* net) {
   if (!net) return CPRUNE_ERR_INVALID_ARG;
   hipError_t e = hipDeviceSynchronize();
