@@ -240,6 +240,18 @@ int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out)
 int cprune_net_set_layer_variant(cprune_net* net, int layer, int variant);
 int cprune_net_destroy(cprune_net* net);
 
+/* ---- measured ceilings (for reporting kernel throughput against what the device
+ * delivers, next to its datasheet peaks; the paper reports end-to-end rates only) ----
+ * cprune_probe_mfma: rate of back-to-back dense MFMA instructions of `dtype` on register
+ * operands, no memory traffic (the better of the 16x16 and the 32x32 block forms); scratch: device, >= cprune_probe_scratch_bytes() (values
+ * written there are meaningless); tflops_out: host.  cprune_probe_copy: rate of a plain
+ * copy of `bytes` (a multiple of 16) from src to dst (device, 16-byte aligned, not
+ * overlapping), counted as bytes read + bytes written; gbps_out: host.  Both synchronise. */
+size_t cprune_probe_scratch_bytes(void);
+int cprune_probe_mfma(cprune_dtype dtype, void* scratch, size_t scratch_bytes, float* tflops_out,
+                      void* stream);
+int cprune_probe_copy(const void* src, void* dst, size_t bytes, float* gbps_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

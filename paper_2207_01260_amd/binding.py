@@ -48,6 +48,7 @@ EXPORTS = [
     "cprune_net_create", "cprune_net_forward", "cprune_net_layer_times",
     "cprune_net_copy_activation", "cprune_net_output_shape", "cprune_net_layer_variant",
     "cprune_net_set_layer_variant", "cprune_net_destroy",
+    "cprune_probe_scratch_bytes", "cprune_probe_mfma", "cprune_probe_copy",
 ]
 
 _lib = None
@@ -73,7 +74,7 @@ def lib():
         L.cprune_status_string.restype = C.c_char_p
         L.cprune_status_string.argtypes = [C.c_int]
         for name in ("cprune_rank_filters_workspace_bytes", "cprune_conv_workspace_bytes",
-                     "cprune_fc_workspace_bytes"):
+                     "cprune_fc_workspace_bytes", "cprune_probe_scratch_bytes"):
             getattr(L, name).restype = C.c_size_t
         L.cprune_clear_tile_cache.restype = None
         _lib = L
@@ -258,6 +259,28 @@ def cprune_fc(x, w, bias=None, act=ACT_NONE, stream=None):
                          _stream(stream))
     _check(st, "cprune_fc")
     return y
+
+
+# ---- measured ceilings ---------------------------------------------------------
+
+def cprune_probe_mfma(dtype: int = F32, stream=None) -> float:
+    """TFLOP/s of back-to-back MFMA instructions of `dtype` on register operands."""
+    ws = _ws(lib().cprune_probe_scratch_bytes(), "cuda")
+    out = C.c_float(0.0)
+    st = lib().cprune_probe_mfma(C.c_int(dtype), _ptr(ws), C.c_size_t(ws.numel()), C.byref(out),
+                                 _stream(stream))
+    _check(st, "cprune_probe_mfma")
+    return float(out.value)
+
+
+def cprune_probe_copy(nbytes: int = 1 << 30, stream=None) -> float:
+    """GB/s (read + written) of a plain device copy of `nbytes`."""
+    src = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    out = C.c_float(0.0)
+    st = lib().cprune_probe_copy(_ptr(src), _ptr(dst), C.c_size_t(nbytes), C.byref(out), _stream(stream))
+    _check(st, "cprune_probe_copy")
+    return float(out.value)
 
 
 # ---- network handle ------------------------------------------------------------

@@ -171,6 +171,111 @@ __global__ __launch_bounds__(256) void depthwise_nhwc_kernel(const T* __restrict
   st(y + i, act_f(acc, act));
 }
 
+// Channels-last depthwise, vectorised: a thread owns one 16-byte channel vector (4 floats /
+// 8 halves) of TX neighbouring output pixels of a row.  Consecutive lanes take consecutive
+// channel vectors, so every access is a coalesced 16-byte load or store; the K x K weights of
+// the vector sit in registers; each input column loaded serves every output of the run whose
+// window covers it ((TX - 1) * S + K loads per row for TX outputs instead of TX * K).
+template <typename T> struct VecOf;
+template <> struct VecOf<float> { static constexpr int V = 4; };
+template <> struct VecOf<_Float16> { static constexpr int V = 8; };
+template <> struct VecOf<__bf16> { static constexpr int V = 8; };
+
+template <typename T, int V>
+__device__ __forceinline__ void unpack16(const uint4& q, float (&f)[V]) {
+  if constexpr (V == 4) {
+    f[0] = __uint_as_float(q.x); f[1] = __uint_as_float(q.y); f[2] = __uint_as_float(q.z); f[3] = __uint_as_float(q.w);
+  } else {
+    const T* h = reinterpret_cast<const T*>(&q);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = (float)h[i];
+  }
+}
+
+template <typename T, int K, int S, int TX>
+__global__ __launch_bounds__(256) void depthwise_nhwc_vec_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                                 const float* __restrict__ bias,
+                                                                 const T* __restrict__ res, T* __restrict__ y,
+                                                                 unsigned total, int c_real, int cp, int h, int wd,
+                                                                 int ho, int wo, int xblocks, int pad, int act) {
+  constexpr int V = VecOf<T>::V;
+  constexpr int NIN = (TX - 1) * S + K;
+  const unsigned idx = blockIdx.x * 256u + threadIdx.x;
+  if (idx >= total) return;
+  const unsigned nvec = (unsigned)cp / V;
+  const unsigned cv = idx % nvec;
+  unsigned r = idx / nvec;
+  const int xb = (int)(r % (unsigned)xblocks); r /= (unsigned)xblocks;
+  const int oy = (int)(r % (unsigned)ho);
+  const int n = (int)(r / (unsigned)ho);
+  const int c0 = (int)cv * V;
+
+  float wk[K * K][V];
+#pragma unroll
+  for (int i = 0; i < K * K; ++i) unpack16<T, V>(*reinterpret_cast<const uint4*>(w + (size_t)i * cp + c0), wk[i]);
+  float acc[TX][V];
+#pragma unroll
+  for (int t = 0; t < TX; ++t)
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[t][e] = 0.0f;
+
+  const int ox0 = xb * TX;
+  const int ix_base = ox0 * S - pad;
+#pragma unroll
+  for (int u = 0; u < K; ++u) {
+    const int iy = oy * S - pad + u;
+    if ((unsigned)iy >= (unsigned)h) continue;
+    const T* row = x + ((size_t)(n * h + iy) * wd) * cp + c0;
+#pragma unroll
+    for (int j = 0; j < NIN; ++j) {
+      const int ix = ix_base + j;
+      float in[V];
+      if ((unsigned)ix < (unsigned)wd) {
+        unpack16<T, V>(*reinterpret_cast<const uint4*>(row + (size_t)ix * cp), in);
+      } else {
+#pragma unroll
+        for (int e = 0; e < V; ++e) in[e] = 0.0f;
+      }
+#pragma unroll
+      for (int t = 0; t < TX; ++t) {
+        const int v = j - t * S;
+        if (v >= 0 && v < K) {
+#pragma unroll
+          for (int e = 0; e < V; ++e) acc[t][e] += in[e] * wk[u * K + v][e];
+        }
+      }
+    }
+  }
+  float bv[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) bv[e] = (bias && c0 + e < c_real) ? bias[c0 + e] : 0.0f;
+#pragma unroll
+  for (int t = 0; t < TX; ++t) {
+    const int ox = ox0 + t;
+    if (ox >= wo) break;
+    const size_t off = ((size_t)(n * ho + oy) * wo + ox) * cp + c0;
+    float o[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) o[e] = acc[t][e] + bv[e];
+    if (res) {
+      float rv[V];
+      unpack16<T, V>(*reinterpret_cast<const uint4*>(res + off), rv);
+#pragma unroll
+      for (int e = 0; e < V; ++e) o[e] += rv[e];
+    }
+    uint4 q;
+    if constexpr (V == 4) {
+      q.x = __float_as_uint(act_f(o[0], act)); q.y = __float_as_uint(act_f(o[1], act));
+      q.z = __float_as_uint(act_f(o[2], act)); q.w = __float_as_uint(act_f(o[3], act));
+    } else {
+      T* hq = reinterpret_cast<T*>(&q);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) hq[e] = (T)act_f(o[e], act);
+    }
+    *reinterpret_cast<uint4*>(y + off) = q;
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void nchw_to_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y,
                                                            long total, int c, int hw, int cp) {
@@ -335,6 +440,35 @@ template <typename T>
 static int depthwise_nhwc_dispatch(const cprune_conv_desc& d, int cp, const void* x, const void* w,
                                    const float* bias, const void* res, void* y, hipStream_t s) {
   const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
+  constexpr int V = VecOf<T>::V;
+  // vectorised kernel: 3x3 and 5x5 at stride 1 or 2, channel stride a whole number of vectors;
+  // four outputs per thread when that still leaves every compute unit several work-groups
+  if ((d.kh == 3 || d.kh == 5) && (d.stride == 1 || d.stride == 2) && cp % V == 0) {
+    const long per_row = (long)d.n * ho * (cp / V);
+    const int tx = per_row * ((wo + 3) / 4) >= 256L * 1024 ? 4 : 1;
+    const int xblocks = (wo + tx - 1) / tx;
+    const long total = per_row * xblocks;
+    if (total < (1L << 32)) {
+#define GOV(K, S, TX)                                                                                           \
+      hipLaunchKernelGGL((depthwise_nhwc_vec_kernel<T, K, S, TX>), blocks_for(total), dim3(256), 0, s, (const T*)x, \
+                         (const T*)w, bias, (const T*)res, (T*)y, (unsigned)total, d.c_in, cp, d.h, d.w, ho, wo,  \
+                         xblocks, d.pad, d.act)
+      const int key = d.kh * 100 + d.stride * 10 + tx;
+      switch (key) {
+        case 311: GOV(3, 1, 1); break;
+        case 314: GOV(3, 1, 4); break;
+        case 321: GOV(3, 2, 1); break;
+        case 324: GOV(3, 2, 4); break;
+        case 511: GOV(5, 1, 1); break;
+        case 514: GOV(5, 1, 4); break;
+        case 521: GOV(5, 2, 1); break;
+        case 524: GOV(5, 2, 4); break;
+      }
+#undef GOV
+      CPRUNE_LAUNCH_CHECK();
+      return CPRUNE_OK;
+    }
+  }
   const long total = (long)d.n * ho * wo * cp;
 #define GO(K)                                                                                          \
   hipLaunchKernelGGL((depthwise_nhwc_kernel<T, K>), blocks_for(total), dim3(256), 0, s, (const T*)x,   \

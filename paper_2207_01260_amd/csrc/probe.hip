@@ -1,0 +1,143 @@
+// Measured ceilings of the device, next to which kernel throughput is reported: the
+// rate of back-to-back MFMA instructions on register operands (no memory traffic at all),
+// and the rate of a plain device-to-device copy.
+#include "common.hpp"
+#include <functional>
+
+namespace cprune {
+namespace {
+
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kProbeGroups = 2048;   // 8 work-groups of 4 wavefronts per compute unit
+
+// DT 0: fp32, 1: fp16, 2: bf16.  BIG 0: 16x16 blocks (x4 fp32, x32 16-bit), 16 independent
+// accumulators; BIG 1: 32x32 blocks (x2 fp32, x16 16-bit), 4 accumulators.
+template <int DT, int BIG>
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters, float seed) {
+  const float av = seed + (float)threadIdx.x * 1e-3f, bv = seed * 0.5f;
+  half8_t ah, bh;
+  bf16x8_t ab, bb;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { ah[e] = (_Float16)av; bh[e] = (_Float16)bv; ab[e] = (__bf16)av; bb[e] = (__bf16)bv; }
+  float s = 0.f;
+  if constexpr (BIG == 0) {
+    constexpr int NA = 16;
+    float4_t acc[NA];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) acc[i] = (float4_t){0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) {
+        if constexpr (DT == 0) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[i], 0, 0, 0);
+        else if constexpr (DT == 1) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh, acc[i], 0, 0, 0);
+        else acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bb, acc[i], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NA; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  } else {
+    constexpr int NA = 4;
+    float16_t acc[NA];
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) {
+        if constexpr (DT == 0) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i], 0, 0, 0);
+        else if constexpr (DT == 1) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh, acc[i], 0, 0, 0);
+        else acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, bb, acc[i], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s += acc[i][j];
+  }
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+int timed(hipStream_t s, int reps, float* ms_out, const std::function<void()>& launch) {
+  hipEvent_t e0, e1;
+  CPRUNE_HIP_TRY(hipEventCreate(&e0));
+  hipError_t e = hipEventCreate(&e1);
+  if (e != hipSuccess) { hipEventDestroy(e0); set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
+  float best = 0.f;
+  launch();   // warm-up
+  for (int r = 0; r < reps && e == hipSuccess; ++r) {
+    e = hipEventRecord(e0, s);
+    launch();
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (r == 0 || ms < best) best = ms;
+  }
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
+  *ms_out = best;
+  return CPRUNE_OK;
+}
+
+}  // namespace
+}  // namespace cprune
+
+using namespace cprune;
+
+extern "C" size_t cprune_probe_scratch_bytes(void) { return (size_t)kProbeGroups * 256 * sizeof(float); }
+
+extern "C" int cprune_probe_mfma(cprune_dtype dtype, void* scratch, size_t scratch_bytes, float* tflops_out,
+                                 void* stream) {
+  if (!scratch || !tflops_out || !dtype_ok(dtype)) return CPRUNE_ERR_INVALID_ARG;
+  if (scratch_bytes < cprune_probe_scratch_bytes()) return CPRUNE_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const int iters = 2000;
+  float best = 0.f;
+  for (int big = 0; big < 2; ++big) {
+    float ms = 0.f;
+    int rc = timed(s, 3, &ms, [&]() {
+#define CPRUNE_PROBE(DT, BIG) hipLaunchKernelGGL((mfma_probe_kernel<DT, BIG>), dim3(kProbeGroups), dim3(256), 0, s, (float*)scratch, iters, 1.0f)
+      if (dtype == CPRUNE_F32) { if (big) CPRUNE_PROBE(0, 1); else CPRUNE_PROBE(0, 0); }
+      else if (dtype == CPRUNE_F16) { if (big) CPRUNE_PROBE(1, 1); else CPRUNE_PROBE(1, 0); }
+      else { if (big) CPRUNE_PROBE(2, 1); else CPRUNE_PROBE(2, 0); }
+#undef CPRUNE_PROBE
+    });
+    if (rc != CPRUNE_OK) return rc;
+    // 16x16x4 and 32x32x2 (fp32) are 2048 / 4096 FLOP, 16x16x32 and 32x32x16 (16-bit) 16384 / 32768
+    const double flop_per_mfma = (dtype == CPRUNE_F32 ? 2048.0 : 16384.0) * (big ? 2.0 : 1.0);
+    const double flops = (double)kProbeGroups * 4 * iters * (big ? 4 : 16) * flop_per_mfma;
+    const float t = (float)(flops / (ms * 1e-3) / 1e12);
+    if (t > best) best = t;
+  }
+  *tflops_out = best;
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_probe_copy(const void* src, void* dst, size_t bytes, float* gbps_out, void* stream) {
+  if (!src || !dst || !gbps_out || bytes < 16 || (bytes & 15)) return CPRUNE_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  float ms = 0.f;
+  const size_t n16 = bytes / 16;
+  size_t groups = (n16 + 255) / 256;
+  if (groups > 16384) groups = 16384;
+  int rc = timed(s, 5, &ms, [&]() {
+    hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)groups), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n16);
+  });
+  if (rc != CPRUNE_OK) return rc;
+  *gbps_out = (float)(2.0 * (double)bytes / (ms * 1e-3) / 1e9);   // bytes read + bytes written
+  return CPRUNE_OK;
+}

@@ -1,0 +1,133 @@
+"""Per-configuration report: every evaluated workload shape of the paper (Section 4: VGG-16
+on CIFAR-sized inputs, ResNet-18 and MobileNetV2 on ImageNet-sized inputs) as a seeded,
+synthetic, channel-pruned network, plus the single pruned layer and the measured ceilings of
+the device.  One JSON object per line.
+
+    python -m paper_2207_01260_amd.report [--quick]
+
+For each network and batch: images/s and ms per forward (HIP graph replay or eager launches,
+whichever is faster), useful TFLOP/s on the pruned channel counts, and the device time by
+layer kind (dense conv / depthwise / pool / fc) with what bounds it: dense layers against the
+MFMA peak of the dtype, depthwise and pools against HBM bandwidth by the bytes they must move
+(input once + output once); dense layers also show that byte rate (input, weights and output
+once), since 1x1 layers with few channels are bandwidth-bound rather than MFMA-bound.
+"""
+import argparse
+import json
+import time
+
+import torch
+
+from . import binding as B
+from . import pipeline, synth
+
+PEAK_TFLOPS = {B.F32: 157.3, B.F16: 2500.0, B.BF16: 2500.0}
+PEAK_GBS = 8000.0
+DT_NAME = {B.F32: "f32", B.F16: "f16", B.BF16: "bf16"}
+
+
+def time_forward(handle, x, steps, graph):
+    out = handle.forward(x, use_graph=graph)
+    for _ in range(5):
+        handle.forward(x, out, use_graph=graph)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        handle.forward(x, out, use_graph=graph)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
+def net_report(name, net, cid, batch, dtype, steps):
+    params = synth.layer_params(net, cid)
+    dparams = pipeline.upload_params(params)
+    layers, kept = pipeline.prune_net(net, dparams, dtype)
+    kept_counts = {i: int(k.numel()) for i, k in kept.items()}
+    handle = pipeline.build_net(net, layers, batch, dtype, tune=True)
+    x = torch.from_numpy(synth.net_input(net, cid, batch)).cuda().to(B.TORCH_DTYPE[dtype])
+    ms = min(time_forward(handle, x, steps, g) for g in (False, True))
+    lt = handle.layer_times(x, iters=10)
+    shp = synth.shapes(net, kept_counts)
+    es = 4 if dtype == B.F32 else 2
+    groups = {}
+    for i, (L, t) in enumerate(zip(net.layers, lt)):
+        cin, cout, ho, wo = shp[i]
+        hin, win = (net.in_h, net.in_w) if L.input < 0 else shp[L.input][2:4]
+        moved = es * batch * (cin * hin * win + cout * ho * wo)   # input once + output once
+        if L.kind == "conv" and L.groups == 1:
+            kind, fl = "dense_conv", 2.0 * batch * cout * cin * L.k * L.k * ho * wo
+            by = moved + es * cout * cin * L.k * L.k
+        elif L.kind == "conv":
+            kind, fl, by = "depthwise", 2.0 * batch * cout * L.k * L.k * ho * wo, moved
+        elif L.kind == "fc":
+            kind, fl, by = "fc", 2.0 * batch * cin * hin * win * cout, 0.0
+        else:
+            kind, fl, by = "pool", 0.0, (moved if t > 0 else 0.0)
+        g = groups.setdefault(kind, {"ms": 0.0, "flop": 0.0, "bytes": 0.0, "launches": 0})
+        g["ms"] += t; g["flop"] += fl; g["bytes"] += by; g["launches"] += 1 if t > 0 else 0
+    by_kind = {}
+    for kind, g in groups.items():
+        row = {"ms": round(g["ms"], 4), "layers": g["launches"]}
+        if g["flop"] and kind in ("dense_conv", "fc") and g["ms"] > 0:
+            tf = g["flop"] / (g["ms"] * 1e-3) / 1e12
+            row.update(tflops=round(tf, 2), frac_mfma_peak=round(tf / PEAK_TFLOPS[dtype], 4))
+        if g["bytes"] and g["ms"] > 0:
+            gbs = g["bytes"] / (g["ms"] * 1e-3) / 1e9
+            row.update(gbs=round(gbs, 1), frac_hbm_peak=round(gbs / PEAK_GBS, 4))
+        by_kind[kind] = row
+    total = pipeline.useful_flops(net, kept_counts, batch)
+    handle.close()
+    return {"config": name, "batch": batch, "dtype": DT_NAME[dtype], "images_per_s": round(batch / (ms * 1e-3), 1),
+            "ms_per_forward": round(ms, 4), "useful_gflop": round(total / 1e9, 3),
+            "useful_tflops": round(total / (ms * 1e-3) / 1e12, 2), "by_layer_kind": by_kind}
+
+
+def single_layer_report(steps):
+    """One 3x3 conv + BN + ReLU at 32x32, 64 filters pruned to 45 by L1 rank, batch 1:
+    latency-bound (53 MFLOP), so microseconds are the figure."""
+    net = synth.single_conv(64, 64, 32)
+    params = synth.layer_params(net, 1)
+    dparams = pipeline.upload_params(params)
+    rows = []
+    for keep in (45, 64):
+        layers, _ = pipeline.prune_net(net, dparams, B.F32, keep_override={0: keep})
+        handle = pipeline.build_net(net, layers, 1, B.F32, tune=True)
+        x = torch.from_numpy(synth.net_input(net, 1, 1)).cuda()
+        us_handle = min(handle.layer_times(x, iters=50)[0] for _ in range(3)) * 1e3
+        handle.close()
+        d = B.conv_desc(x.shape, layers[0]["w"].shape, 1, 1)
+        _, ms_api, _ = B.cprune_select_tile(d, x, layers[0]["w"], layers[0]["b"], warmup=3, iters=50)
+        rows.append({"config": "single conv 64->%d @32x32 b1 f32" % keep, "us_in_handle": round(us_handle, 2),
+                     "us_entry_point": round(ms_api * 1e3, 2), "mflop": round(2e-6 * keep * 64 * 9 * 1024, 1)})
+    return rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--quick", action="store_true", help="fewer timed steps, small batches only")
+    args = ap.parse_args()
+    steps = 20 if args.quick else 100
+    props = torch.cuda.get_device_properties(0)
+    print(json.dumps({"device": props.name, "compute_units": props.multi_processor_count,
+                      "clock_mhz": getattr(props, "clock_rate", 0) // 1000,
+                      "hbm_gib": round(props.total_memory / 2 ** 30, 1)}), flush=True)
+    ceil = {"mfma_f32_tflops": round(B.cprune_probe_mfma(B.F32), 1),
+            "mfma_f16_tflops": round(B.cprune_probe_mfma(B.F16), 1),
+            "mfma_bf16_tflops": round(B.cprune_probe_mfma(B.BF16), 1),
+            "copy_gbs": round(B.cprune_probe_copy(1 << 30), 1),
+            "datasheet": {"mfma_f32_tflops": 157.3, "mfma_f16_bf16_tflops": 2500.0, "hbm_gbs": 8000.0}}
+    print(json.dumps({"measured_ceilings": ceil}), flush=True)
+    for row in single_layer_report(steps):
+        print(json.dumps(row), flush=True)
+    cases = [("pruned VGG-16 32x32", synth.vgg16(10, 32), 2, [(1, B.F32), (64, B.F32), (1, B.F16), (64, B.F16)]),
+             ("pruned ResNet-18 224x224", synth.resnet18(1000, 224), 3, [(1, B.F32), (32, B.F32), (1, B.BF16), (32, B.BF16)]),
+             ("pruned MobileNetV2 224x224", synth.mobilenetv2(1000, 224), 4, [(1, B.F32), (64, B.F32)])]
+    for name, net, cid, runs in cases:
+        for batch, dtype in runs:
+            if args.quick and batch > 1 and "VGG" not in name:
+                continue
+            print(json.dumps(net_report(name, net, cid, batch, dtype, steps)), flush=True)
+
+
+if __name__ == "__main__":
+    main()
