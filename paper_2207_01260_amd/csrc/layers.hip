@@ -192,6 +192,46 @@ __device__ __forceinline__ void unpack16(const uint4& q, float (&f)[V]) {
   }
 }
 
+// Channels-last max-pool on 16-byte channel vectors (one output pixel and vector per thread).
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_nhwc_vec_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                               unsigned total, int cp, int h, int wd, int ho,
+                                                               int wo, int k, int stride, int pad) {
+  constexpr int V = VecOf<T>::V;
+  const unsigned idx = blockIdx.x * 256u + threadIdx.x;
+  if (idx >= total) return;
+  const unsigned nvec = (unsigned)cp / V;
+  const int c0 = (int)(idx % nvec) * V;
+  unsigned r = idx / nvec;
+  const int ox = (int)(r % (unsigned)wo); r /= (unsigned)wo;
+  const int oy = (int)(r % (unsigned)ho);
+  const int n = (int)(r / (unsigned)ho);
+  float m[V];
+  bool have = false;
+  for (int u = 0; u < k; ++u) {
+    const int iy = oy * stride - pad + u;
+    if ((unsigned)iy >= (unsigned)h) continue;
+    for (int v = 0; v < k; ++v) {
+      const int ix = ox * stride - pad + v;
+      if ((unsigned)ix >= (unsigned)wd) continue;
+      float in[V];
+      unpack16<T, V>(*reinterpret_cast<const uint4*>(x + ((size_t)(n * h + iy) * wd + ix) * cp + c0), in);
+#pragma unroll
+      for (int e = 0; e < V; ++e) m[e] = have ? fmaxf(m[e], in[e]) : in[e];
+      have = true;
+    }
+  }
+  uint4 q;
+  if constexpr (V == 4) {
+    q.x = __float_as_uint(m[0]); q.y = __float_as_uint(m[1]); q.z = __float_as_uint(m[2]); q.w = __float_as_uint(m[3]);
+  } else {
+    T* hq = reinterpret_cast<T*>(&q);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) hq[e] = (T)m[e];
+  }
+  *reinterpret_cast<uint4*>(y + (size_t)idx * V) = q;
+}
+
 template <typename T, int K, int S, int TX>
 __global__ __launch_bounds__(256) void depthwise_nhwc_vec_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                                  const float* __restrict__ bias,
@@ -422,6 +462,14 @@ int launch_maxpool_nhwc(const void* x, int n, int cp, int h, int w, int k, int s
                         void* y, hipStream_t s) {
   const int ho = conv_out_dim(h, k, stride, pad), wo = conv_out_dim(w, k, stride, pad);
   const long total = (long)n * ho * wo * cp;
+  const int vec = dt == CPRUNE_F32 ? 4 : 8;
+  if (cp % vec == 0 && total / vec < (1L << 32)) {
+    const long tv = total / vec;
+    CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(maxpool_nhwc_vec_kernel<T>, blocks_for(tv), dim3(256), 0, s, (const T*)x,
+                                           (T*)y, (unsigned)tv, cp, h, w, ho, wo, k, stride, pad));
+    CPRUNE_LAUNCH_CHECK();
+    return CPRUNE_OK;
+  }
   CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(maxpool_nhwc_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)x,
                                          (T*)y, total, cp, h, w, ho, wo, k, stride, pad));
   CPRUNE_LAUNCH_CHECK();
