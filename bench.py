@@ -2,13 +2,17 @@
 """Benchmark: images/s of the pruned VGG-16 (32x32 inputs) on one MI355X.
 
 A step is one pass of the inference hot path over one batch of synthetic images:
-13 pruned conv+BN+ReLU layers (MFMA implicit GEMM), 5 max-pools and the FC, through
-cprune_net_forward.  The one-off pruning stage (L1 ranking, kept-list selection, weight
+13 pruned conv+BN+ReLU layers (MFMA kernels; the 2x2 max-pools run in their epilogues) and the
+FC, through cprune_net_forward.  The one-off pruning stage (L1 ranking, kept-list selection, weight
 gather with BN folding) and the per-shape tile selection run before the timed region and
 are reported separately (`prune_ms`, `tune_s`).  Inputs and weights are resident in HBM
 when timing starts.
 
-Prints ONE JSON line; see the design doc for the definition of every field.
+Prints ONE JSON line.  `value`: images/s over the timed steps.  `roofline`: useful FLOP of the
+13 conv layers of a step over the sum of their device times (HIP events around back-to-back
+launches of each layer), against the dense fp32 / fp16 MFMA peak; `traffic`: bytes between L2
+and fabric per conv layer from hardware counters (fixed figure for the default workload).
+`cpu_baseline`: the CPU oracle's forward on a bounded sample of the same images.
 """
 import argparse
 import json
