@@ -240,6 +240,37 @@ int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out)
 int cprune_net_set_layer_variant(cprune_net* net, int layer, int variant);
 int cprune_net_destroy(cprune_net* net);
 
+/* ---- search-side rules (host only, no device work) ----
+ * Section 3.5.  A program splits the iterator over a layer's filters into factors (their
+ * product is the filter count); the filters form a box with these side lengths, and removing
+ * one slice of the box keeps the program's structure.  cprune_lcm_step: l1 / l2 (host arrays,
+ * n1 / n2 >= 1 positive entries) are the splits of the program's two filter iterators (the
+ * reduction loop's and the output stage's); step_out (host) gets the least common multiple of
+ * the two smallest slices, product / largest factor each: the minimum number of filters to
+ * prune.  CPRUNE_ERR_INVALID_ARG for empty lists or factors < 1. */
+int cprune_lcm_step(const int64_t* l1, int n1, const int64_t* l2, int n2, int64_t* step_out);
+/* Filters to prune from c_out so that the count left is the next lower multiple of step (step
+ * itself when c_out is a multiple); 0 when that would leave no filter.  Host out. */
+int cprune_prune_count(int c_out, int64_t step, int* count_out);
+/* The structure of tile variant `variant` on a layer of c_out filters, as that rule needs it:
+ * both filter iterators walk (output tile, 16-filter MFMA row block of the tile), so
+ * main_loop[2] = epilogue[2] = {tiles, blocks per tile} and *unit_out = 16 filters per block
+ * (the rows inside a block are fixed by the instruction and cannot shrink).  Host outs. */
+int cprune_variant_filter_splits(int variant, int c_out, int64_t* main_loop, int64_t* epilogue,
+                                 int* unit_out);
+/* cprune_lcm_step of those splits, in filters (times the unit). */
+int cprune_variant_prune_step(int variant, int c_out, int64_t* step_out);
+/* Section 3.3.  Pruning impact of a task = its execution time x the number of subgraphs
+ * (layers) that map to it; order_out[n_tasks] gets the task indices by descending impact, equal
+ * impacts in index order; impact_out[n_tasks] (or NULL) the impacts.  Host arrays. */
+int cprune_order_tasks(const double* exec_time, const int* n_subgraphs, int n_tasks, int* order_out,
+                       double* impact_out);
+/* Section 3.4.  Groups the handle's dense conv / fully connected layers into tasks: layers
+ * with the same shape, stride, padding, activation, shortcut and layout are one task, numbered
+ * in order of first appearance.  task_of_layer: host [n_layers], -1 for layers that have no
+ * variants (pools, depthwise); n_tasks_out: host. */
+int cprune_net_task_table(const cprune_net* net, int* task_of_layer, int* n_tasks_out);
+
 /* ---- measured ceilings (for reporting kernel throughput against what the device
  * delivers, next to its datasheet peaks; the paper reports end-to-end rates only) ----
  * cprune_probe_mfma: rate of back-to-back dense MFMA instructions of `dtype` on register

@@ -49,6 +49,8 @@ EXPORTS = [
     "cprune_net_copy_activation", "cprune_net_output_shape", "cprune_net_layer_variant",
     "cprune_net_set_layer_variant", "cprune_net_destroy",
     "cprune_probe_scratch_bytes", "cprune_probe_mfma", "cprune_probe_copy",
+    "cprune_lcm_step", "cprune_prune_count", "cprune_variant_filter_splits",
+    "cprune_variant_prune_step", "cprune_order_tasks", "cprune_net_task_table",
 ]
 
 _lib = None
@@ -261,6 +263,47 @@ def cprune_fc(x, w, bias=None, act=ACT_NONE, stream=None):
     return y
 
 
+# ---- search-side rules (host only) ----------------------------------------------
+
+def cprune_lcm_step(l1, l2) -> int:
+    a = (C.c_int64 * len(l1))(*l1)
+    b = (C.c_int64 * len(l2))(*l2)
+    out = C.c_int64(0)
+    _check(lib().cprune_lcm_step(a, C.c_int(len(l1)), b, C.c_int(len(l2)), C.byref(out)), "cprune_lcm_step")
+    return int(out.value)
+
+
+def cprune_prune_count(c_out: int, step: int) -> int:
+    out = C.c_int(0)
+    _check(lib().cprune_prune_count(C.c_int(c_out), C.c_int64(step), C.byref(out)), "cprune_prune_count")
+    return int(out.value)
+
+
+def cprune_variant_filter_splits(variant: int, c_out: int):
+    """-> (main-loop split, epilogue split, filters per unit)."""
+    ml, ep, unit = (C.c_int64 * 2)(), (C.c_int64 * 2)(), C.c_int(0)
+    _check(lib().cprune_variant_filter_splits(C.c_int(variant), C.c_int(c_out), ml, ep, C.byref(unit)),
+           "cprune_variant_filter_splits")
+    return list(ml), list(ep), int(unit.value)
+
+
+def cprune_variant_prune_step(variant: int, c_out: int) -> int:
+    out = C.c_int64(0)
+    _check(lib().cprune_variant_prune_step(C.c_int(variant), C.c_int(c_out), C.byref(out)),
+           "cprune_variant_prune_step")
+    return int(out.value)
+
+
+def cprune_order_tasks(exec_time, n_subgraphs):
+    """-> (task indices by descending pruning impact, impacts)."""
+    n = len(exec_time)
+    t = (C.c_double * n)(*[float(v) for v in exec_time])
+    c = (C.c_int * n)(*[int(v) for v in n_subgraphs])
+    order, impact = (C.c_int * n)(), (C.c_double * n)()
+    _check(lib().cprune_order_tasks(t, c, C.c_int(n), order, impact), "cprune_order_tasks")
+    return list(order), list(impact)
+
+
 # ---- measured ceilings ---------------------------------------------------------
 
 def cprune_probe_mfma(dtype: int = F32, stream=None) -> float:
@@ -331,6 +374,13 @@ class Net:
                                               _stream(stream))
         _check(st, "cprune_net_copy_activation")
         return out
+
+    def task_table(self):
+        """-> (task of each layer or -1, number of tasks)."""
+        tasks = (C.c_int * self.n_layers)()
+        n = C.c_int(0)
+        _check(lib().cprune_net_task_table(self._h, tasks, C.byref(n)), "cprune_net_task_table")
+        return list(tasks), int(n.value)
 
     def set_layer_variant(self, layer: int, variant: int):
         _check(lib().cprune_net_set_layer_variant(self._h, C.c_int(layer), C.c_int(variant)),

@@ -676,6 +676,21 @@ extern "C" int cprune_net_layer_variant(const cprune_net* net, int layer, int* v
   return CPRUNE_OK;
 }
 
+extern "C" int cprune_net_task_table(const cprune_net* net, int* task_of_layer, int* n_tasks_out) {
+  if (!net || !task_of_layer || !n_tasks_out) return CPRUNE_ERR_INVALID_ARG;
+  std::map<DescKey, int> ids;
+  for (size_t i = 0; i < net->layers.size(); ++i) {
+    const NetLayer& L = net->layers[i];
+    if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) { task_of_layer[i] = -1; continue; }
+    const DescKey key = key_of(layer_conv_desc(*net, L, net->max_batch), layer_layout(L));
+    auto it = ids.find(key);
+    if (it == ids.end()) it = ids.emplace(key, (int)ids.size()).first;
+    task_of_layer[i] = it->second;
+  }
+  *n_tasks_out = (int)ids.size();
+  return CPRUNE_OK;
+}
+
 extern "C" int cprune_net_set_layer_variant(cprune_net* net, int layer, int variant) {
   if (!net || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
   NetLayer& L = net->layers[layer];

@@ -1,0 +1,95 @@
+"""Search-side rows on the device: the handle's task table against the oracle's grouping,
+Algorithm 1 driven by measured latencies against the oracle's control flow on the same
+measurements, and the predicted prune step against the measured latency staircase."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import search as osearch
+from paper_2207_01260_amd import binding as B
+from paper_2207_01260_amd import pipeline, synth
+from paper_2207_01260_amd import search as psearch
+
+pytestmark = pytest.mark.gpu
+
+
+def test_task_table_resnet18_unpruned():
+    """Unpruned ResNet-18 has repeated layer shapes; layers with the same shape, stride,
+    padding, activation and shortcut are one task (Section 3.4)."""
+    net = synth.resnet18(100, 64)
+    params = synth.layer_params(net, 3)
+    full = {i: L.c_out for i, L in enumerate(net.layers) if L.prune_out == "own"}
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), B.F32, keep_override=full)
+    handle = pipeline.build_net(net, layers, 2, B.F32, tune=False)
+    task_of, n_tasks = handle.task_table()
+    handle.close()
+    shp = synth.shapes(net, full)
+    keys = []
+    for i, L in enumerate(net.layers):
+        if L.kind == "fc" or (L.kind == "conv" and L.groups == 1):
+            cin, cout, ho, wo = shp[i]
+            hin, win = (net.in_h, net.in_w) if L.input < 0 else shp[L.input][2:4]
+            keys.append((L.kind, cin, cout, hin, win, L.k, L.stride, L.pad, L.act, L.residual is not None))
+        else:
+            keys.append(None)
+    want_of, want_members = osearch.task_table(keys)
+    assert task_of == want_of and n_tasks == len(want_members)
+    assert max(len(m) for m in want_members) >= 2          # the repeated shapes did merge
+    assert n_tasks < sum(k is not None for k in keys)
+
+
+def test_algorithm1_on_measured_latencies_matches_oracle_control_flow():
+    print("algorithm 1, vgg16 b8", flush=True)
+    net = synth.vgg16(10, 32)
+    params = synth.layer_params(net, 2)
+    ds = psearch.DeviceSearch(net, params, 2, batch=8, steps=10)
+    start = ds.initial_model(params)
+    acc = lambda m: 1.0
+    final, log = psearch.algorithm1(start, 0.0, 0.95, 0.999, ds.tune, ds.prune, ds.measure, acc, max_iterations=2)
+    assert log, "no candidate was tried"
+    for task, l_m, l_t, a_s, verdict in log:
+        assert verdict in ("accepted", "slow", "exhausted")
+        if verdict == "accepted":
+            assert l_m < l_t
+        if verdict == "slow":
+            assert l_m >= l_t
+    assert all(final[i] <= start[i] for i in start)
+    n_acc = sum(v == "accepted" for *_, v in log)
+    assert sum(start.values()) - sum(final.values()) > 0 if n_acc else final == start
+    # every accepted cut follows the step rule on the task's own program
+    table, order = ds.tune(start)
+    first = log[0][0]
+    layers_of, program = table[first]
+    assert first == order[0] and program["step"] % 16 == 0
+    # the oracle's loop over the same (cached) measurements takes the same decisions
+    want_final, want_log = osearch.algorithm1(start, 0.0, 0.95, 0.999, ds.tune, ds.prune, ds.measure, acc,
+                                              max_iterations=2)
+    assert want_final == final and want_log == log
+
+
+def test_predicted_step_against_measured_staircase():
+    """Config-5 layer (3x3, 56x56, C_in 128, batch 8): inside one predicted step the latency
+    stays on its plateau; one step down it drops."""
+    net = synth.single_conv(128, 128, 56)
+    params = synth.layer_params(net, 5)
+    dparams = pipeline.upload_params(params)
+    x = torch.from_numpy(synth.net_input(net, 5, 8)).cuda()
+
+    def timed(c_out, variant=None):
+        layers, _ = pipeline.prune_net(net, dparams, B.F32, keep_override={0: c_out})
+        handle = pipeline.build_net(net, layers, 8, B.F32, tune=(variant is None))
+        if variant is not None:
+            handle.set_layer_variant(0, variant)
+        ms = min(handle.layer_times(x, iters=20)[0] for _ in range(3))
+        v = handle.layer_variant(0)
+        handle.close()
+        return ms, v
+
+    t128, v = timed(128)
+    step = B.cprune_variant_prune_step(v, 128)
+    assert step in (16, 32, 64, 128)
+    t_in, _ = timed(128 - step + 1, v)       # same number of 16-row blocks per tile row
+    t_down, _ = timed(128 - step, v)
+    print("variant", B.cprune_tile_variant_info(v), "step", step, t128, t_in, t_down, flush=True)
+    assert t_in > 0.93 * t128
+    assert t_down < 0.97 * t128
