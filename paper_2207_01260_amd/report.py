@@ -1,5 +1,5 @@
 """Per-configuration report: every evaluated workload shape of the paper (Section 4: VGG-16
-on CIFAR-sized inputs, ResNet-18 and MobileNetV2 on ImageNet-sized inputs) as a seeded,
+on CIFAR-sized inputs, ResNet-18, MobileNetV2 and MnasNet1.0 on ImageNet-sized inputs) as a seeded,
 synthetic, channel-pruned network, plus the single pruned layer and the measured ceilings of
 the device.  One JSON object per line.
 
@@ -121,7 +121,8 @@ def main():
         print(json.dumps(row), flush=True)
     cases = [("pruned VGG-16 32x32", synth.vgg16(10, 32), 2, [(1, B.F32), (64, B.F32), (1, B.F16), (64, B.F16)]),
              ("pruned ResNet-18 224x224", synth.resnet18(1000, 224), 3, [(1, B.F32), (32, B.F32), (1, B.BF16), (32, B.BF16)]),
-             ("pruned MobileNetV2 224x224", synth.mobilenetv2(1000, 224), 4, [(1, B.F32), (64, B.F32)])]
+             ("pruned MobileNetV2 224x224", synth.mobilenetv2(1000, 224), 4, [(1, B.F32), (64, B.F32)]),
+             ("pruned MnasNet1.0 224x224", synth.mnasnet(1000, 224), 6, [(1, B.F32), (64, B.F32)])]
     for name, net, cid, runs in cases:
         for batch, dtype in runs:
             if args.quick and batch > 1 and "VGG" not in name:

@@ -159,7 +159,8 @@ class DeviceSearch:
 def run(net_name="vgg16", batch=64, dtype=B.F32, alpha=0.95, beta=0.98, a_goal=0.0, iterations=4,
         accuracy: Optional[Callable] = None):
     net, cid = {"vgg16": (synth.vgg16(10, 32), 2), "resnet18": (synth.resnet18(1000, 224), 3),
-                "mobilenetv2": (synth.mobilenetv2(1000, 224), 4)}[net_name]
+                "mobilenetv2": (synth.mobilenetv2(1000, 224), 4),
+                "mnasnet": (synth.mnasnet(1000, 224), 6)}[net_name]
     params = synth.layer_params(net, cid)
     ds = DeviceSearch(net, params, cid, batch, dtype)
     model = ds.initial_model(params)
@@ -171,7 +172,7 @@ def run(net_name="vgg16", batch=64, dtype=B.F32, alpha=0.95, beta=0.98, a_goal=0
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--net", default="vgg16", choices=["vgg16", "resnet18", "mobilenetv2"])
+    ap.add_argument("--net", default="vgg16", choices=["vgg16", "resnet18", "mobilenetv2", "mnasnet"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--iterations", type=int, default=4)
     ap.add_argument("--beta", type=float, default=0.98)

@@ -218,6 +218,41 @@ def mobilenetv2(num_classes: int = 1000, in_hw: int = 224) -> NetSpec:
     return net
 
 
+def mnasnet(num_classes: int = 1000, in_hw: int = 224) -> NetSpec:
+    """MnasNet 1.0 (the depth-multiplier-1 network without squeeze-excite stages): inverted
+    residual blocks like MobileNetV2's, with 5x5 depthwise convolutions in three of the six
+    stages and plain ReLU.  The expansion channels of every block are pruned; depthwise and
+    projection follow the expansion's list."""
+    net = NetSpec("mnasnet1_0", 3, in_hw, in_hw, keep_lo=0.4, keep_hi=0.9)
+    prev = net.add(Layer("conv", -1, 3, 32, k=3, stride=2, pad=1, act=ACT_RELU, bn=True, name="stem"))
+    prev = net.add(Layer("conv", prev, 32, 32, k=3, stride=1, pad=1, groups=32, act=ACT_RELU, bn=True,
+                         name="stem.dw"))
+    prev = net.add(Layer("conv", prev, 32, 16, k=1, act=ACT_NONE, bn=True, name="stem.project"))
+    c = 16
+    # (expansion, output channels, blocks, stride of the first block, depthwise kernel)
+    table = [(3, 24, 3, 2, 3), (3, 40, 3, 2, 5), (6, 80, 3, 2, 5),
+             (6, 96, 2, 1, 3), (6, 192, 4, 2, 5), (6, 320, 1, 1, 3)]
+    bidx = 0
+    for t, cout, n, s, k in table:
+        for i in range(n):
+            stride = s if i == 0 else 1
+            block_in = prev
+            hidden = c * t
+            exp = net.add(Layer("conv", prev, c, hidden, k=1, act=ACT_RELU, bn=True, prune_out="own",
+                                name=f"b{bidx}.expand"))
+            prev = net.add(Layer("conv", exp, hidden, hidden, k=k, stride=stride, pad=k // 2, groups=hidden,
+                                 act=ACT_RELU, bn=True, prune_out=exp, name=f"b{bidx}.dw"))
+            res = block_in if (stride == 1 and c == cout) else None
+            prev = net.add(Layer("conv", prev, hidden, cout, k=1, act=ACT_NONE, bn=True, residual=res,
+                                 prune_in=exp, name=f"b{bidx}.project"))
+            c = cout
+            bidx += 1
+    prev = net.add(Layer("conv", prev, c, 1280, k=1, act=ACT_RELU, bn=True, name="last"))
+    prev = net.add(Layer("gavgpool", prev, 1280, 1280, name="gap"))
+    net.add(Layer("fc", prev, 1280, num_classes, bias=True, name="fc"))
+    return net
+
+
 def single_conv(c_in: int, c_out: int, hw: int, k: int = 3, stride: int = 1,
                 pad: int = 1) -> NetSpec:
     """One conv+BN+ReLU layer whose filters are pruned (the single-layer workloads)."""

@@ -159,6 +159,19 @@ def test_mobilenetv2_reduced_input(orc):
     handle.close()
 
 
+def test_mnasnet_reduced_input(orc):
+    """5x5 depthwise stages, plain ReLU; every layer's activation checked."""
+    print("mnasnet 64x64", flush=True)
+    handle, *_ = _run(orc, synth.mnasnet(100, 64), 6, 2, B.F32, tune=False)
+    handle.close()
+
+
+def test_mnasnet_bf16_full_size_batch1(orc):
+    print("mnasnet 224 b1 bf16", flush=True)
+    handle, *_ = _run(orc, synth.mnasnet(1000, 224), 6, 1, B.BF16, tune=False, check_layers=False)
+    handle.close()
+
+
 def test_resnet18_full_size_batch1(orc):
     print("resnet18 224 b1", flush=True)
     handle, *_ = _run(orc, synth.resnet18(1000, 224), 3, 1, B.F32, tune=False, check_layers=False)

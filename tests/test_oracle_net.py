@@ -24,6 +24,7 @@ BUILDERS = {
     "resnet18": lambda: synth.resnet18(1000, 224),
     "mobilenetv2": lambda: synth.mobilenetv2(1000, 224),
     "resnet18_cifar": lambda: synth.resnet18(10, 32, cifar_stem=True),
+    "mnasnet1_0": lambda: synth.mnasnet(1000, 224),
 }
 
 
@@ -41,6 +42,7 @@ def test_exact_counts():
     assert synth.count_macs_params(synth.mobilenetv2()) == (300774272, 3470760)
     assert synth.count_macs_params(synth.resnet18(10, 32, True)) == (555422720, 11164362)
     assert synth.count_macs_params(synth.vgg16()) == (313201664, 14715594)
+    assert synth.count_macs_params(synth.mnasnet()) == (314415872, 4345392)
 
 
 def test_keep_count_rule():
@@ -62,7 +64,7 @@ def test_generator_is_reproducible_and_sane():
 
 def _small_nets():
     return [("vgg16", synth.vgg16(10, 32), 2), ("resnet18", synth.resnet18(20, 64), 3),
-            ("mobilenetv2", synth.mobilenetv2(20, 64), 4)]
+            ("mobilenetv2", synth.mobilenetv2(20, 64), 4), ("mnasnet", synth.mnasnet(20, 64), 6)]
 
 
 @pytest.mark.parametrize("name,net,cid", _small_nets())
