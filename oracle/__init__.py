@@ -78,6 +78,17 @@ def rank_filters(w: np.ndarray, keep: int):
     return s, order, kept
 
 
+def group_scores(ws) -> np.ndarray:
+    """Per-channel score of a group of layers with the same number of filters: the sum over
+    the layers, in the order given, of each layer's filter L1 norm."""
+    total = l1_scores(ws[0])
+    for w in ws[1:]:
+        if w.shape[0] != ws[0].shape[0]:
+            raise ValueError("all layers of a group need the same number of filters")
+        total = total + l1_scores(w)
+    return total
+
+
 # ---- gather / fold -------------------------------------------------------
 
 def gather_weights(w: np.ndarray, keep_out=None, keep_in=None) -> np.ndarray:
@@ -247,7 +258,14 @@ def prune_net(net, params: List[dict], keep_override: Optional[Dict[int, int]] =
     for i, (L, p) in enumerate(zip(net.layers, params)):
         if L.prune_out == "own":
             k = (keep_override or {}).get(i, p["keep"])
-            _, _, kept[i] = rank_filters(p["w"], k)
+            if getattr(L, "score_with", None):
+                # layers whose outputs a shortcut adds lose the same channels (Section 3.5, last
+                # paragraph).  Reading: a channel's score is the sum of its filter norms over
+                # those layers, added in layer order; the paper only names the mode of the
+                # pruning toolkit it uses.
+                _, kept[i] = rank(group_scores([p["w"]] + [params[j]["w"] for j in L.score_with]), k)
+            else:
+                _, _, kept[i] = rank_filters(p["w"], k)
     out = []
     for i, (L, p) in enumerate(zip(net.layers, params)):
         q: dict = {}

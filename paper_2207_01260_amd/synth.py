@@ -100,6 +100,10 @@ class Layer:
               own L1 norm; int i: output channels follow layer i's kept list
               (depthwise conv behind a pruned expansion)
     prune_in  int i: input channels gathered by layer i's kept list; else None
+    score_with  for an 'own'-pruned layer: indices of other layers (same c_out) whose filter
+              norms are added to its own before ranking; those layers set prune_out to this
+              layer's index, so that all of them lose the same channels (layers whose outputs
+              a shortcut adds)
     """
     kind: str
     input: int
@@ -113,6 +117,7 @@ class Layer:
     bn: bool = False
     bias: bool = False
     residual: Optional[int] = None
+    score_with: Optional[List[int]] = None
     prune_out: object = None
     prune_in: Optional[int] = None
     name: str = ""
@@ -152,36 +157,57 @@ def vgg16(num_classes: int = 10, in_hw: int = 32) -> NetSpec:
     return net
 
 
-def resnet18(num_classes: int = 1000, in_hw: int = 224, cifar_stem: bool = False) -> NetSpec:
-    """Basic-block ResNet-18; the first conv of each block is the pruned one."""
+def resnet18(num_classes: int = 1000, in_hw: int = 224, cifar_stem: bool = False,
+             prune_shortcuts: bool = False) -> NetSpec:
+    """Basic-block ResNet-18; the first conv of each block is the pruned one.
+
+    prune_shortcuts: also prune the channels that run along the shortcuts.  Every layer that
+    writes into one stage's shortcut sum (the stem or the stage's 1x1 downsample conv, and
+    the second conv of both blocks) must lose the same channels: the first of them in layer
+    order ranks the sum of all their filter norms, the others follow its list, and every
+    reader of the sum (the next convs, the next downsample, the FC) drops the matching inputs."""
     net = NetSpec("resnet18_cifar" if cifar_stem else "resnet18", 3, in_hw, in_hw,
                   keep_lo=0.3, keep_hi=0.9)
+    lead = None           # layer whose kept list governs the current shortcut stream
     if cifar_stem:
         prev = net.add(Layer("conv", -1, 3, 64, k=3, stride=1, pad=1, act=ACT_RELU, bn=True,
                              name="stem"))
+        stem = prev
     else:
         prev = net.add(Layer("conv", -1, 3, 64, k=7, stride=2, pad=3, act=ACT_RELU, bn=True,
                              name="stem"))
+        stem = prev
         prev = net.add(Layer("maxpool", prev, 64, 64, k=3, stride=2, pad=1, name="pool"))
+    if prune_shortcuts:
+        lead = stem
+        net.layers[stem].prune_out = "own"
+        net.layers[stem].score_with = []
     c = 64
     for si, width in enumerate([64, 128, 256, 512]):
         for bi in range(2):
             stride = 2 if (si > 0 and bi == 0) else 1
             block_in = prev
+            stream_in = lead
             if stride != 1 or c != width:
                 short = net.add(Layer("conv", block_in, c, width, k=1, stride=stride, pad=0,
-                                      act=ACT_NONE, bn=True, name=f"s{si}b{bi}.down"))
+                                      act=ACT_NONE, bn=True, prune_in=stream_in, name=f"s{si}b{bi}.down"))
+                if prune_shortcuts:
+                    lead = short
+                    net.layers[short].prune_out = "own"
+                    net.layers[short].score_with = []
             else:
                 short = block_in
             c1 = net.add(Layer("conv", block_in, c, width, k=3, stride=stride, pad=1,
-                               act=ACT_RELU, bn=True, prune_out="own",
+                               act=ACT_RELU, bn=True, prune_out="own", prune_in=stream_in,
                                name=f"s{si}b{bi}.conv1"))
             prev = net.add(Layer("conv", c1, width, width, k=3, stride=1, pad=1, act=ACT_RELU,
-                                 bn=True, residual=short, prune_in=c1,
+                                 bn=True, residual=short, prune_in=c1, prune_out=lead,
                                  name=f"s{si}b{bi}.conv2"))
+            if prune_shortcuts:
+                net.layers[lead].score_with.append(prev)
             c = width
     prev = net.add(Layer("gavgpool", prev, c, c, name="gap"))
-    net.add(Layer("fc", prev, c, num_classes, bias=True, name="fc"))
+    net.add(Layer("fc", prev, c, num_classes, bias=True, prune_in=lead, name="fc"))
     return net
 
 

@@ -64,7 +64,8 @@ def test_generator_is_reproducible_and_sane():
 
 def _small_nets():
     return [("vgg16", synth.vgg16(10, 32), 2), ("resnet18", synth.resnet18(20, 64), 3),
-            ("mobilenetv2", synth.mobilenetv2(20, 64), 4), ("mnasnet", synth.mnasnet(20, 64), 6)]
+            ("mobilenetv2", synth.mobilenetv2(20, 64), 4), ("mnasnet", synth.mnasnet(20, 64), 6),
+            ("resnet18_shortcuts", synth.resnet18(20, 64, prune_shortcuts=True), 7)]
 
 
 @pytest.mark.parametrize("name,net,cid", _small_nets())
@@ -122,6 +123,32 @@ def test_pruned_net_equals_masked_full_net(orc, name, net, cid):
     macs_full, _ = synth.count_macs_params(net)
     macs_pruned, _ = synth.count_macs_params(net, {i: k.size for i, k in kept.items()})
     assert macs_pruned < 0.9 * macs_full
+
+
+def test_shortcut_groups_share_one_kept_list(orc):
+    """Layers that write into the same shortcut sum follow one kept list, ranked on the sum
+    of their filter norms; every reader of the sum drops the matching input channels."""
+    net = synth.resnet18(20, 64, prune_shortcuts=True)
+    params = synth.layer_params(net, 7)
+    layers, kept = orc.prune_net(net, params)
+    leads = [i for i, L in enumerate(net.layers) if L.score_with]
+    assert len(leads) == 4                      # the stem and three downsample convs
+    for lead in leads:
+        L = net.layers[lead]
+        members = [lead] + L.score_with
+        total = sum(np.abs(params[j]["w"].astype(np.float64)).reshape(L.c_out, -1).sum(axis=1) for j in members)
+        k = kept[lead].size
+        order = sorted(range(L.c_out), key=lambda j: (-total[j], j))
+        assert kept[lead].tolist() == sorted(order[:k])
+        assert synth.min_relative_gap(total) > 1e-9
+        for j in members:
+            assert layers[j]["w"].shape[0] == k
+            assert net.layers[j].prune_out == (lead if j != lead else "own")
+        readers = [i for i, R in enumerate(net.layers) if R.prune_in == lead]
+        assert readers
+        for r in readers:
+            assert layers[r]["w"].shape[1] == k
+    assert layers[-1]["w"].shape == (20, kept[leads[-1]].size)
 
 
 def test_folded_net_close_to_unfolded(orc):

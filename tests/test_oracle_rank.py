@@ -142,3 +142,21 @@ def test_drop_filter_two_layers_bit_exact(orc):
                                   synth.ACT_RELU)
         pruned = orc.conv2d_f64(a1p, orc.gather_weights(w2, None, keep), 1, 1)
         assert np.array_equal(full, pruned)
+
+
+def test_group_scores_are_sums_of_member_norms(orc):
+    """A group's channel score is the sum of the members' filter norms; one member alone is the
+    plain score; the group ranking can differ from every member's own."""
+    a = np.zeros((3, 2, 1, 1), np.float32)
+    b = np.zeros((3, 1, 3, 3), np.float32)
+    a[0] = 1.0; a[1] = 0.5; a[2] = 0.25          # norms 2, 1, 0.5
+    b[0] = 0.0; b[1] = 0.125; b[2] = 1.0         # norms 0, 1.125, 9
+    s = orc.group_scores([a, b])
+    assert s.tolist() == [2.0, 2.125, 9.5]
+    assert np.array_equal(orc.group_scores([a]), orc.l1_scores(a))
+    _, kept = orc.rank(s, 2)
+    assert kept.tolist() == [1, 2]               # member a alone would keep {0, 1}
+    _, _, kept_a = orc.rank_filters(a, 2)
+    assert kept_a.tolist() == [0, 1]
+    with pytest.raises(ValueError):
+        orc.group_scores([a, np.zeros((4, 1, 1, 1), np.float32)])
