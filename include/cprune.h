@@ -65,6 +65,16 @@ int cprune_rank_filters(const float* w, int c_out, int c_in_per_group, int kh, i
                         double* scores_out, int32_t* order_out, int32_t* kept_out,
                         void* ws, size_t ws_bytes, void* stream);
 
+/* Ranking of a group of layers that must lose the same channels (Section 3.5, last
+ * paragraph: the layers whose outputs a shortcut adds are pruned at the same output
+ * channels).  A channel's score is the sum, in member order, of its filter's L1 sum in every
+ * member.  w: HOST array of n_members device pointers, member m being
+ * [c_out][per_filter[m]] fp32; per_filter: HOST array of filter lengths
+ * (c_in_per_group * kh * kw).  Everything else as cprune_rank_filters. */
+int cprune_rank_filter_group(const float* const* w, const int64_t* per_filter, int n_members,
+                             int c_out, int keep, double* scores_out, int32_t* order_out,
+                             int32_t* kept_out, void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------------
  * Weight gather with batch-norm folding (paper Section 2.1 / Fig. 2: removing a
  * filter removes an output channel, removing an input channel shrinks every

@@ -39,7 +39,7 @@ class LayerDesc(C.Structure):
 
 EXPORTS = [
     "cprune_status_string", "cprune_last_hip_error",
-    "cprune_rank_filters_workspace_bytes", "cprune_rank_filters",
+    "cprune_rank_filters_workspace_bytes", "cprune_rank_filters", "cprune_rank_filter_group",
     "cprune_gather_pruned_weights", "cprune_gather_channels",
     "cprune_num_tile_variants", "cprune_tile_variant_info", "cprune_conv_workspace_bytes",
     "cprune_conv2d_bn_relu", "cprune_select_tile", "cprune_clear_tile_cache",
@@ -121,6 +121,29 @@ def cprune_rank_filters(w: torch.Tensor, keep: int, want_scores=True, want_order
                                    C.c_int(keep), _ptr(scores), _ptr(order), _ptr(kept), _ptr(ws),
                                    C.c_size_t(ws.numel()), _stream(stream))
     _check(st, "cprune_rank_filters")
+    return scores, order, kept
+
+
+def cprune_rank_filter_group(ws_list, keep: int, want_scores=True, want_order=True, stream=None):
+    """Layers that must lose the same channels, ranked on the sum of their filter norms.
+    ws_list: fp32 device weight tensors with the same number of filters.
+    -> (scores fp64 or None, order int32 or None, kept int32 ascending)."""
+    c_out = ws_list[0].shape[0]
+    assert all(w.dtype == torch.float32 and w.shape[0] == c_out for w in ws_list)
+    dev = ws_list[0].device
+    n = len(ws_list)
+    ptrs = (C.c_void_p * n)(*[w.data_ptr() for w in ws_list])
+    lens = (C.c_int64 * n)(*[w.numel() // c_out for w in ws_list])
+    for w in ws_list:
+        assert w.is_cuda and w.is_contiguous()
+    scores = torch.empty(c_out, dtype=torch.float64, device=dev) if want_scores else None
+    order = torch.empty(c_out, dtype=torch.int32, device=dev) if want_order else None
+    kept = torch.empty(max(keep, 1), dtype=torch.int32, device=dev)
+    ws = _ws(lib().cprune_rank_filters_workspace_bytes(C.c_int(c_out)), dev)
+    st = lib().cprune_rank_filter_group(ptrs, lens, C.c_int(n), C.c_int(c_out), C.c_int(keep), _ptr(scores),
+                                        _ptr(order), _ptr(kept), _ptr(ws), C.c_size_t(ws.numel()),
+                                        _stream(stream))
+    _check(st, "cprune_rank_filter_group")
     return scores, order, kept
 
 

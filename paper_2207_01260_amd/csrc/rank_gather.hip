@@ -14,8 +14,9 @@ constexpr int kMaxRankFilters = 4096;
 // double, then a fixed-shape tree (wavefront shuffles, then 4 partials in LDS)
 // combines them: the order of additions depends only on the filter length, so
 // the score is reproducible bit for bit.
+// accumulate != 0: the sum is added to the score already there (groups of layers).
 __global__ __launch_bounds__(256) void l1_score_kernel(const float* __restrict__ w, long per_filter,
-                                                       double* __restrict__ scores) {
+                                                       double* __restrict__ scores, int accumulate) {
   const float* f = w + (long)blockIdx.x * per_filter;
   double s = 0.0;
   for (long i = threadIdx.x; i < per_filter; i += 256) s += (double)fabsf(f[i]);
@@ -24,7 +25,10 @@ __global__ __launch_bounds__(256) void l1_score_kernel(const float* __restrict__
   __shared__ double part[4];
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
   __syncthreads();
-  if (threadIdx.x == 0) scores[blockIdx.x] = (part[0] + part[1]) + (part[2] + part[3]);
+  if (threadIdx.x == 0) {
+    const double sum = (part[0] + part[1]) + (part[2] + part[3]);
+    scores[blockIdx.x] = accumulate ? scores[blockIdx.x] + sum : sum;
+  }
 }
 
 // Enumeration sort in one work-group: rank(i) = #{ j : s_j > s_i or (s_j == s_i and j < i) }.
@@ -143,10 +147,34 @@ extern "C" int cprune_rank_filters(const float* w, int c_out, int c_in_per_group
   }
   hipStream_t s = (hipStream_t)stream;
   long per_filter = (long)c_in_per_group * kh * kw;
-  hipLaunchKernelGGL(l1_score_kernel, dim3(c_out), dim3(256), 0, s, w, per_filter, scores);
+  hipLaunchKernelGGL(l1_score_kernel, dim3(c_out), dim3(256), 0, s, w, per_filter, scores, 0);
   CPRUNE_LAUNCH_CHECK();
   hipLaunchKernelGGL(rank_select_kernel, dim3(1), dim3(1024), 0, s, scores, c_out, keep, order_out,
                      kept_out);
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_rank_filter_group(const float* const* w, const int64_t* per_filter, int n_members,
+                                        int c_out, int keep, double* scores_out, int32_t* order_out,
+                                        int32_t* kept_out, void* ws, size_t ws_bytes, void* stream) {
+  if (!w || !per_filter || n_members < 1 || !kept_out || c_out < 1) return CPRUNE_ERR_INVALID_ARG;
+  for (int m = 0; m < n_members; ++m)
+    if (!w[m] || per_filter[m] < 1) return CPRUNE_ERR_INVALID_ARG;
+  if (keep < 1 || keep > c_out) return CPRUNE_ERR_INVALID_ARG;
+  if (c_out > kMaxRankFilters) return CPRUNE_ERR_UNSUPPORTED;
+  double* scores = scores_out;
+  if (!scores) {
+    if (!ws) return CPRUNE_ERR_INVALID_ARG;
+    if (ws_bytes < cprune_rank_filters_workspace_bytes(c_out)) return CPRUNE_ERR_WORKSPACE;
+    scores = (double*)ws;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  for (int m = 0; m < n_members; ++m) {   // same stream: member m + 1 adds to what member m left
+    hipLaunchKernelGGL(l1_score_kernel, dim3(c_out), dim3(256), 0, s, w[m], (long)per_filter[m], scores, m > 0 ? 1 : 0);
+    CPRUNE_LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(rank_select_kernel, dim3(1), dim3(1024), 0, s, scores, c_out, keep, order_out, kept_out);
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }

@@ -38,8 +38,13 @@ def prune_net(net: synth.NetSpec, dev_params: List[dict], dtype: int = B.F32,
     for i, (L, p) in enumerate(zip(net.layers, dev_params)):
         if L.prune_out == "own":
             k = (keep_override or {}).get(i, p["keep"])
-            _, _, kept[i] = B.cprune_rank_filters(p["w"], k, want_scores=False, want_order=False,
-                                                  stream=stream)
+            if L.score_with:     # layers that feed the same shortcut sum lose the same channels
+                group = [p["w"]] + [dev_params[j]["w"] for j in L.score_with]
+                _, _, kept[i] = B.cprune_rank_filter_group(group, k, want_scores=False, want_order=False,
+                                                           stream=stream)
+            else:
+                _, _, kept[i] = B.cprune_rank_filters(p["w"], k, want_scores=False, want_order=False,
+                                                      stream=stream)
     layers = []
     for i, (L, p) in enumerate(zip(net.layers, dev_params)):
         q: dict = {}

@@ -148,6 +148,20 @@ def test_resnet18_reduced_input(orc):
     handle.close()
 
 
+def test_resnet18_shortcut_channels_pruned(orc):
+    """Dependency-aware pruning: every layer on a stage's shortcut stream follows one kept
+    list ranked on the summed filter norms; kept lists bit-exact, activations at the bar."""
+    print("resnet18 shortcuts 64x64", flush=True)
+    handle, *_ = _run(orc, synth.resnet18(100, 64, prune_shortcuts=True), 7, 2, B.F32, tune=False)
+    handle.close()
+
+
+def test_resnet18_shortcuts_full_size_fp16(orc):
+    handle, *_ = _run(orc, synth.resnet18(1000, 224, prune_shortcuts=True), 7, 1, B.F16, tune=False,
+                      check_layers=False)
+    handle.close()
+
+
 def test_resnet18_bf16(orc):
     handle, *_ = _run(orc, synth.resnet18(100, 64), 3, 2, B.BF16, tune=False, check_layers=False)
     handle.close()

@@ -284,3 +284,23 @@ def test_maxpool_gavgpool_fc(orc):
         bf = synth.tensor_normal((c,), 144, std=0.1)
         y = B.cprune_fc(dev(xf), dev(wf), dev(bf)).cpu().numpy()
         assert nmax(y, orc.fc(xf, wf, bf)) < 1e-4
+
+
+def test_rank_filter_group(orc):
+    """Group ranking: scores are the sum of the members' L1 sums in member order; order and
+    kept list bit-exact with the oracle; a single member equals the plain ranking."""
+    a = synth.tensor_normal((96, 40, 3, 3), 71, 1)
+    b = synth.tensor_normal((96, 24, 1, 1), 71, 2)
+    c = synth.tensor_normal((96, 96, 3, 3), 71, 3, std=0.05)
+    ref = orc.group_scores([a, b, c])
+    assert synth.min_relative_gap(ref) > 1e-9
+    ref_order, ref_kept = orc.rank(ref, 57)
+    da, db, dc = (torch.from_numpy(t).cuda() for t in (a, b, c))
+    s, order, kept = B.cprune_rank_filter_group([da, db, dc], 57)
+    assert np.allclose(s.cpu().numpy(), ref, rtol=1e-12, atol=0)
+    assert np.array_equal(order.cpu().numpy(), ref_order) and np.array_equal(kept.cpu().numpy(), ref_kept)
+    s1, o1, k1 = B.cprune_rank_filter_group([da], 10)
+    s2, o2, k2 = B.cprune_rank_filters(da, 10)
+    assert torch.equal(s1, s2) and torch.equal(o1, o2) and torch.equal(k1, k2)
+    with pytest.raises(B.CPruneError):
+        B.cprune_rank_filter_group([da, db], 97)
