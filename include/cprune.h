@@ -263,9 +263,10 @@ int cprune_lcm_step(const int64_t* l1, int n1, const int64_t* l2, int n2, int64_
  * itself when c_out is a multiple); 0 when that would leave no filter.  Host out. */
 int cprune_prune_count(int c_out, int64_t step, int* count_out);
 /* The structure of tile variant `variant` on a layer of c_out filters, as that rule needs it:
- * both filter iterators walk (output tile, 16-filter MFMA row block of the tile), so
- * main_loop[2] = epilogue[2] = {tiles, blocks per tile} and *unit_out = 16 filters per block
- * (the rows inside a block are fixed by the instruction and cannot shrink).  Host outs. */
+ * both filter iterators walk (output tile, MFMA row block of the tile), so
+ * main_loop[2] = epilogue[2] = {tiles, blocks per tile} and *unit_out = the filters per block
+ * (16, or 32 for the variants built on 32x32 blocks; the rows inside a block are fixed by the
+ * instruction and cannot shrink).  Host outs. */
 int cprune_variant_filter_splits(int variant, int c_out, int64_t* main_loop, int64_t* epilogue,
                                  int* unit_out);
 /* cprune_lcm_step of those splits, in filters (times the unit). */

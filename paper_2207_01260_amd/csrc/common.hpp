@@ -38,6 +38,7 @@ struct TileVariant {
   int sched;    // scheduling mode: 0 = one tile per work-group, n = runs for n * 256 groups,
                 // -1 = 3x3 spatial-patch kernel (one th x tw pixel block per work-group)
   int th = 0, tw = 0, ni = 1, patch_id = -1;
+  int blk32 = 0;  // patch kernels: 1 = 32x32 MFMA blocks (patch_id then indexes that kernel's list)
   int tile_m() const { return wm * mb * 16; }
   int tile_p() const { return wn * nb * 16; }
 };

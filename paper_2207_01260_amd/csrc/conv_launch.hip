@@ -1,6 +1,6 @@
 // Host side of the dense convolution: the variant table (tile x scheduling
 // mode), what each variant supports and needs, and the launch.
-#include "conv_patch_kernel.hpp"
+#include "conv_patch32_kernel.hpp"
 
 namespace cprune {
 namespace {
@@ -58,10 +58,10 @@ Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv, const ConvLayou
 
 }  // namespace
 
-int num_variants() { return kNumTiles * kNumScheds + kNumPatch; }
+int num_variants() { return kNumTiles * kNumScheds + kNumPatch + kNumPatch32; }
 
 const TileVariant& variant(int id) {
-  static TileVariant table[kNumTiles * kNumScheds + kNumPatch];
+  static TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32];
   static bool init = false;
   if (!init) {
 #define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_, KQ_, KS_)                                 \
@@ -72,6 +72,14 @@ const TileVariant& variant(int id) {
     }
     CPRUNE_PATCH_LIST(CPRUNE_PATCH_ROW)
 #undef CPRUNE_PATCH_ROW
+#define CPRUNE_PATCH32_ROW(ID, MB2_, NB2_, WPX_, TH_, TW_, NI_, KQ_)                       \
+    {                                                                                      \
+      TileVariant& pv = table[kNumTiles * kNumScheds + kNumPatch + ID];                    \
+      pv.wm = 1; pv.wn = WPX_; pv.mb = 2 * MB2_; pv.nb = 2 * NB2_; pv.kq = KQ_; pv.ni = NI_; \
+      pv.sched = -1; pv.th = TH_; pv.tw = TW_; pv.patch_id = ID; pv.blk32 = 1;             \
+    }
+    CPRUNE_PATCH32_LIST(CPRUNE_PATCH32_ROW)
+#undef CPRUNE_PATCH32_ROW
     for (int t = 0; t < kNumTiles; ++t)
       for (int s = 0; s < kNumScheds; ++s) {
         table[t * kNumScheds + s] = kTiles[t];
@@ -140,7 +148,11 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     pa.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
     pa.m_major = pa.w_bytes > pa.x_bytes ? 1 : 0;
     dim3 pgrid((unsigned)(pa.tiles_n * pa.tiles_y * pa.tiles_x * pa.tiles_m));
-    if (d.dtype == CPRUNE_F32) launch_conv_patch_f32(tv.patch_id, pgrid, s, pa);
+    if (tv.blk32) {
+      if (d.dtype == CPRUNE_F32) launch_conv_patch32_f32(tv.patch_id, pgrid, s, pa);
+      else if (d.dtype == CPRUNE_F16) launch_conv_patch32_f16(tv.patch_id, pgrid, s, pa);
+      else launch_conv_patch32_bf16(tv.patch_id, pgrid, s, pa);
+    } else if (d.dtype == CPRUNE_F32) launch_conv_patch_f32(tv.patch_id, pgrid, s, pa);
     else if (d.dtype == CPRUNE_F16) launch_conv_patch_f16(tv.patch_id, pgrid, s, pa);
     else launch_conv_patch_bf16(tv.patch_id, pgrid, s, pa);
     CPRUNE_LAUNCH_CHECK();

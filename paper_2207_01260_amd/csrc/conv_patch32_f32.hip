@@ -1,0 +1,10 @@
+// Instantiations of the 32x32-block spatial-patch convolution kernel for float data.
+#include "conv_patch32_kernel.hpp"
+
+namespace cprune {
+
+void launch_conv_patch32_f32(int id, dim3 grid, hipStream_t s, const PatchArgs& a) {
+  launch_patch32<float>(id, grid, s, a);
+}
+
+}  // namespace cprune

@@ -214,7 +214,9 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
       constexpr int NR = 9 * KQ;
       auto rounds = [&](auto lo_tag, auto hi_tag) {
         constexpr int LO = decltype(lo_tag)::value, HI = decltype(hi_tag)::value;
-        uint4 af[2][MB], bf[2][NB];
+        // fragments are fetched PF rounds ahead of their use (PF + 1 register sets)
+        constexpr int PF = 1;
+        uint4 af[PF + 1][MB], bf[PF + 1][NB];
         auto fetch = [&](int rnd, uint4 (&fa)[MB], uint4 (&fb)[NB]) {
           const int tap = rnd / KQ, q4 = rnd % KQ;
           const int boff = ((tap / 3) * PW + (tap % 3)) * BROW + q4 * 64;
@@ -223,11 +225,19 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
 #pragma unroll
           for (int i = 0; i < MBC; ++i) fa[i] = *(const uint4*)&sA[a_frag + i * 16 * AROW + tap * (64 * KQ) + q4 * 64];
         };
-        fetch(LO, af[0], bf[0]);
+#pragma unroll
+        for (int p = 0; p < PF; ++p)
+          if (LO + p < HI) fetch(LO + p, af[p], bf[p]);
 #pragma unroll
         for (int rnd = LO; rnd < HI; ++rnd) {
-          if (rnd + 1 < HI) fetch(rnd + 1, af[(rnd + 1 - LO) & 1], bf[(rnd + 1 - LO) & 1]);
-          mma_round<T, MBC, NB, MB, NS>(af[(rnd - LO) & 1], bf[(rnd - LO) & 1], accs, rnd);
+          if (rnd + PF < HI) fetch(rnd + PF, af[(rnd + PF - LO) % (PF + 1)], bf[(rnd + PF - LO) % (PF + 1)]);
+          // Multi-image tiles serve small maps, whose grids leave one wavefront per SIMD: there
+          // the fetch is pinned ahead of the multiplies (left alone, the scheduler sinks every LDS
+          // read to just before its first use and the four wavefronts take turns on the LDS and
+          // the matrix pipes).  With many resident wavefronts the scheduler's own order is faster.
+          if constexpr (NI > 1) __builtin_amdgcn_sched_barrier(0);
+          mma_round<T, MBC, NB, MB, NS>(af[(rnd - LO) % (PF + 1)], bf[(rnd - LO) % (PF + 1)], accs, rnd);
+          if constexpr (NI > 1) __builtin_amdgcn_sched_barrier(0);
         }
       };
       if constexpr (KS == 1) {

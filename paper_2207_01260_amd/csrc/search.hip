@@ -51,13 +51,14 @@ extern "C" int cprune_variant_filter_splits(int v, int c_out, int64_t* main_loop
   if (v < 0 || v >= num_variants() || c_out < 1 || !main_loop || !epilogue || !unit_out) return CPRUNE_ERR_INVALID_ARG;
   const TileVariant& tv = variant(v);
   const int tile_m = tv.tile_m();
+  const int unit = tv.blk32 ? 32 : 16;   // rows of the MFMA block the variant is built on
   const int64_t tiles = (c_out + tile_m - 1) / tile_m;
-  const int64_t blocks = std::min<int64_t>(tile_m / 16, (c_out + 15) / 16);
-  // the reduction loop walks (tile, 16-row block of the tile); the store loop walks the same
-  // blocks (inside a block the 4 lane groups x 4 rows are the MFMA result layout, not a loop)
+  const int64_t blocks = std::min<int64_t>(tile_m / unit, (c_out + unit - 1) / unit);
+  // the reduction loop walks (tile, MFMA row block of the tile); the store loop walks the same
+  // blocks (inside a block the rows are the MFMA result layout, not a loop)
   main_loop[0] = tiles; main_loop[1] = blocks;
   epilogue[0] = tiles; epilogue[1] = blocks;
-  *unit_out = 16;
+  *unit_out = unit;
   return CPRUNE_OK;
 }
 

@@ -71,12 +71,12 @@ def test_variant_structure_and_step():
         tile_m, _, _ = B.cprune_tile_variant_info(v)
         for c_out in (1, 16, 45, 64, 128, 247, 512):
             ml, ep, unit = B.cprune_variant_filter_splits(v, c_out)
-            assert unit == 16 and ml == ep
+            assert unit in (16, 32) and ml == ep and tile_m % unit == 0
             tiles, blocks = ml
-            assert tiles == -(-c_out // tile_m) and blocks == min(tile_m // 16, -(-c_out // 16))
-            assert tiles * blocks * 16 >= c_out
+            assert tiles == -(-c_out // tile_m) and blocks == min(tile_m // unit, -(-c_out // unit))
+            assert tiles * blocks * unit >= c_out
             step = B.cprune_variant_prune_step(v, c_out)
-            assert step == 16 * search.lcm_step(ml, ep)
+            assert step == unit * search.lcm_step(ml, ep)
             assert step % 16 == 0
     # a 16-row tile steps by one MFMA block whatever the filter count
     v16 = next(v for v in range(nv) if B.cprune_tile_variant_info(v)[0] == 16)
