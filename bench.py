@@ -137,6 +137,8 @@ def main():
         fl = 2.0 * args.batch * cout * cin * 9 * ho * wo
         tm, tp, sk = B.cprune_tile_variant_info(handle.layer_variant(i))
         kern = "conv_patch_kernel" if sk < 0 else ("conv_nhwc_kernel" + ("+fixup" if sk > 0 else ""))
+        if L.input < 0 and cin <= 4:
+            kern = "conv_igemm_kernel" + ("+fixup" if sk > 0 else "") + " (NCHW input)"
         if ho == 2 and sk >= 0:
             kern += " (2x2 map as one matrix)"
         kernels.add(kern.split(" ")[0])

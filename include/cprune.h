@@ -211,7 +211,8 @@ typedef struct cprune_net cprune_net;
 /* Builds a handle: copies every layer's weights and bias into memory the handle
  * owns (repacked channels-last: inside a handle activations are [n][h][w][c'] and weights
  * [c_out][kh][kw][c'], c' = channels rounded up to one 16-byte vector, pad channels zero;
- * x and logits at the boundary stay NCHW), allocates one activation buffer per layer for
+ * x and logits at the boundary stay NCHW; a dense conv with at most 4 input channels that
+ * reads the network input takes the NCHW tensor as it is), allocates one activation buffer per layer for
  * `max_batch` images and the conv scratch, and picks a tile variant per conv shape (timing it on the device
  * when tune != 0, as cprune_select_tile does, for batch `max_batch`).  `layers` is
  * a host array.  in_c/in_h/in_w: the network input [n][in_c][in_h][in_w]. */

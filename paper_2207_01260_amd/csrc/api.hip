@@ -41,10 +41,10 @@ int validate_conv_desc(const cprune_conv_desc* d) {
 }
 
 // ---- variant cache -------------------------------------------------------------
-typedef std::array<int, 17> DescKey;
+typedef std::array<int, 18> DescKey;
 static DescKey key_of(const cprune_conv_desc& d, const ConvLayout& lay) {
   return DescKey{d.n, d.c_in, d.h, d.w, d.c_out, d.kh, d.kw, d.stride, d.pad, d.groups, d.dtype, d.act,
-                 d.has_residual, lay.nhwc, lay.cp_in, lay.cp_out, lay.pool};
+                 d.has_residual, lay.nhwc, lay.cp_in, lay.cp_out, lay.pool, lay.nhwc_out};
 }
 static std::mutex g_cache_mutex;
 static std::map<DescKey, int> g_cache;
@@ -320,6 +320,8 @@ struct NetLayer {
   bool fused_pool = false;    // conv: the 2x2 max-pool that follows runs in its epilogue; act is the pooled map
   bool alias = false;         // max-pool folded into its producer: no kernel, act is the producer's buffer
   bool map2x2 = false;        // 3x3 / stride 1 / pad 1 conv on a 2x2 map, run as one matrix over the whole map
+  bool nchw_in = false;       // dense conv on the network input: reads the caller's NCHW tensor and its own
+                              // OIHW weights, writes channels-last (no layout conversion pass)
 };
 
 struct GraphKey {
@@ -336,6 +338,7 @@ struct cprune_net {
   int in_c, in_h, in_w, in_cp, max_batch, dtype;
   std::vector<void*> allocs;
   void* x_cl = nullptr;       // the network input, channels-last
+  bool convert_input = true;  // false when every reader of the input takes the caller's NCHW tensor itself
   void* ws = nullptr;
   size_t ws_bytes = 0;
   std::map<GraphKey, hipGraphExec_t> graphs;
@@ -366,6 +369,7 @@ static cprune_conv_desc layer_conv_desc(const cprune_net& net, const NetLayer& L
 static ConvLayout layer_layout(const NetLayer& L) {
   ConvLayout lay;
   lay.nhwc = 1; lay.cp_in = L.cp_in; lay.cp_out = L.cp_out; lay.pool = L.fused_pool ? 1 : 0;
+  if (L.nchw_in) { lay.nhwc = 0; lay.nhwc_out = 1; lay.cp_in = 0; return lay; }
   if (L.map2x2) {
     lay.cp_in = 4 * L.cp_in;
     if (L.fused_pool) lay.pool = 2;   // rows ordered (channel, pixel); cp_out stays the pooled map's stride
@@ -381,9 +385,9 @@ static void net_free(cprune_net* net) {
   delete net;
 }
 
-static int net_run_layer(cprune_net* net, int i, int n, void* out_override, hipStream_t s) {
+static int net_run_layer(cprune_net* net, int i, int n, const void* x, void* out_override, hipStream_t s) {
   NetLayer& L = net->layers[i];
-  const void* src = L.d.input < 0 ? net->x_cl : net->layers[L.d.input].act;
+  const void* src = L.d.input < 0 ? (L.nchw_in ? x : net->x_cl) : net->layers[L.d.input].act;
   void* dst = out_override ? out_override : L.act;
   switch (L.d.kind) {
     case CPRUNE_LAYER_CONV:
@@ -408,12 +412,13 @@ static int net_run_layer(cprune_net* net, int i, int n, void* out_override, hipS
 // channel stride is then the dense channel count); otherwise its buffer is converted.
 static int net_enqueue(cprune_net* net, const void* x, int n, void* logits, hipStream_t s) {
   const int nl = (int)net->layers.size();
-  int rc = launch_nchw_to_nhwc(x, n, net->in_c, net->in_h * net->in_w, net->in_cp, net->dtype, net->x_cl, s);
+  int rc = CPRUNE_OK;
+  if (net->convert_input) rc = launch_nchw_to_nhwc(x, n, net->in_c, net->in_h * net->in_w, net->in_cp, net->dtype, net->x_cl, s);
   if (rc != CPRUNE_OK) return rc;
   const NetLayer& last = net->layers[nl - 1];
   const bool direct = last.h_out * last.w_out == 1;
   for (int i = 0; i < nl; ++i) {
-    rc = net_run_layer(net, i, n, (i == nl - 1 && direct) ? logits : nullptr, s);
+    rc = net_run_layer(net, i, n, x, (i == nl - 1 && direct) ? logits : nullptr, s);
     if (rc != CPRUNE_OK) return rc;
   }
   if (!direct)
@@ -509,6 +514,19 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
       L.map2x2 = true;
   }
 
+  // A dense conv on the network input reads the caller's NCHW tensor directly (its few input
+  // channels gain nothing from the channels-last vector loads) and writes channels-last.
+  net->convert_input = false;
+  for (int i = 0; i < n_layers; ++i) {
+    NetLayer& L = net->layers[i];
+    if (L.d.input >= 0) continue;
+    if (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1 && L.d.c_in <= 4 && !L.fused_pool && !L.map2x2 &&
+        L.d.residual < 0 && L.cp_out == round_up_vec(L.d.c_out, dtype))
+      L.nchw_in = true;
+    else
+      net->convert_input = true;
+  }
+
   auto dev_alloc = [&](size_t bytes, void** p) -> int {
     hipError_t e = hipMalloc(p, bytes ? bytes : 16);
     if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
@@ -528,6 +546,20 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
       if (rc != CPRUNE_OK) break;
       rc = launch_repack_map2x2(d.weight, d.bias, d.c_out, d.c_in, L.cp_in, cpo, L.fused_pool ? 1 : 0, dtype, L.w, L.b, s);
       if (rc != CPRUNE_OK) break;
+      cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
+      size_t need = conv_ws_bytes(cd, -1, layer_layout(L));
+      if (need > net->ws_bytes) net->ws_bytes = need;
+    } else if (L.nchw_in) {
+      const size_t nw = (size_t)d.c_out * d.c_in * d.k * d.k;
+      rc = dev_alloc(nw * es, &L.w);
+      if (rc != CPRUNE_OK) break;
+      hipError_t e = hipMemcpyAsync(L.w, d.weight, nw * es, hipMemcpyDeviceToDevice, s);
+      if (e == hipSuccess && d.bias) {
+        rc = dev_alloc((size_t)d.c_out * sizeof(float), (void**)&L.b);
+        if (rc != CPRUNE_OK) break;
+        e = hipMemcpyAsync(L.b, d.bias, (size_t)d.c_out * sizeof(float), hipMemcpyDeviceToDevice, s);
+      }
+      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; break; }
       cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
       size_t need = conv_ws_bytes(cd, -1, layer_layout(L));
       if (need > net->ws_bytes) net->ws_bytes = need;
@@ -631,15 +663,16 @@ extern "C" int cprune_net_layer_times(cprune_net* net, const void* x, int n, int
   hipError_t ec = hipEventCreate(&e1);
   if (ec != hipSuccess) { hipEventDestroy(e0); set_last_hip_error(ec); return CPRUNE_ERR_DEVICE; }
   net->last_n = n;
-  int rc = launch_nchw_to_nhwc(x, n, net->in_c, net->in_h * net->in_w, net->in_cp, net->dtype, net->x_cl, s);
+  int rc = CPRUNE_OK;
+  if (net->convert_input) rc = launch_nchw_to_nhwc(x, n, net->in_c, net->in_h * net->in_w, net->in_cp, net->dtype, net->x_cl, s);
   // layer by layer, in order (so every layer finds its inputs): `iters` launches back to
   // back between two events, which is how the layer runs inside a forward pass
   for (int i = 0; i < nl && rc == CPRUNE_OK; ++i) {
     ms_out[i] = 0.0f;
-    rc = net_run_layer(net, i, n, nullptr, s);   // untimed first run
+    rc = net_run_layer(net, i, n, x, nullptr, s);   // untimed first run
     if (rc != CPRUNE_OK || net->layers[i].alias) continue;
     hipError_t e = hipEventRecord(e0, s);
-    for (int it = 0; it < iters && rc == CPRUNE_OK && e == hipSuccess; ++it) rc = net_run_layer(net, i, n, nullptr, s);
+    for (int it = 0; it < iters && rc == CPRUNE_OK && e == hipSuccess; ++it) rc = net_run_layer(net, i, n, x, nullptr, s);
     if (e == hipSuccess) e = hipEventRecord(e1, s);
     if (e == hipSuccess) e = hipEventSynchronize(e1);
     float ms = 0.0f;

@@ -53,6 +53,8 @@ struct ConvLayout {
   int nhwc = 0;
   int cp_in = 0;
   int cp_out = 0;
+  int nhwc_out = 0;  // with nhwc = 0: NCHW input and OIHW weights (the boundary's layout) but a channels-last
+                     // output of channel stride cp_out: the first layer of a network handle
   int pool = 0;  // 1: channels-last 3x3 layer with a 2x2/2 max-pool fused behind the activation (patch kernels);
                  // 2: rows are (channel, position of a 2x2 map) and each group of four rows is reduced to its
                  //    maximum behind the activation; cp_out is the stride of the pooled output

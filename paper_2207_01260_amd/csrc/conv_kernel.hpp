@@ -62,6 +62,7 @@ struct ConvArgs {
   int Cp, Cop;        // channels-last kernels: channel stride of x / of y (elements)
   unsigned magic_cp;  // division by Cp
   int vec_out;        // channels-last: y may be written 4 channels at a time
+  int nhwc_out = 0;   // NCHW-input kernel: y is channels-last [p][Cop] (the first layer of a network handle)
   int pool4 = 0;      // channels-last: rows 4c..4c+3 are the four positions of channel c of a 2x2 map;
                       // their maximum (behind bias and activation) is stored as y[p][c] (Cop = stride of y)
   int slabs;          // reduction slabs per output tile
@@ -159,6 +160,57 @@ __device__ __forceinline__ void unit_range(const ConvArgs& a, int g, int& ub, in
   ue = (int)(e < a.units ? e : a.units);
 }
 
+// bias + residual + activation + channels-last store of one 16x16 block column:
+// a lane holds 4 consecutive channels of one pixel.
+template <typename T>
+__device__ __forceinline__ void nhwc_store4(const ConvArgs& a, const float4_t& acc, int p, int o) {
+  if (a.pool4) {
+    if (o >= a.O) return;
+    float m = apply_act(acc[0] + (a.bias ? a.bias[o] : 0.0f), a.act);
+#pragma unroll
+    for (int i = 1; i < 4; ++i) m = fmaxf(m, apply_act(acc[i] + (a.bias ? a.bias[o + i] : 0.0f), a.act));
+    ((T*)a.y)[(size_t)p * a.Cop + (o >> 2)] = Elem<T>::from_f32(m);
+    return;
+  }
+  if (o >= a.Cop) return;
+  float v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = acc[i] + ((a.bias && o + i < a.O) ? a.bias[o + i] : 0.0f);
+  const size_t off = (size_t)p * a.Cop + o;
+  if (a.vec_out) {
+    if (a.res) {
+      if constexpr (sizeof(T) == 4) {
+        const float4 rv = *(const float4*)((const float*)a.res + off);
+        v[0] += rv.x; v[1] += rv.y; v[2] += rv.z; v[3] += rv.w;
+      } else {
+        const T* rp = (const T*)a.res + off;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] += Elem<T>::to_f32(rp[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = apply_act(v[i], a.act);
+    if constexpr (sizeof(T) == 4) {
+      *(float4*)((float*)a.y + off) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+      T h[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) h[i] = Elem<T>::from_f32(v[i]);
+      *(uint2*)((T*)a.y + off) = *(const uint2*)h;
+    }
+  } else {
+    // dense output whose channel stride is not a vector multiple (the logits)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (o + i < a.Cop) {
+        float val = v[i];
+        if (a.res) val += Elem<T>::to_f32(((const T*)a.res)[off + i]);
+        ((T*)a.y)[off + i] = Elem<T>::from_f32(apply_act(val, a.act));
+      }
+    }
+  }
+}
+
 // bias + residual + activation + store of one wave's accumulators.
 template <typename T, int WM, int WN, int MB, int NB>
 __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, const float4_t (&acc)[MB][NB], int tile_m,
@@ -171,6 +223,11 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs& a, const float4_t 
   for (int j = 0; j < NB; ++j) {
     const int p = tile_p * PT + wn * NB * 16 + j * 16 + r;
     if (p >= a.P) continue;
+    if (a.nhwc_out) {   // the pixel index is the same in both layouts; only the store differs
+#pragma unroll
+      for (int i = 0; i < MB; ++i) nhwc_store4<T>(a, acc[i][j], p, m_wave + i * 16 + 4 * g4);
+      continue;
+    }
     const int n = p / a.HoWo;
     const int rem = p - n * a.HoWo;
     const size_t pix = (size_t)n * a.O * a.HoWo + rem;
@@ -466,6 +523,10 @@ __global__ __launch_bounds__(256) void conv_fixup_kernel(ConvArgs a) {
   const int tile_m = tile % a.tiles_m, tile_p = tile / a.tiles_m;
   const int p = tile_p * PT + wn * NB * 16 + bj * 16 + r;
   if (p >= a.P) return;
+  if (a.nhwc_out) {
+    nhwc_store4<T>(a, acc, p, tile_m * MT + wm * MB * 16 + bi * 16 + 4 * g4);
+    return;
+  }
   const int n = p / a.HoWo;
   const int rem = p - n * a.HoWo;
   const size_t pix = (size_t)n * a.O * a.HoWo + rem;

@@ -102,6 +102,7 @@ bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
     return d.h * 2 > tv.th && d.w * 2 > tv.tw;
   }
   if (lay.pool == 1) return false;                // only the patch kernels fuse a spatial pool
+  if (lay.pool && lay.nhwc_out && !lay.nhwc) return false;
   if (lay.pool == 2 && !(lay.nhwc && (d.c_out & 3) == 0)) return false;
   const int ho = conv_out_dim(d.h, d.kh, d.stride, d.pad), wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
   const long P = (long)d.n * ho * wo;
@@ -171,6 +172,7 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
   a.magic_cp = magic_for((unsigned)lay.cp_in);
   a.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
   a.pool4 = lay.pool == 2 ? 1 : 0;
+  a.nhwc_out = (!lay.nhwc && lay.nhwc_out) ? 1 : 0;
   a.HoWo = a.Ho * a.Wo;
   a.P = d.n * a.HoWo;
   a.HW = d.h * d.w;

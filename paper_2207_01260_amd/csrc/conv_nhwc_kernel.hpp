@@ -23,57 +23,6 @@ __device__ __forceinline__ uint4 load_b128(__amdgpu_buffer_rsrc_t r, unsigned vo
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-// bias + residual + activation + channels-last store of one 16x16 block column:
-// a lane holds 4 consecutive channels of one pixel.
-template <typename T>
-__device__ __forceinline__ void nhwc_store4(const ConvArgs& a, const float4_t& acc, int p, int o) {
-  if (a.pool4) {
-    if (o >= a.O) return;
-    float m = apply_act(acc[0] + (a.bias ? a.bias[o] : 0.0f), a.act);
-#pragma unroll
-    for (int i = 1; i < 4; ++i) m = fmaxf(m, apply_act(acc[i] + (a.bias ? a.bias[o + i] : 0.0f), a.act));
-    ((T*)a.y)[(size_t)p * a.Cop + (o >> 2)] = Elem<T>::from_f32(m);
-    return;
-  }
-  if (o >= a.Cop) return;
-  float v[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) v[i] = acc[i] + ((a.bias && o + i < a.O) ? a.bias[o + i] : 0.0f);
-  const size_t off = (size_t)p * a.Cop + o;
-  if (a.vec_out) {
-    if (a.res) {
-      if constexpr (sizeof(T) == 4) {
-        const float4 rv = *(const float4*)((const float*)a.res + off);
-        v[0] += rv.x; v[1] += rv.y; v[2] += rv.z; v[3] += rv.w;
-      } else {
-        const T* rp = (const T*)a.res + off;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] += Elem<T>::to_f32(rp[i]);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = apply_act(v[i], a.act);
-    if constexpr (sizeof(T) == 4) {
-      *(float4*)((float*)a.y + off) = make_float4(v[0], v[1], v[2], v[3]);
-    } else {
-      T h[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) h[i] = Elem<T>::from_f32(v[i]);
-      *(uint2*)((T*)a.y + off) = *(const uint2*)h;
-    }
-  } else {
-    // dense output whose channel stride is not a vector multiple (the logits)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (o + i < a.Cop) {
-        float val = v[i];
-        if (a.res) val += Elem<T>::to_f32(((const T*)a.res)[off + i]);
-        ((T*)a.y)[off + i] = Elem<T>::from_f32(apply_act(val, a.act));
-      }
-    }
-  }
-}
-
 template <typename T, int WM, int WN, int MB, int NB, int KQ>
 __global__ __launch_bounds__(256) void conv_nhwc_kernel(ConvArgs a) {
   constexpr int ES = (int)sizeof(T);
