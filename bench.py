@@ -8,10 +8,12 @@ gather with BN folding) and the per-shape tile selection run before the timed re
 are reported separately (`prune_ms`, `tune_s`).  Inputs and weights are resident in HBM
 when timing starts.
 
-Prints ONE JSON line.  `value`: images/s over the timed steps.  `roofline`: useful FLOP of the
-13 conv layers of a step over the sum of their device times (HIP events around back-to-back
-launches of each layer), against the dense fp32 / fp16 MFMA peak; `traffic`: bytes between L2
-and fabric per conv layer from hardware counters (fixed figure for the default workload).
+Prints ONE JSON line.  `value`: images/s over the timed steps.  `roofline`: the dominant
+kernel (the conv instantiation with the most device time per step): useful FLOP of the layers it
+runs over the sum of their device times (HIP events around back-to-back launches of each layer),
+against the dense fp32 / fp16 MFMA peak; `traffic`: its bytes between L2 and fabric per launch
+from hardware counters (fixed figures for the default workload).  `conv_layers`: the same ratio
+over all 13 conv layers.
 `cpu_baseline`: the CPU oracle's forward on a bounded sample of the same images.
 """
 import argparse
@@ -25,10 +27,17 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}   # dense MFMA TFLOP/s, MI355X
-# Bytes between L2 and fabric per conv layer launch (FETCH_SIZE + WRITE_SIZE of all conv kernels of a
-# step, scaled by a copy kernel of known size, / 13) for the default workload, from the rocprofv3
-# counter runs summarised in profiles/vgg16_b64_f32_hbm_traffic.md.  Valid for that workload only.
-TRAFFIC_F32_B64 = 10.05 * 2 ** 20
+# Bytes between L2 and fabric per launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the counter
+# reads for a copy kernel of known size), by (kernel instantiation, batch), for the default workload:
+# from the rocprofv3 counter runs summarised in profiles/vgg16_b64_f32_hbm_traffic.md.  A kernel that
+# is not listed (the timed selection picked another variant) reports null.
+TRAFFIC = {
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64): 8888493,     # algorithmic (conv3-6 average): 6.4e6
+    ("conv_patch_kernel<float, 2, 8, 16, 1, 1, 1>", 64): 9849711,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 1>", 64): 12131649,
+    ("conv_patch_kernel<float, 1, 4, 4, 4, 1, 1>", 64): 10282022,
+    ("conv_patch_kernel<float, 1, 4, 4, 4, 2, 2>", 64): 14947033,
+}
 
 
 def main():
@@ -120,31 +129,35 @@ def main():
     ms = time_forward(handle, x, args.steps, args.warmup, graph)
     value = args.batch / (ms * 1e-3)
 
-    # per-layer device time (HIP events on the launch stream), conv layers = dominant kernel
+    # per-layer device time (HIP events on the launch stream around back-to-back launches)
     layer_ms = handle.layer_times(x, iters=20)
     conv_ms = sum(m for m, L in zip(layer_ms, net.layers) if L.kind == "conv")
     n_conv = sum(1 for L in net.layers if L.kind == "conv")
     conv_flops = pipeline.useful_flops(net, kept_counts, args.batch, conv_only=True)
     total_flops = pipeline.useful_flops(net, kept_counts, args.batch)
-    achieved = conv_flops / (conv_ms * 1e-3) / 1e12
     per_layer = []
-    kernels = set()
+    by_kernel = {}        # kernel instantiation -> [launches, ms, flop]
     shp = synth.shapes(net, kept_counts)
     for i, (L, m) in enumerate(zip(net.layers, layer_ms)):
         if L.kind != "conv":
             continue
         cin, cout, ho, wo = shp[i]
         fl = 2.0 * args.batch * cout * cin * 9 * ho * wo
-        tm, tp, sk = B.cprune_tile_variant_info(handle.layer_variant(i))
-        kern = "conv_patch_kernel" if sk < 0 else ("conv_nhwc_kernel" + ("+fixup" if sk > 0 else ""))
-        if L.input < 0 and cin <= 4:
-            kern = "conv_igemm_kernel" + ("+fixup" if sk > 0 else "") + " (NCHW input)"
-        if ho == 2 and sk >= 0:
-            kern += " (2x2 map as one matrix)"
-        kernels.add(kern.split(" ")[0])
+        v = handle.layer_variant(i)
+        tm, tp, sk = B.cprune_tile_variant_info(v)
+        first = L.input < 0 and cin <= 4         # reads the NCHW input itself
+        kern = B.cprune_tile_variant_name(v, channels_last=not first, dtype=dt)
+        note = (" + fix-up" if sk > 0 else "") + (" (2x2 map as one matrix)" if (ho == 2 and sk >= 0) else "")
+        g = by_kernel.setdefault(kern, [0, 0.0, 0.0])
+        g[0] += 1; g[1] += m; g[2] += fl
         per_layer.append({"layer": L.name, "c_in": cin, "c_out": cout, "hw": ho, "us": round(m * 1e3, 2),
                           "tflops": round(fl / (m * 1e-3) / 1e12, 2), "tile": f"{tm}x{tp}/s{sk}",
-                          "kernel": kern})
+                          "kernel": kern + note})
+    # the dominant kernel: the instantiation with the most device time per step
+    dom = max(by_kernel, key=lambda k: by_kernel[k][1])
+    d_n, d_ms, d_fl = by_kernel[dom]
+    achieved = d_fl / (d_ms * 1e-3) / 1e12
+    agg = conv_flops / (conv_ms * 1e-3) / 1e12
 
     out = {
         "metric": "images/sec pruned VGG-16 32x32",
@@ -158,13 +171,18 @@ def main():
         "useful_gflop_per_step": round(total_flops / 1e9, 3),
         "whole_net_tflops": round(total_flops / (ms * 1e-3) / 1e12, 2),
         "prune_ms": round(prune_ms, 3), "tune_s": round(tune_s, 2), "variants": variants,
-        "roofline": {"bound": "mfma", "kernel": " / ".join(sorted(kernels)) + " (the 13 conv layers of one step)",
+        "roofline": {"bound": "mfma", "kernel": dom, "launches_per_step": d_n,
                      "achieved": round(achieved, 2), "peak": PEAK[args.dtype], "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK[args.dtype], 4),
-                     "traffic": (round(TRAFFIC_F32_B64) if (args.dtype == "f32" and args.batch == 64) else None),
-                     "traffic_unit": "bytes per conv layer (FETCH_SIZE + WRITE_SIZE, scaled; algorithmic: 5.29e6)",
-                     "launches_per_step": n_conv, "avg_launch_us": round(conv_ms / n_conv * 1e3, 2),
-                     "useful_gflop_per_launch_avg": round(conv_flops / n_conv / 1e9, 3)},
+                     "traffic": TRAFFIC.get((dom, args.batch)),
+                     "traffic_unit": "bytes per launch between L2 and fabric (FETCH_SIZE + WRITE_SIZE, scaled)",
+                     "avg_launch_us": round(d_ms / d_n * 1e3, 2),
+                     "useful_gflop_per_launch": round(d_fl / d_n / 1e9, 3),
+                     "share_of_step": round(d_ms / ms, 3)},
+        "conv_layers": {"launches_per_step": n_conv, "tflops": round(agg, 2),
+                        "frac_of_peak": round(agg / PEAK[args.dtype], 4),
+                        "avg_layer_us": round(conv_ms / n_conv * 1e3, 2),
+                        "useful_gflop_per_layer_avg": round(conv_flops / n_conv / 1e9, 3)},
         "layers": per_layer,
     }
     handle.close()

@@ -137,6 +137,11 @@ typedef struct {
  * CPRUNE_ERR_UNSUPPORTED. */
 int cprune_num_tile_variants(void);
 int cprune_tile_variant_info(int variant, int* tile_m, int* tile_p, int* sched); /* host out */
+/* The kernel instantiation behind a variant, written as profilers print it (e.g.
+ * "conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>"): channels_last = 0 names the NCHW kernel of
+ * cprune_conv2d_bn_relu, 1 the one used inside a network handle.  buf: host, buf_bytes >= 96. */
+int cprune_tile_variant_name(int variant, int channels_last, cprune_dtype dtype, char* buf,
+                             size_t buf_bytes);
 
 /* Scratch needed by `variant` (-1 = the largest any variant needs for desc). */
 size_t cprune_conv_workspace_bytes(const cprune_conv_desc* desc, int variant);

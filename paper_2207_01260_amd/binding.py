@@ -41,7 +41,8 @@ EXPORTS = [
     "cprune_status_string", "cprune_last_hip_error",
     "cprune_rank_filters_workspace_bytes", "cprune_rank_filters", "cprune_rank_filter_group",
     "cprune_gather_pruned_weights", "cprune_gather_channels",
-    "cprune_num_tile_variants", "cprune_tile_variant_info", "cprune_conv_workspace_bytes",
+    "cprune_num_tile_variants", "cprune_tile_variant_info", "cprune_tile_variant_name",
+    "cprune_conv_workspace_bytes",
     "cprune_conv2d_bn_relu", "cprune_select_tile", "cprune_clear_tile_cache",
     "cprune_cached_tile", "cprune_maxpool2d", "cprune_global_avgpool",
     "cprune_fc_workspace_bytes", "cprune_fc",
@@ -197,6 +198,13 @@ def out_shape(d: ConvDesc):
 
 def cprune_num_tile_variants() -> int:
     return int(lib().cprune_num_tile_variants())
+
+
+def cprune_tile_variant_name(v: int, channels_last: bool = True, dtype: int = F32) -> str:
+    buf = C.create_string_buffer(128)
+    _check(lib().cprune_tile_variant_name(C.c_int(v), C.c_int(1 if channels_last else 0), C.c_int(dtype), buf,
+                                          C.c_size_t(128)), "cprune_tile_variant_name")
+    return buf.value.decode()
 
 
 def cprune_tile_variant_info(v: int) -> Tuple[int, int, int]:

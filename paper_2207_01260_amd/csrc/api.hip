@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <array>
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 
 namespace cprune {
@@ -204,6 +205,22 @@ extern "C" int cprune_tile_variant_info(int v, int* tile_m, int* tile_p, int* sc
   if (tile_p) *tile_p = tv.tile_p();
   if (sched) *sched = tv.sched;
   return CPRUNE_OK;
+}
+
+extern "C" int cprune_tile_variant_name(int v, int channels_last, cprune_dtype dtype, char* buf, size_t buf_bytes) {
+  if (v < 0 || v >= num_variants() || !buf || buf_bytes < 1 || !dtype_ok(dtype)) return CPRUNE_ERR_INVALID_ARG;
+  const TileVariant& tv = variant(v);
+  const char* t = dtype == CPRUNE_F32 ? "float" : dtype == CPRUNE_F16 ? "_Float16" : "__bf16";
+  int n;
+  if (tv.sched >= 0)
+    n = snprintf(buf, buf_bytes, "%s<%s, %d, %d, %d, %d, %d>", channels_last ? "conv_nhwc_kernel" : "conv_igemm_kernel", t,
+                 tv.wm, tv.wn, tv.mb, tv.nb, tv.kq);
+  else if (tv.blk32)
+    n = snprintf(buf, buf_bytes, "conv_patch32_kernel<%s, %d, %d, %d, %d, %d, %d, %d>", t, tv.mb / 2, tv.nb / 2, tv.wn, tv.th,
+                 tv.tw, tv.ni, tv.kq);
+  else
+    n = snprintf(buf, buf_bytes, "conv_patch_kernel<%s, %d, %d, %d, %d, %d, %d>", t, tv.mb, tv.th, tv.tw, tv.ni, tv.kq, tv.ks);
+  return (n < 0 || (size_t)n >= buf_bytes) ? CPRUNE_ERR_INVALID_ARG : CPRUNE_OK;
 }
 
 extern "C" size_t cprune_conv_workspace_bytes(const cprune_conv_desc* desc, int v) {

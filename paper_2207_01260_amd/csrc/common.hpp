@@ -39,6 +39,7 @@ struct TileVariant {
                 // -1 = 3x3 spatial-patch kernel (one th x tw pixel block per work-group)
   int th = 0, tw = 0, ni = 1, patch_id = -1;
   int blk32 = 0;  // patch kernels: 1 = 32x32 MFMA blocks (patch_id then indexes that kernel's list)
+  int ks = 1;     // patch kernels on 16x16 blocks: wave groups per tile
   int tile_m() const { return wm * mb * 16; }
   int tile_p() const { return wn * nb * 16; }
 };

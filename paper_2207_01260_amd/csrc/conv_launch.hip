@@ -68,7 +68,7 @@ const TileVariant& variant(int id) {
     {                                                                         \
       TileVariant& pv = table[kNumTiles * kNumScheds + ID];                   \
       pv.wm = 1; pv.wn = 4; pv.mb = MB_; pv.nb = (TH_ * TW_ * NI_) / 64; pv.kq = KQ_; pv.ni = NI_; \
-      pv.sched = -1; pv.th = TH_; pv.tw = TW_; pv.patch_id = ID;              \
+      pv.sched = -1; pv.th = TH_; pv.tw = TW_; pv.patch_id = ID; pv.ks = KS_; \
     }
     CPRUNE_PATCH_LIST(CPRUNE_PATCH_ROW)
 #undef CPRUNE_PATCH_ROW
