@@ -28,15 +28,13 @@ if ROOT not in sys.path:
 
 PEAK = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}   # dense MFMA TFLOP/s, MI355X
 # Bytes between L2 and fabric per launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the counter
-# reads for a copy kernel of known size), by (kernel instantiation, batch), for the default workload:
-# from the rocprofv3 counter runs summarised in profiles/vgg16_b64_f32_hbm_traffic.md.  A kernel that
-# is not listed (the timed selection picked another variant) reports null.
+# reads for a copy kernel of known size), by (kernel instantiation, batch, layers it ran per step), for
+# the default workload: from the rocprofv3 counter runs summarised in
+# profiles/vgg16_b64_f32_hbm_traffic.md.  The timed selection decides which layers a kernel runs; when
+# that differs from the profiled run the figure does not apply and null is reported.
 TRAFFIC = {
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64): 8888493,     # algorithmic (conv3-6 average): 6.4e6
-    ("conv_patch_kernel<float, 2, 8, 16, 1, 1, 1>", 64): 9849711,
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 1>", 64): 12131649,
-    ("conv_patch_kernel<float, 1, 4, 4, 4, 1, 1>", 64): 10282022,
-    ("conv_patch_kernel<float, 1, 4, 4, 4, 2, 2>", 64): 14947033,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, 4): 8888493,     # algorithmic (conv3-6 average): 6.4e6
+    ("conv_patch_kernel<float, 1, 4, 4, 4, 1, 1>", 64, 2): 10282022,
 }
 
 
@@ -174,7 +172,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": dom, "launches_per_step": d_n,
                      "achieved": round(achieved, 2), "peak": PEAK[args.dtype], "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK[args.dtype], 4),
-                     "traffic": TRAFFIC.get((dom, args.batch)),
+                     "traffic": TRAFFIC.get((dom, args.batch, d_n)),
                      "traffic_unit": "bytes per launch between L2 and fabric (FETCH_SIZE + WRITE_SIZE, scaled)",
                      "avg_launch_us": round(d_ms / d_n * 1e3, 2),
                      "useful_gflop_per_launch": round(d_fl / d_n / 1e9, 3),
