@@ -198,3 +198,53 @@ def test_mobilenetv2_full_size_batch1(orc):
     handle, *_ = _run(orc, synth.mobilenetv2(1000, 224), 4, 1, B.F32, tune=False,
                       check_layers=False)
     handle.close()
+
+
+# ---- the channels-last kernels on arbitrary layer shapes, every variant -----------------
+
+def _two_layer_net(c0, c1, c2, hw, k, stride, pad, act, residual):
+    net = synth.NetSpec(f"probe_{c0}_{c1}_{c2}_{hw}_{k}_{stride}", c0, hw, hw)
+    a = net.add(synth.Layer("conv", -1, c0, c1, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="a"))
+    net.add(synth.Layer("conv", a, c1, c2, k=k, stride=stride, pad=pad, act=act, bn=True,
+                        residual=(a if residual else None), name="b"))
+    return net
+
+
+@pytest.mark.parametrize("cfg", [
+    # c0, c1, c2, hw, k, stride, pad, act, residual, batch, dtype
+    (5, 37, 45, 13, 3, 1, 1, synth.ACT_RELU, False, 3, B.F32),       # ragged everything
+    (8, 24, 24, 12, 3, 1, 1, synth.ACT_NONE, True, 2, B.F32),        # shortcut add, no activation
+    (6, 64, 100, 14, 1, 1, 0, synth.ACT_RELU6, False, 2, B.F32),     # 1x1
+    (6, 40, 70, 15, 1, 2, 0, synth.ACT_NONE, False, 2, B.F32),       # strided 1x1 (downsample)
+    (7, 19, 33, 17, 3, 2, 1, synth.ACT_RELU, False, 2, B.F32),       # strided 3x3
+    (5, 9, 20, 21, 7, 2, 3, synth.ACT_RELU, False, 1, B.F32),        # 7x7 / 2
+    (6, 12, 18, 11, 5, 1, 2, synth.ACT_RELU, False, 2, B.F32),       # 5x5
+    (8, 44, 44, 8, 3, 1, 1, synth.ACT_RELU, True, 5, B.BF16),        # 16-bit, shortcut, 8x8 map
+    (8, 30, 50, 4, 3, 1, 1, synth.ACT_RELU, False, 9, B.F16),        # 4x4 map: multi-image tiles
+])
+def test_channels_last_layer_every_variant(orc, cfg):
+    c0, c1, c2, hw, k, stride, pad, act, residual, batch, dtype = cfg
+    print("probe", cfg, flush=True)
+    net = _two_layer_net(c0, c1, c2, hw, k, stride, pad, act, residual)
+    cid = 40 + k + stride
+    params = synth.layer_params(net, cid)
+    x = synth.net_input(net, cid, batch)
+    ref_layers, _ = orc.prune_net(net, params)
+    ref = orc.forward(net, ref_layers, x)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), dtype)
+    handle = pipeline.build_net(net, layers, batch, dtype, tune=False)
+    xd = torch.from_numpy(x).cuda().to(B.TORCH_DTYPE[dtype])
+    ran = 0
+    for v in range(B.cprune_num_tile_variants()):
+        try:
+            handle.set_layer_variant(1, v)
+        except B.CPruneError as e:
+            assert e.status == B.ERR_UNSUPPORTED
+            continue
+        ran += 1
+        out = handle.forward(xd)
+        torch.cuda.synchronize()
+        err = nmax(out.float().cpu().numpy(), ref)
+        assert err < TOL[dtype], (v, B.cprune_tile_variant_name(v, True, dtype), err)
+    handle.close()
+    assert ran >= 100 or (k == 3 and stride == 1 and ran >= 110)
