@@ -324,7 +324,8 @@ extern "C" int cprune_fc(const void* x, const void* w, const float* bias, int n,
 // Inside a handle everything is channels-last: activations [n][h][w][cp], dense weights
 // [c_out][kh][kw][cp], depthwise weights [kh][kw][cp], with cp the channel count rounded up
 // to one 16-byte vector (pad channels are zero and stay zero through every layer).  The
-// boundary stays NCHW: the input is converted on the way in, activations on the way out.
+// boundary stays NCHW: a dense first layer with few input channels reads the caller's tensor
+// as it is (any other reader gets a converted copy); activations are converted on the way out.
 struct NetLayer {
   cprune_layer_desc d;
   int h_in, w_in, h_out, w_out;

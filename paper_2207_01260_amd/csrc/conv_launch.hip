@@ -60,10 +60,10 @@ Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv, const ConvLayou
 
 int num_variants() { return kNumTiles * kNumScheds + kNumPatch + kNumPatch32; }
 
-const TileVariant& variant(int id) {
-  static TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32];
-  static bool init = false;
-  if (!init) {
+namespace {
+struct VariantTable {
+  TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32];
+  VariantTable() {
 #define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_, KQ_, KS_)                                 \
     {                                                                         \
       TileVariant& pv = table[kNumTiles * kNumScheds + ID];                   \
@@ -85,9 +85,13 @@ const TileVariant& variant(int id) {
         table[t * kNumScheds + s] = kTiles[t];
         table[t * kNumScheds + s].sched = kScheds[s];
       }
-    init = true;
   }
-  return table[id];
+};
+}  // namespace
+
+const TileVariant& variant(int id) {
+  static const VariantTable vt;   // built once, on first use, whichever thread gets there first
+  return vt.table[id];
 }
 
 bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
