@@ -234,7 +234,8 @@ int cprune_net_forward(cprune_net* net, const void* x, int n, void* logits, int 
                        void* stream);
 /* Per-layer device time: after one untimed pass that gives every layer its inputs, each
  * layer is launched `iters` times back to back between two events on `stream`; ms_out
- * (host, [n_layers]) gets the time per launch (0 for a pool folded into its producer).
+ * (host, [n_layers]) gets the time per launch (0 for a pool folded into its producer and for a depthwise layer
+ * that runs inside its reader's kernel).
  * Synchronises. */
 int cprune_net_layer_times(cprune_net* net, const void* x, int n, int iters, float* ms_out,
                            void* stream);
@@ -242,13 +243,22 @@ int cprune_net_layer_times(cprune_net* net, const void* x, int n, int iters, flo
  * NCHW [n][c_out][h_out][w_out].  For the last layer of a net whose output map is 1x1 the
  * values are those of the last cprune_net_layer_times pass (forward writes that layer
  * straight into `logits`).  A conv layer whose following 2x2 max-pool was fused into its
- * epilogue has no activation of its own: CPRUNE_ERR_UNSUPPORTED (ask for the pool layer). */
+ * epilogue has no activation of its own: CPRUNE_ERR_UNSUPPORTED (ask for the pool layer); so
+ * has a depthwise layer that runs inside the kernel of the 1x1 conv that reads it. */
 int cprune_net_copy_activation(cprune_net* net, int layer, int n, void* dst, size_t dst_bytes,
                                void* stream);
 /* Shape of one image's output (the last layer's c_out, h_out, w_out); host outs. */
 int cprune_net_output_shape(const cprune_net* net, int* c_out, int* h_out, int* w_out);
 /* The tile variant in use for layer `layer` (-1 for layers without one); host out. */
 int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out);
+/* A depthwise conv (3x3 or 5x5, stride 1 or 2, "same" padding) whose only reader is a 1x1
+ * conv can run inside that conv's kernel (the tensor between them is then never stored).
+ * cprune_net_create decides per pair (by size, or by timing both forms when tune != 0);
+ * this call overrides the decision for depthwise layer `layer`.  CPRUNE_ERR_UNSUPPORTED when
+ * the layer is no such depthwise conv.  Recorded graphs are dropped.  Not to be called while
+ * a forward is in flight.  cprune_net_layer_fused reports the current state (host out). */
+int cprune_net_fuse_depthwise(cprune_net* net, int layer, int enable);
+int cprune_net_layer_fused(const cprune_net* net, int layer, int* fused_out);
 /* Pins the tile variant of a dense conv / fully connected layer (what a stored tuning result
  * is applied with).  CPRUNE_ERR_INVALID_ARG for a layer without variants,
  * CPRUNE_ERR_UNSUPPORTED when the variant cannot run that layer's shape.  Recorded graphs

@@ -48,7 +48,8 @@ EXPORTS = [
     "cprune_fc_workspace_bytes", "cprune_fc",
     "cprune_net_create", "cprune_net_forward", "cprune_net_layer_times",
     "cprune_net_copy_activation", "cprune_net_output_shape", "cprune_net_layer_variant",
-    "cprune_net_set_layer_variant", "cprune_net_destroy",
+    "cprune_net_set_layer_variant", "cprune_net_fuse_depthwise", "cprune_net_layer_fused",
+    "cprune_net_destroy",
     "cprune_probe_scratch_bytes", "cprune_probe_mfma", "cprune_probe_copy",
     "cprune_lcm_step", "cprune_prune_count", "cprune_variant_filter_splits",
     "cprune_variant_prune_step", "cprune_order_tasks", "cprune_net_task_table",
@@ -412,6 +413,15 @@ class Net:
         n = C.c_int(0)
         _check(lib().cprune_net_task_table(self._h, tasks, C.byref(n)), "cprune_net_task_table")
         return list(tasks), int(n.value)
+
+    def fuse_depthwise(self, layer: int, enable: bool):
+        _check(lib().cprune_net_fuse_depthwise(self._h, C.c_int(layer), C.c_int(1 if enable else 0)),
+               "cprune_net_fuse_depthwise")
+
+    def layer_fused(self, layer: int) -> bool:
+        f = C.c_int(0)
+        _check(lib().cprune_net_layer_fused(self._h, C.c_int(layer), C.byref(f)), "cprune_net_layer_fused")
+        return bool(f.value)
 
     def set_layer_variant(self, layer: int, variant: int):
         _check(lib().cprune_net_set_layer_variant(self._h, C.c_int(layer), C.c_int(variant)),

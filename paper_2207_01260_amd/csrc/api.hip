@@ -338,6 +338,9 @@ struct NetLayer {
   bool fused_pool = false;    // conv: the 2x2 max-pool that follows runs in its epilogue; act is the pooled map
   bool alias = false;         // max-pool folded into its producer: no kernel, act is the producer's buffer
   bool map2x2 = false;        // 3x3 / stride 1 / pad 1 conv on a 2x2 map, run as one matrix over the whole map
+  int fuse_dw = -1;           // 1x1 conv: index of the depthwise layer computed inside its kernel, or -1
+  bool fused_away = false;    // depthwise conv that runs inside its consumer's kernel (no launch, no activation)
+  int dw_reader = -1;         // depthwise conv that may run inside the 1x1 conv dw_reader's kernel
   bool nchw_in = false;       // dense conv on the network input: reads the caller's NCHW tensor and its own
                               // OIHW weights, writes channels-last (no layout conversion pass)
 };
@@ -403,10 +406,41 @@ static void net_free(cprune_net* net) {
   delete net;
 }
 
+// Depthwise layer P.fuse_dw and the 1x1 layer i in one kernel: reads the depthwise layer's input.
+static int net_run_dwproj(cprune_net* net, int i, int n, void* dst, hipStream_t s) {
+  const NetLayer& P = net->layers[i];
+  const NetLayer& D = net->layers[P.fuse_dw];
+  const size_t es = dtype_size(net->dtype);
+  DwProjArgs a;
+  a.x = net->layers[D.d.input].act;
+  a.wdw = D.w; a.bdw = D.b; a.wp = P.w; a.bp = P.b;
+  a.res = P.d.residual >= 0 ? net->layers[P.d.residual].act : nullptr;
+  a.y = dst;
+  a.N = n; a.H = D.h_in; a.W = D.w_in; a.Ho = D.h_out; a.Wo = D.w_out;
+  a.Ce = D.d.c_out; a.Cpe = D.cp_in; a.O = P.d.c_out; a.Cop = P.cp_out;
+  a.pad = D.d.pad; a.act_dw = D.d.act; a.act_out = P.d.act;
+  const int mb = P.d.c_out <= 32 ? 2 : (P.d.c_out <= 64 ? 4 : 8);
+  a.tiles_y = (a.Ho + 7) / 8; a.tiles_x = (a.Wo + 7) / 8; a.tiles_m = (a.O + mb * 16 - 1) / (mb * 16);
+  a.x_bytes = (unsigned)((size_t)n * a.H * a.W * a.Cpe * es);
+  a.wp_bytes = (unsigned)((size_t)a.O * a.Cpe * es);
+  a.wdw_bytes = (unsigned)((size_t)D.d.k * D.d.k * a.Cpe * es);
+  a.vec_out = (a.Cop % 4) == 0 ? 1 : 0;
+  dim3 grid((unsigned)(n * a.tiles_y * a.tiles_x * a.tiles_m));
+  int rc;
+  if (net->dtype == CPRUNE_F32) rc = launch_dwproj_f32(D.d.k, D.d.stride, mb, grid, s, a);
+  else if (net->dtype == CPRUNE_F16) rc = launch_dwproj_f16(D.d.k, D.d.stride, mb, grid, s, a);
+  else rc = launch_dwproj_bf16(D.d.k, D.d.stride, mb, grid, s, a);
+  if (rc != CPRUNE_OK) return rc;
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
 static int net_run_layer(cprune_net* net, int i, int n, const void* x, void* out_override, hipStream_t s) {
   NetLayer& L = net->layers[i];
   const void* src = L.d.input < 0 ? (L.nchw_in ? x : net->x_cl) : net->layers[L.d.input].act;
   void* dst = out_override ? out_override : L.act;
+  if (L.fused_away) return CPRUNE_OK;
+  if (L.fuse_dw >= 0) return net_run_dwproj(net, i, n, dst, s);
   switch (L.d.kind) {
     case CPRUNE_LAYER_CONV:
     case CPRUNE_LAYER_FC: {
@@ -633,6 +667,58 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     }
     L.variant = v;
   }
+  // A depthwise conv whose only reader is a 1x1 conv can run inside that conv's kernel: the
+  // expanded activations are then read once and never written.  It pays on large maps (enough
+  // 8x8 pixel blocks to fill the chip); with tune != 0 both forms are timed and the faster kept.
+  for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
+    NetLayer& D = net->layers[i];
+    const cprune_layer_desc& dd = D.d;
+    if (!(dd.kind == CPRUNE_LAYER_CONV && dd.groups != 1 && dd.input >= 0 && dd.residual < 0)) continue;
+    if (!((dd.k == 3 || dd.k == 5) && (dd.stride == 1 || dd.stride == 2) && dd.pad == dd.k / 2)) continue;
+    int reader = -1, readers = 0;
+    for (int j = 0; j < n_layers; ++j) {
+      if (net->layers[j].d.input == i) { reader = j; ++readers; }
+      if (net->layers[j].d.residual == i) readers += 2;
+    }
+    if (readers != 1 || i == n_layers - 1) continue;
+    NetLayer& P = net->layers[reader];
+    const cprune_layer_desc& pd = P.d;
+    if (!(pd.kind == CPRUNE_LAYER_CONV && pd.groups == 1 && pd.k == 1 && pd.stride == 1 && pd.pad == 0)) continue;
+    if (P.cp_out != round_up_vec(pd.c_out, dtype) || P.nchw_in || P.map2x2 || P.fused_pool) continue;
+    D.dw_reader = reader;
+    const int mt = pd.c_out <= 32 ? 32 : (pd.c_out <= 64 ? 64 : 128);
+    const long groups = (long)max_batch * ((D.h_out + 7) / 8) * ((D.w_out + 7) / 8) * ((pd.c_out + mt - 1) / mt);
+    bool fuse = groups >= 512;
+    if (tune) {
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      hipError_t e = hipEventCreate(&e0);
+      if (e == hipSuccess) e = hipEventCreate(&e1);
+      float ms[2] = {0.f, 0.f};
+      for (int form = 0; form < 2 && rc == CPRUNE_OK && e == hipSuccess; ++form) {   // 0: two kernels, 1: fused
+        D.fused_away = form == 1;
+        P.fuse_dw = form == 1 ? i : -1;
+        for (int pass = 0; pass < 3 && rc == CPRUNE_OK && e == hipSuccess; ++pass) {   // first pass untimed
+          e = hipEventRecord(e0, s);
+          for (int it = 0; it < 6 && rc == CPRUNE_OK; ++it) {
+            rc = net_run_layer(net, i, max_batch, nullptr, nullptr, s);
+            if (rc == CPRUNE_OK) rc = net_run_layer(net, reader, max_batch, nullptr, nullptr, s);
+          }
+          if (e == hipSuccess) e = hipEventRecord(e1, s);
+          if (e == hipSuccess) e = hipEventSynchronize(e1);
+          float t = 0.f;
+          if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+          if (pass == 1 || (pass == 2 && t < ms[form])) ms[form] = t;
+        }
+      }
+      if (e0) hipEventDestroy(e0);
+      if (e1) hipEventDestroy(e1);
+      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
+      fuse = ms[1] < ms[0];
+    }
+    D.fused_away = fuse;
+    P.fuse_dw = fuse ? i : -1;
+    if (fuse) P.variant = -1;
+  }
   if (rc == CPRUNE_OK) {
     hipError_t e = hipStreamSynchronize(s);
     if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
@@ -688,7 +774,7 @@ extern "C" int cprune_net_layer_times(cprune_net* net, const void* x, int n, int
   for (int i = 0; i < nl && rc == CPRUNE_OK; ++i) {
     ms_out[i] = 0.0f;
     rc = net_run_layer(net, i, n, x, nullptr, s);   // untimed first run
-    if (rc != CPRUNE_OK || net->layers[i].alias) continue;
+    if (rc != CPRUNE_OK || net->layers[i].alias || net->layers[i].fused_away) continue;
     hipError_t e = hipEventRecord(e0, s);
     for (int it = 0; it < iters && rc == CPRUNE_OK && e == hipSuccess; ++it) rc = net_run_layer(net, i, n, x, nullptr, s);
     if (e == hipSuccess) e = hipEventRecord(e1, s);
@@ -709,6 +795,7 @@ extern "C" int cprune_net_copy_activation(cprune_net* net, int layer, int n, voi
   if (n < 1 || n > net->max_batch) return CPRUNE_ERR_INVALID_ARG;
   const NetLayer& L = net->layers[layer];
   if (L.fused_pool) return CPRUNE_ERR_UNSUPPORTED;  // only the pooled map exists: ask for the pool layer
+  if (L.fused_away) return CPRUNE_ERR_UNSUPPORTED;  // computed inside its consumer's kernel, never stored
   const size_t bytes = (size_t)L.d.c_out * L.h_out * L.w_out * n * dtype_size(net->dtype);
   if (dst_bytes < bytes) return CPRUNE_ERR_INVALID_ARG;
   return launch_nhwc_to_nchw(L.act, n, L.d.c_out, L.h_out * L.w_out, L.cp_out, net->dtype, dst, (hipStream_t)stream);
@@ -732,7 +819,7 @@ extern "C" int cprune_net_task_table(const cprune_net* net, int* task_of_layer, 
   std::map<DescKey, int> ids;
   for (size_t i = 0; i < net->layers.size(); ++i) {
     const NetLayer& L = net->layers[i];
-    if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) { task_of_layer[i] = -1; continue; }
+    if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1)) || L.fuse_dw >= 0) { task_of_layer[i] = -1; continue; }
     const DescKey key = key_of(layer_conv_desc(*net, L, net->max_batch), layer_layout(L));
     auto it = ids.find(key);
     if (it == ids.end()) it = ids.emplace(key, (int)ids.size()).first;
@@ -742,10 +829,35 @@ extern "C" int cprune_net_task_table(const cprune_net* net, int* task_of_layer, 
   return CPRUNE_OK;
 }
 
+extern "C" int cprune_net_fuse_depthwise(cprune_net* net, int layer, int enable) {
+  if (!net || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
+  NetLayer& D = net->layers[layer];
+  if (D.dw_reader < 0) return CPRUNE_ERR_UNSUPPORTED;
+  CPRUNE_HIP_TRY(hipDeviceSynchronize());
+  for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
+  net->graphs.clear();
+  NetLayer& P = net->layers[D.dw_reader];
+  D.fused_away = enable != 0;
+  P.fuse_dw = enable ? layer : -1;
+  if (enable) {
+    P.variant = -1;
+  } else if (P.variant < 0) {
+    P.variant = cached_or_heuristic_variant(layer_conv_desc(*net, P, net->max_batch), nullptr, layer_layout(P));
+  }
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_net_layer_fused(const cprune_net* net, int layer, int* fused_out) {
+  if (!net || !fused_out || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
+  *fused_out = net->layers[layer].fused_away ? 1 : 0;
+  return CPRUNE_OK;
+}
+
 extern "C" int cprune_net_set_layer_variant(cprune_net* net, int layer, int variant) {
   if (!net || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
   NetLayer& L = net->layers[layer];
   if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) return CPRUNE_ERR_INVALID_ARG;
+  if (L.fuse_dw >= 0) return CPRUNE_ERR_INVALID_ARG;   // runs the fused depthwise + 1x1 kernel: no variants
   const cprune_conv_desc cd = layer_conv_desc(*net, L, net->max_batch);
   const ConvLayout lay = layer_layout(L);
   if (!variant_supports(cd, variant, lay)) return CPRUNE_ERR_UNSUPPORTED;

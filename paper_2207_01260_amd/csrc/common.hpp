@@ -95,4 +95,26 @@ int launch_repack_weights(const void* w, int o, int c, int khw, int cp, int dt, 
 int launch_repack_map2x2(const void* w, const float* bias, int o, int c, int cp_in, int cp_out,
                          int rows_by_channel, int dt, void* w_out, float* bias_out, hipStream_t s);
 
+// Fused depthwise k x k (+ bias + activation) and the 1x1 convolution behind it, channels-last.
+struct DwProjArgs {
+  const void* x;        // [n][h][w][cpe], expanded activations
+  const void* wdw;      // [k][k][cpe] depthwise weights (folded)
+  const float* bdw;     // [ce] depthwise bias or null
+  const void* wp;       // [o][cpe] projection weights (folded)
+  const float* bp;      // [o] projection bias or null
+  const void* res;      // [n][ho][wo][cop] or null
+  void* y;              // [n][ho][wo][cop]
+  int N, H, W, Ho, Wo, Ce, Cpe, O, Cop;
+  int pad, act_dw, act_out;
+  int tiles_y, tiles_x, tiles_m;
+  unsigned x_bytes, wp_bytes, wdw_bytes;
+  int vec_out;
+};
+
+// k in {3, 5}, stride in {1, 2}, mb in {2, 4, 8} (16-filter blocks per tile); grid = one work-group
+// per (image, 8x8 output block, filter tile).  CPRUNE_ERR_UNSUPPORTED for other combinations.
+int launch_dwproj_f32(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a);
+int launch_dwproj_f16(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a);
+int launch_dwproj_bf16(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a);
+
 }  // namespace cprune

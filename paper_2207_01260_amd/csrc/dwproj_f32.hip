@@ -1,0 +1,10 @@
+// Instantiations of the fused depthwise + 1x1 projection kernel for float data.
+#include "dwproj_kernel.hpp"
+
+namespace cprune {
+
+int launch_dwproj_f32(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a) {
+  return launch_dwproj<float>(k, stride, mb, grid, s, a);
+}
+
+}  // namespace cprune

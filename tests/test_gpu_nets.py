@@ -46,8 +46,11 @@ def _run(orc, net, cid, batch, dtype, tune, check_layers=True, use_graph=False):
         for i, r in enumerate(ref_acts[:-1]):
             try:
                 a = handle.activation(i, batch, r.shape[1:]).float().cpu().numpy()
-            except B.CPruneError as e:     # conv whose max-pool runs in its epilogue: checked at the pool
-                assert e.status == B.ERR_UNSUPPORTED and net.layers[i + 1].kind == "maxpool"
+            except B.CPruneError as e:
+                # a conv whose max-pool runs in its epilogue is checked at the pool, a depthwise
+                # conv computed inside its 1x1 consumer's kernel at that consumer
+                assert e.status == B.ERR_UNSUPPORTED
+                assert net.layers[i + 1].kind == "maxpool" or net.layers[i].groups != 1
                 continue
             e = nmax(a, r)
             assert e < tol, (net.layers[i].name, e)
@@ -248,3 +251,49 @@ def test_channels_last_layer_every_variant(orc, cfg):
         assert err < TOL[dtype], (v, B.cprune_tile_variant_name(v, True, dtype), err)
     handle.close()
     assert ran >= 100 or (k == 3 and stride == 1 and ran >= 110)
+
+
+@pytest.mark.parametrize("which,dtype", [("mobilenetv2", B.F32), ("mnasnet", B.F32), ("mobilenetv2", B.F16),
+                                         ("mnasnet", B.F16)])
+def test_depthwise_fused_into_projection(orc, which, dtype):
+    """Every depthwise + 1x1 pair of the net forced into the fused kernel (3x3 and 5x5 windows,
+    stride 1 and 2, shortcut adds, ragged pruned channel counts), then forced apart again:
+    logits and every stored activation within the bar both ways."""
+    net = synth.mobilenetv2(100, 64) if which == "mobilenetv2" else synth.mnasnet(100, 64)
+    cid = 4 if which == "mobilenetv2" else 6
+    handle, xd, logits, ref = _run(orc, net, cid, 3, dtype, tune=False, check_layers=False)
+    pairs = [i for i, L in enumerate(net.layers) if L.kind == "conv" and L.groups != 1]
+    fused = 0
+    for i in pairs:
+        try:
+            handle.fuse_depthwise(i, True)
+        except B.CPruneError as e:
+            assert e.status == B.ERR_UNSUPPORTED and net.layers[i + 1].k != 1
+            continue
+        assert handle.layer_fused(i)
+        fused += 1
+    assert fused >= 16
+    params = synth.layer_params(net, cid)
+    x = synth.net_input(net, cid, 3)
+    ref_layers, _ = orc.prune_net(net, params)
+    ref_acts = orc.forward(net, ref_layers, x, return_all=True)
+    for graph in (False, True):
+        out = handle.forward(xd, use_graph=graph)
+        torch.cuda.synchronize()
+        assert nmax(out.float().cpu().numpy(), ref) < TOL[dtype]
+    for i, r in enumerate(ref_acts[:-1]):
+        if net.layers[i].kind == "conv" and net.layers[i].groups != 1:
+            with pytest.raises(B.CPruneError):
+                handle.activation(i, 3, r.shape[1:])
+            continue
+        if dtype != B.F32:       # 16-bit: rounding accumulates over ~50 layers; the logits carry the bar
+            continue
+        a = handle.activation(i, 3, r.shape[1:]).float().cpu().numpy()
+        assert nmax(a, r) < TOL[dtype], net.layers[i].name
+    for i in pairs:
+        handle.fuse_depthwise(i, False)
+        assert not handle.layer_fused(i)
+    out = handle.forward(xd)
+    torch.cuda.synchronize()
+    assert nmax(out.float().cpu().numpy(), ref) < TOL[dtype]
+    handle.close()
