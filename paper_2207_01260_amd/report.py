@@ -58,7 +58,8 @@ def net_report(name, net, cid, batch, dtype, steps):
             kind, fl = "dense_conv", 2.0 * batch * cout * cin * L.k * L.k * ho * wo
             by = moved + es * cout * cin * L.k * L.k
         elif L.kind == "conv":
-            kind, fl, by = "depthwise", 2.0 * batch * cout * L.k * L.k * ho * wo, moved
+            # 0 time: the layer runs inside the kernel of the 1x1 conv that reads it
+            kind, fl, by = "depthwise", 2.0 * batch * cout * L.k * L.k * ho * wo, (moved if t > 0 else 0.0)
         elif L.kind == "fc":
             kind, fl, by = "fc", 2.0 * batch * cin * hin * win * cout, 0.0
         else:
@@ -76,6 +77,9 @@ def net_report(name, net, cid, batch, dtype, steps):
             row.update(gbs=round(gbs, 1), frac_hbm_peak=round(gbs / PEAK_GBS, 4))
         by_kind[kind] = row
     total = pipeline.useful_flops(net, kept_counts, batch)
+    fused = sum(1 for i, L in enumerate(net.layers) if L.kind == "conv" and L.groups != 1 and handle.layer_fused(i))
+    if fused:
+        by_kind["depthwise"]["fused_into_their_1x1_reader"] = fused
     handle.close()
     return {"config": name, "batch": batch, "dtype": DT_NAME[dtype], "images_per_s": round(batch / (ms * 1e-3), 1),
             "ms_per_forward": round(ms, 4), "useful_gflop": round(total / 1e9, 3),
