@@ -154,7 +154,7 @@ int cprune_conv2d_bn_relu(const cprune_conv_desc* desc, const void* x, const voi
                           void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
- * Variant selection by timing on the device (paper Section 3.2, step 2: for each
+ * Variant selection by timing on the device (paper Section 3.2, Fig. 3: for each
  * task the compiler generates candidate programs and keeps the one that runs
  * fastest on the target; layers of equal shape share a task).  Times every
  * variant that supports desc with `warmup` untimed and `iters` timed launches on
@@ -189,7 +189,7 @@ int cprune_fc(const void* x, const void* w, const float* bias, int n, int f, int
               void* stream);
 
 /* ------------------------------------------------------------------------
- * Whole-network inference (paper Algorithm 1, step 9: run the aggregate of the
+ * Whole-network inference (paper Algorithm 1: run the aggregate of the
  * tuned tasks on the device and measure its latency).
  */
 typedef enum {

@@ -1,5 +1,5 @@
 // Channels-last twin of the implicit-GEMM convolution kernel, used inside the
-// network handle (Algorithm 1, step 9 of the paper: the pruned model run on the
+// network handle (Algorithm 1 of the paper: the pruned model run on the
 // device).  Same tiling, MFMA blocks, slab pipeline, equal-run scheduling and
 // fix-up as conv_igemm_kernel; what changes is how operands reach LDS.
 //

@@ -1,7 +1,7 @@
 """Host-side drivers built on the C-ABI calls: prune a whole network on the
 device (rank -> gather -> fold, Section 3.5 of the paper) and wrap the result in
-an inference handle (Algorithm 1, step 9).  Only sequencing lives here; every
-tensor operation is a library call.
+an inference handle (Algorithm 1: the candidate model is run on the device and
+timed).  Only sequencing lives here; every tensor operation is a library call.
 """
 
 from __future__ import annotations
