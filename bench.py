@@ -228,6 +228,16 @@ def main():
                                "kind": "oracle",
                                "sample": f"{n_img} images of the same pruned VGG-16, fp64-accumulate "
                                          f"direct loops, OpenMP over (image, filter), {dt_cpu:.1f} s"}
+        # the same loops on one thread, on a smaller sample
+        n1 = max(4, min(64, int(3.0 * n_img / dt_cpu / max(threads, 1))))
+        oracle.set_threads(1)
+        x1 = synth.net_input(net, cid, n1)
+        t0 = time.perf_counter()
+        oracle.forward(net, ref_layers, x1)
+        dt1 = time.perf_counter() - t0
+        oracle.set_threads(threads)
+        out["cpu_baseline"]["single_thread"] = {"value": round(n1 / dt1, 2), "unit": "images/s",
+                                                "sample": f"{n1} images, {dt1:.1f} s"}
     print(json.dumps(out))
 
 

@@ -5,7 +5,8 @@ the device.  One JSON object per line.
 
     python -m paper_2207_01260_amd.report [--quick]
 
-For each network and batch: images/s and ms per forward (HIP graph replay or eager launches,
+For each network and batch: images/s and ms per forward (at batch 1 also with the caches scrubbed
+before every run: back-to-back replays keep the weights in the last-level cache) (HIP graph replay or eager launches,
 whichever is faster), useful TFLOP/s on the pruned channel counts, and the device time by
 layer kind (dense conv / depthwise / pool / fc) with what bounds it: dense layers against the
 MFMA peak of the dtype, depthwise and pools against HBM bandwidth by the bytes they must move
@@ -38,6 +39,24 @@ def time_forward(handle, x, steps, graph):
     return (time.perf_counter() - t0) / steps * 1e3
 
 
+def time_forward_cold(handle, x, steps):
+    """ms per forward with the caches scrubbed before every run (a 1 GiB fill between runs: the
+    last-level cache is 256 MiB), timed by events around the forward alone."""
+    out = handle.forward(x)
+    scrub = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    total = 0.0
+    for i in range(steps):
+        scrub.fill_(float(i))
+        e0.record()
+        handle.forward(x, out)
+        e1.record()
+        e1.synchronize()
+        total += e0.elapsed_time(e1)
+    del scrub
+    return total / steps
+
+
 def net_report(name, net, cid, batch, dtype, steps):
     params = synth.layer_params(net, cid)
     dparams = pipeline.upload_params(params)
@@ -46,6 +65,7 @@ def net_report(name, net, cid, batch, dtype, steps):
     handle = pipeline.build_net(net, layers, batch, dtype, tune=True)
     x = torch.from_numpy(synth.net_input(net, cid, batch)).cuda().to(B.TORCH_DTYPE[dtype])
     ms = min(time_forward(handle, x, steps, g) for g in (False, True))
+    ms_cold = time_forward_cold(handle, x, min(steps, 20)) if batch == 1 else None
     lt = handle.layer_times(x, iters=10)
     shp = synth.shapes(net, kept_counts)
     es = 4 if dtype == B.F32 else 2
@@ -82,7 +102,9 @@ def net_report(name, net, cid, batch, dtype, steps):
         by_kind["depthwise"]["fused_into_their_1x1_reader"] = fused
     handle.close()
     return {"config": name, "batch": batch, "dtype": DT_NAME[dtype], "images_per_s": round(batch / (ms * 1e-3), 1),
-            "ms_per_forward": round(ms, 4), "useful_gflop": round(total / 1e9, 3),
+            "ms_per_forward": round(ms, 4),
+            **({"ms_per_forward_cold_caches": round(ms_cold, 4)} if ms_cold is not None else {}),
+            "useful_gflop": round(total / 1e9, 3),
             "useful_tflops": round(total / (ms * 1e-3) / 1e12, 2), "by_layer_kind": by_kind}
 
 
