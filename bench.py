@@ -115,7 +115,8 @@ def main():
     if pinned:
         assert len(pinned) == len(dense), "--variants needs one entry per conv / fc layer"
         for i, v in zip(dense, pinned):
-            handle.set_layer_variant(i, v)
+            if v >= 0:                           # -1: a layer without tile variants (first-layer kernel)
+                handle.set_layer_variant(i, v)
     variants = [handle.layer_variant(i) for i in dense]
     kept_counts = {i: int(k.numel()) for i, k in kept.items()}
     x = torch.from_numpy(synth.net_input(net, cid, args.batch)).cuda().to(B.TORCH_DTYPE[dt])
@@ -142,9 +143,14 @@ def main():
         cin, cout, ho, wo = shp[i]
         fl = 2.0 * args.batch * cout * cin * 9 * ho * wo
         v = handle.layer_variant(i)
-        tm, tp, sk = B.cprune_tile_variant_info(v)
         first = L.input < 0 and cin <= 4         # reads the NCHW input itself
-        kern = B.cprune_tile_variant_name(v, channels_last=not first, dtype=dt)
+        if v < 0:                                # the first-layer kernel: no tile variants
+            tm, tp, sk = 16 * (2 if cout <= 32 else 4), 128, 0
+            kern = "conv_stem_kernel<%s, %d, %d, %d>" % ({"f32": "float", "f16": "_Float16", "bf16": "__bf16"}[args.dtype],
+                                                          L.k, L.stride, tm // 16)
+        else:
+            tm, tp, sk = B.cprune_tile_variant_info(v)
+            kern = B.cprune_tile_variant_name(v, channels_last=not first, dtype=dt)
         note = (" + fix-up" if sk > 0 else "") + (" (2x2 map as one matrix)" if (ho == 2 and sk >= 0) else "")
         g = by_kernel.setdefault(kern, [0, 0.0, 0.0])
         g[0] += 1; g[1] += m; g[2] += fl

@@ -294,8 +294,10 @@ int cprune_order_tasks(const double* exec_time, const int* n_subgraphs, int n_ta
                        double* impact_out);
 /* Section 3.4.  Groups the handle's dense conv / fully connected layers into tasks: layers
  * with the same shape, stride, padding, activation, shortcut and layout are one task, numbered
- * in order of first appearance.  task_of_layer: host [n_layers], -1 for layers that have no
- * variants (pools, depthwise); n_tasks_out: host. */
+ * in order of first appearance.  task_of_layer: host [n_layers], -1 for pools and depthwise
+ * layers; n_tasks_out: host.  A task's layer may run a kernel without tile variants (the
+ * first-layer kernel, the fused depthwise + 1x1 kernel: cprune_net_layer_variant gives -1);
+ * those are built on 16-filter blocks. */
 int cprune_net_task_table(const cprune_net* net, int* task_of_layer, int* n_tasks_out);
 
 /* ---- measured ceilings (for reporting kernel throughput against what the device

@@ -341,6 +341,9 @@ struct NetLayer {
   int fuse_dw = -1;           // 1x1 conv: index of the depthwise layer computed inside its kernel, or -1
   bool fused_away = false;    // depthwise conv that runs inside its consumer's kernel (no launch, no activation)
   int dw_reader = -1;         // depthwise conv that may run inside the 1x1 conv dw_reader's kernel
+  void* w_stem = nullptr;     // weights packed for the first-layer kernel
+  bool stem = false;          // nchw_in layer that runs the first-layer kernel (whole reduction in LDS)
+  int stem_ok = 0;            // that kernel exists for the layer's window and stride
   bool nchw_in = false;       // dense conv on the network input: reads the caller's NCHW tensor and its own
                               // OIHW weights, writes channels-last (no layout conversion pass)
 };
@@ -406,6 +409,36 @@ static void net_free(cprune_net* net) {
   delete net;
 }
 
+// The first-layer kernel on the caller's NCHW input.
+static int net_run_stem(cprune_net* net, int i, int n, const void* x, void* dst, hipStream_t s) {
+  const NetLayer& L = net->layers[i];
+  StemArgs a;
+  a.x = x; a.w = L.w_stem; a.bias = L.b; a.y = dst;
+  a.N = n; a.C = L.d.c_in; a.H = L.h_in; a.W = L.w_in; a.Ho = L.h_out; a.Wo = L.w_out;
+  a.O = L.d.c_out; a.Cop = L.cp_out; a.pad = L.d.pad; a.act = L.d.act;
+  const int mb = L.d.c_out <= 32 ? 2 : 4;
+  a.tiles_y = (a.Ho + 7) / 8; a.tiles_x = (a.Wo + 15) / 16; a.tiles_m = (a.O + mb * 16 - 1) / (mb * 16);
+  a.vec_out = (a.Cop % 4) == 0 ? 1 : 0;
+  const long ptiles = (long)n * a.tiles_y * a.tiles_x;
+  // as many workers as stay resident: LDS per work-group = weight tile + patch + offset table
+  const int es = (int)dtype_size(net->dtype), kp = stem_packed_k(L.d.k, net->dtype);
+  const int ph = 7 * L.d.stride + L.d.k, pwp = (15 * L.d.stride + L.d.k + 3) / 4 * 4;
+  const long lds = (long)mb * 16 * (kp * es + 16) + 3L * ph * pwp * es + kp * 4;
+  long per_cu = (160 * 1024) / lds;
+  per_cu = per_cu > 8 ? 8 : (per_cu < 1 ? 1 : per_cu);
+  // a small weight tile costs little to stage: then one pixel block per work-group keeps more of them in flight
+  const bool light = (long)mb * 16 * (kp * es + 16) < 8192;
+  const long workers = (light || ptiles < 256 * per_cu) ? ptiles : 256 * per_cu;
+  dim3 grid((unsigned)workers, (unsigned)a.tiles_m);
+  int rc;
+  if (net->dtype == CPRUNE_F32) rc = launch_conv_stem_f32(L.d.k, L.d.stride, mb, grid, s, a);
+  else if (net->dtype == CPRUNE_F16) rc = launch_conv_stem_f16(L.d.k, L.d.stride, mb, grid, s, a);
+  else rc = launch_conv_stem_bf16(L.d.k, L.d.stride, mb, grid, s, a);
+  if (rc != CPRUNE_OK) return rc;
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
 // Depthwise layer P.fuse_dw and the 1x1 layer i in one kernel: reads the depthwise layer's input.
 static int net_run_dwproj(cprune_net* net, int i, int n, void* dst, hipStream_t s) {
   const NetLayer& P = net->layers[i];
@@ -441,6 +474,7 @@ static int net_run_layer(cprune_net* net, int i, int n, const void* x, void* out
   void* dst = out_override ? out_override : L.act;
   if (L.fused_away) return CPRUNE_OK;
   if (L.fuse_dw >= 0) return net_run_dwproj(net, i, n, dst, s);
+  if (L.stem) return net_run_stem(net, i, n, src, dst, s);
   switch (L.d.kind) {
     case CPRUNE_LAYER_CONV:
     case CPRUNE_LAYER_FC: {
@@ -667,6 +701,50 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     }
     L.variant = v;
   }
+  // A first layer with an image-like input (<= 3 channels; 3x3 or 7x7 window) has a kernel of its
+  // own that keeps the whole reduction in LDS; with tune != 0 it is timed against the chosen variant
+  // of the general kernel, otherwise it is taken.
+  for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
+    NetLayer& L = net->layers[i];
+    const cprune_layer_desc& d = L.d;
+    if (!L.nchw_in || d.c_in > 3 || d.pad != d.k / 2) continue;
+    if (!((d.k == 3 && (d.stride == 1 || d.stride == 2)) || (d.k == 7 && d.stride == 2))) continue;
+    L.stem_ok = 1;
+    {
+      const int mb = d.c_out <= 32 ? 2 : 4;
+      const int rows = (d.c_out + mb * 16 - 1) / (mb * 16) * (mb * 16);
+      const int kp = stem_packed_k(d.k, dtype);
+      rc = dev_alloc((size_t)rows * kp * es, &L.w_stem);
+      if (rc == CPRUNE_OK) rc = launch_repack_stem(L.w, d.c_out, d.c_in * d.k * d.k, rows, kp, dtype, L.w_stem, s);
+      if (rc != CPRUNE_OK) break;
+    }
+    bool use = true;
+    if (tune) {
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      hipError_t e = hipEventCreate(&e0);
+      if (e == hipSuccess) e = hipEventCreate(&e1);
+      float ms[2] = {0.f, 0.f};
+      for (int form = 0; form < 2 && rc == CPRUNE_OK && e == hipSuccess; ++form) {   // 0: general kernel, 1: first-layer kernel
+        L.stem = form == 1;
+        for (int pass = 0; pass < 3 && rc == CPRUNE_OK && e == hipSuccess; ++pass) {   // first pass untimed
+          e = hipEventRecord(e0, s);
+          for (int it = 0; it < 6 && rc == CPRUNE_OK; ++it) rc = net_run_layer(net, i, max_batch, net->x_cl, nullptr, s);
+          if (e == hipSuccess) e = hipEventRecord(e1, s);
+          if (e == hipSuccess) e = hipEventSynchronize(e1);
+          float t = 0.f;
+          if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+          if (pass == 1 || (pass == 2 && t < ms[form])) ms[form] = t;
+        }
+      }
+      if (e0) hipEventDestroy(e0);
+      if (e1) hipEventDestroy(e1);
+      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
+      use = ms[1] < ms[0];
+    }
+    L.stem = use;
+    if (use) L.variant = -1;
+  }
+
   // A depthwise conv whose only reader is a 1x1 conv can run inside that conv's kernel: the
   // expanded activations are then read once and never written.  It pays on large maps (enough
   // 8x8 pixel blocks to fill the chip); with tune != 0 both forms are timed and the faster kept.
@@ -819,7 +897,7 @@ extern "C" int cprune_net_task_table(const cprune_net* net, int* task_of_layer, 
   std::map<DescKey, int> ids;
   for (size_t i = 0; i < net->layers.size(); ++i) {
     const NetLayer& L = net->layers[i];
-    if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1)) || L.fuse_dw >= 0) { task_of_layer[i] = -1; continue; }
+    if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) { task_of_layer[i] = -1; continue; }
     const DescKey key = key_of(layer_conv_desc(*net, L, net->max_batch), layer_layout(L));
     auto it = ids.find(key);
     if (it == ids.end()) it = ids.emplace(key, (int)ids.size()).first;
@@ -858,6 +936,7 @@ extern "C" int cprune_net_set_layer_variant(cprune_net* net, int layer, int vari
   NetLayer& L = net->layers[layer];
   if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) return CPRUNE_ERR_INVALID_ARG;
   if (L.fuse_dw >= 0) return CPRUNE_ERR_INVALID_ARG;   // runs the fused depthwise + 1x1 kernel: no variants
+  if (L.stem) L.stem = false;                          // a pinned variant means the general kernel
   const cprune_conv_desc cd = layer_conv_desc(*net, L, net->max_batch);
   const ConvLayout lay = layer_layout(L);
   if (!variant_supports(cd, variant, lay)) return CPRUNE_ERR_UNSUPPORTED;

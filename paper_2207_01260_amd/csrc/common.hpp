@@ -117,4 +117,25 @@ int launch_dwproj_f32(int k, int stride, int mb, dim3 grid, hipStream_t s, const
 int launch_dwproj_f16(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a);
 int launch_dwproj_bf16(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a);
 
+// First-layer convolution: NCHW input with at most 3 channels, OIHW weights, channels-last output.
+struct StemArgs {
+  const void* x;        // [n][c][h][w]
+  const void* w;        // [tiles_m * 16 * mb][kp] packed by launch_repack_stem: k = (c, u, v) padded with
+                        // zeros to kp, rows beyond o zero
+  const float* bias;    // [o] or null
+  void* y;              // [n][ho][wo][cop]
+  int N, C, H, W, Ho, Wo, O, Cop;
+  int pad, act;
+  int tiles_y, tiles_x, tiles_m;
+  int vec_out;
+};
+// (k, stride) in {(3, 1), (3, 2), (7, 2)}, mb in {2, 4} (16-filter blocks per tile); grid.x = workers
+// that share the (image, 8x16 output block) list round-robin, grid.y = filter tiles.
+// CPRUNE_ERR_UNSUPPORTED for other windows.  stem_packed_k: padded row length in elements.
+int stem_packed_k(int k, int dt);
+int launch_repack_stem(const void* w, int o, int ktot, int rows, int kp, int dt, void* y, hipStream_t s);
+int launch_conv_stem_f32(int k, int stride, int mb, dim3 grid, hipStream_t s, const StemArgs& a);
+int launch_conv_stem_f16(int k, int stride, int mb, dim3 grid, hipStream_t s, const StemArgs& a);
+int launch_conv_stem_bf16(int k, int stride, int mb, dim3 grid, hipStream_t s, const StemArgs& a);
+
 }  // namespace cprune

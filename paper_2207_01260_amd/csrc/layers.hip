@@ -381,6 +381,19 @@ __global__ __launch_bounds__(256) void repack_map2x2_kernel(const T* __restrict_
   if (col == 0) bias_out[row] = (bias && o < o_count) ? bias[o] : 0.0f;
 }
 
+// [o][ktot] -> [rows][kp], zero beyond ktot and beyond the last filter
+template <typename T>
+__global__ __launch_bounds__(256) void repack_stem_kernel(const T* __restrict__ w, T* __restrict__ y, long total,
+                                                          int o_count, int ktot, int kp) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int k = (int)(i % kp);
+  const long o = i / kp;
+  T v = (T)0.0f;
+  if (o < o_count && k < ktot) v = w[o * ktot + k];
+  y[i] = v;
+}
+
 inline dim3 blocks_for(long total) { return dim3((unsigned)((total + 255) / 256)); }
 
 int plane_slices(int total) {
@@ -562,6 +575,19 @@ int launch_repack_weights(const void* w, int o, int c, int khw, int cp, int dt, 
   const long total = (long)o * khw * cp;
   CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_weights_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w,
                                          (T*)y, total, c, khw, cp));
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+int stem_packed_k(int k, int dt) {
+  const int rk = dt == CPRUNE_F32 ? 16 : 32;   // k per 64-byte MFMA round
+  return (3 * k * k + rk - 1) / rk * rk;
+}
+
+int launch_repack_stem(const void* w, int o, int ktot, int rows, int kp, int dt, void* y, hipStream_t s) {
+  const long total = (long)rows * kp;
+  CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_stem_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w, (T*)y,
+                                         total, o, ktot, kp));
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }

@@ -127,8 +127,10 @@ class DeviceSearch:
         table = {}
         for t, m in enumerate(members):
             v = handle.layer_variant(m[0])
+            # kernels without tile variants (first layer, fused depthwise + 1x1) work on 16-filter blocks
+            step = B.cprune_variant_prune_step(v, shp[m[0]][1]) if v >= 0 else 16
             table[keys[t]] = (m, {"variant": v, "c_out": shp[m[0]][1], "time_ms": times[t], "impact": impact[t],
-                                  "step": B.cprune_variant_prune_step(v, shp[m[0]][1])})
+                                  "step": step})
         handle.close()
         st = {"table": table, "order": [keys[t] for t in order], "ms": ms}
         self._cache[key] = st
