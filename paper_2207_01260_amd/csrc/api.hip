@@ -215,6 +215,8 @@ extern "C" int cprune_tile_variant_name(int v, int channels_last, cprune_dtype d
   if (tv.sched >= 0)
     n = snprintf(buf, buf_bytes, "%s<%s, %d, %d, %d, %d, %d>", channels_last ? "conv_nhwc_kernel" : "conv_igemm_kernel", t,
                  tv.wm, tv.wn, tv.mb, tv.nb, tv.kq);
+  else if (tv.sched == -2)
+    n = snprintf(buf, buf_bytes, "conv_ksplit_kernel<%s, %d, %d>", t, tv.nb, tv.kwaves);
   else if (tv.blk32)
     n = snprintf(buf, buf_bytes, "conv_patch32_kernel<%s, %d, %d, %d, %d, %d, %d, %d>", t, tv.mb / 2, tv.nb / 2, tv.wn, tv.th,
                  tv.tw, tv.ni, tv.kq);

@@ -1,5 +1,6 @@
 // Host side of the dense convolution: the variant table (tile x scheduling
 // mode), what each variant supports and needs, and the launch.
+#include "conv_ksplit_kernel.hpp"
 #include "conv_patch32_kernel.hpp"
 
 namespace cprune {
@@ -16,6 +17,7 @@ static_assert(sizeof(kTiles) / sizeof(kTiles[0]) == kNumTiles, "tile table");
 const int kScheds[] = {0, 1, 2, 3, 4, 6, 8};
 constexpr int kNumScheds = sizeof(kScheds) / sizeof(kScheds[0]);
 constexpr int kMinUnitsPerGroup = 4;
+constexpr long kMaxKsplitGroups = 8192;
 
 unsigned magic_for(unsigned d) {
   if (d <= 1) return 0;
@@ -58,11 +60,11 @@ Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv, const ConvLayou
 
 }  // namespace
 
-int num_variants() { return kNumTiles * kNumScheds + kNumPatch + kNumPatch32; }
+int num_variants() { return kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit; }
 
 namespace {
 struct VariantTable {
-  TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32];
+  TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit];
   VariantTable() {
 #define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_, KQ_, KS_)                                 \
     {                                                                         \
@@ -80,6 +82,14 @@ struct VariantTable {
     }
     CPRUNE_PATCH32_LIST(CPRUNE_PATCH32_ROW)
 #undef CPRUNE_PATCH32_ROW
+#define CPRUNE_KSPLIT_ROW(ID, NB_, KW_)                                                    \
+    {                                                                                      \
+      TileVariant& kv = table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + ID];      \
+      kv.wm = 1; kv.wn = 1; kv.mb = 1; kv.nb = NB_; kv.kq = 1; kv.sched = -2;              \
+      kv.patch_id = ID; kv.kwaves = KW_;                                                   \
+    }
+    CPRUNE_KSPLIT_LIST(CPRUNE_KSPLIT_ROW)
+#undef CPRUNE_KSPLIT_ROW
     for (int t = 0; t < kNumTiles; ++t)
       for (int s = 0; s < kNumScheds; ++s) {
         table[t * kNumScheds + s] = kTiles[t];
@@ -98,6 +108,17 @@ bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
   if (v < 0 || v >= num_variants()) return false;
   if (d.groups != 1) return false;
   const TileVariant& tv = variant(v);
+  if (tv.sched == -2) {
+    // the reduction of a pixel is one contiguous run: 1x1 / stride 1, or a window that covers the whole map
+    const bool pointwise = d.kh == 1 && d.kw == 1 && d.stride == 1 && d.pad == 0;
+    const bool whole_map = d.pad == 0 && d.kh == d.h && d.kw == d.w;
+    if (!lay.nhwc || !(pointwise || whole_map)) return false;
+    if (lay.pool == 1 || (lay.pool == 2 && (d.c_out & 3))) return false;
+    // made for few pixels: with many, the tiled kernels reuse their operands and this one does not
+    const long P = (long)d.n * conv_out_dim(d.h, d.kh, d.stride, d.pad) * conv_out_dim(d.w, d.kw, d.stride, d.pad);
+    const long groups = ((d.c_out + 15) / 16) * ((P + tv.tile_p() - 1) / tv.tile_p());
+    return groups <= kMaxKsplitGroups;
+  }
   if (tv.sched < 0) {
     if (!(lay.nhwc && d.kh == 3 && d.kw == 3 && d.stride == 1 && d.pad == 1)) return false;
     if (lay.pool == 2 || (lay.pool && ((d.h | d.w) & 1))) return false;
@@ -138,6 +159,32 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
                       const void* residual, void* y, int v, void* ws, hipStream_t s, const ConvLayout& lay) {
   const TileVariant& tv = variant(v);
   const size_t es = dtype_size(d.dtype);
+  if (tv.sched == -2) {
+    ConvArgs a;
+    a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.partial = nullptr;
+    a.N = d.n; a.C = d.c_in; a.H = d.h; a.W = d.w; a.O = d.c_out; a.KH = d.kh; a.KW = d.kw;
+    a.stride = d.stride; a.pad = d.pad;
+    a.Ho = conv_out_dim(d.h, d.kh, d.stride, d.pad);
+    a.Wo = conv_out_dim(d.w, d.kw, d.stride, d.pad);
+    a.K = lay.cp_in * d.kh * d.kw;
+    a.Cp = lay.cp_in; a.Cop = lay.cp_out;
+    a.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
+    a.pool4 = lay.pool == 2 ? 1 : 0;
+    a.nhwc_out = 0;
+    a.HoWo = a.Ho * a.Wo;
+    a.P = d.n * a.HoWo;
+    a.x_bytes = (unsigned)((size_t)d.n * lay.cp_in * d.h * d.w * es);
+    a.w_bytes = (unsigned)((size_t)d.c_out * a.K * es);
+    a.act = d.act;
+    a.tiles_m = (d.c_out + 15) / 16;
+    a.tiles_p = (a.P + tv.tile_p() - 1) / tv.tile_p();
+    dim3 grid((unsigned)(a.tiles_m * a.tiles_p));
+    if (d.dtype == CPRUNE_F32) launch_conv_ksplit_f32(tv.patch_id, grid, s, a);
+    else if (d.dtype == CPRUNE_F16) launch_conv_ksplit_f16(tv.patch_id, grid, s, a);
+    else launch_conv_ksplit_bf16(tv.patch_id, grid, s, a);
+    CPRUNE_LAUNCH_CHECK();
+    return CPRUNE_OK;
+  }
   if (tv.sched < 0) {
     PatchArgs pa;
     pa.x = x; pa.w = w; pa.bias = bias; pa.res = residual; pa.y = y;

@@ -126,7 +126,8 @@ def test_pinned_variants(orc, dtype):
     net = synth.vgg16(10, 32)
     handle, xd, logits, ref = _run(orc, net, 2, 3, dtype, tune=False, check_layers=False, use_graph=True)
     nv = B.cprune_num_tile_variants()
-    layers = [1, 3, 4, 8, 11, 12] if dtype == B.F32 else [4, 12]
+    # 14, 16: 2x2 maps run as one matrix (16 with the pool in its epilogue); 18: the classifier
+    layers = [1, 3, 4, 8, 11, 12, 14, 16, 18] if dtype == B.F32 else [4, 12, 16, 18]
     for layer in layers:
         before = handle.layer_variant(layer)
         pinned = 0
@@ -224,6 +225,8 @@ def _two_layer_net(c0, c1, c2, hw, k, stride, pad, act, residual):
     (6, 12, 18, 11, 5, 1, 2, synth.ACT_RELU, False, 2, B.F32),       # 5x5
     (8, 44, 44, 8, 3, 1, 1, synth.ACT_RELU, True, 5, B.BF16),        # 16-bit, shortcut, 8x8 map
     (8, 30, 50, 4, 3, 1, 1, synth.ACT_RELU, False, 9, B.F16),        # 4x4 map: multi-image tiles
+    (8, 52, 52, 3, 1, 1, 0, synth.ACT_RELU, True, 5, B.BF16),        # 1x1 with shortcut on a 3x3 map, 16-bit
+    (4, 300, 21, 2, 1, 1, 0, synth.ACT_NONE, False, 7, B.F32),       # long reduction, few pixels
 ])
 def test_channels_last_layer_every_variant(orc, cfg):
     c0, c1, c2, hw, k, stride, pad, act, residual, batch, dtype = cfg
