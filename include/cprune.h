@@ -132,6 +132,9 @@ typedef struct {
  * caller's scratch and are summed in run order (deterministic).  sched -1: kernels that
  * exist only for the channels-last layout inside a network handle (3x3 stride-1 layers,
  * one tile_p-pixel spatial block per work-group); unsupported through this NCHW call.
+ * sched -2: likewise channels-last only, for layers whose reduction is one contiguous run
+ * per pixel (1x1 stride 1, fully connected): 16 filters x tile_p pixels per work-group, the
+ * wavefronts of the group splitting the reduction; chosen when pixels are few.
  * Ids are 0..n-1
  * and the same for every shape; a variant that cannot run a given shape is
  * CPRUNE_ERR_UNSUPPORTED. */
@@ -259,6 +262,19 @@ int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out)
  * a forward is in flight.  cprune_net_layer_fused reports the current state (host out). */
 int cprune_net_fuse_depthwise(cprune_net* net, int layer, int enable);
 int cprune_net_layer_fused(const cprune_net* net, int layer, int* fused_out);
+/* When the input of such a depthwise conv is a 1x1 / stride 1 conv that nobody else reads (the
+ * expansion of an inverted-residual block, whose filters are the pruned ones), and the 1x1
+ * reader has at most 128 filters, all three layers can run as one kernel: the expanded
+ * activations, the block's largest tensor, then never reach memory.  cprune_net_create decides
+ * per block (by size, or by timing when tune != 0); this call overrides the decision for the
+ * block whose depthwise layer is `layer`: enable != 0 runs the block as one kernel, 0 leaves
+ * the expansion on its own (the depthwise layer stays inside its reader's kernel).
+ * cprune_net_fuse_depthwise on the same layer also leaves the one-kernel form.
+ * CPRUNE_ERR_UNSUPPORTED when the layer heads no such block or the block's input patch does not
+ * fit the local memory of a compute unit.  Recorded graphs are dropped.  Not to be called while
+ * a forward is in flight.  cprune_net_layer_fused reports 1 for the expansion and the
+ * depthwise layer of a block that runs as one kernel. */
+int cprune_net_fuse_block(cprune_net* net, int layer, int enable);
 /* Pins the tile variant of a dense conv / fully connected layer (what a stored tuning result
  * is applied with).  CPRUNE_ERR_INVALID_ARG for a layer without variants,
  * CPRUNE_ERR_UNSUPPORTED when the variant cannot run that layer's shape.  Recorded graphs

@@ -343,6 +343,9 @@ struct NetLayer {
   int fuse_dw = -1;           // 1x1 conv: index of the depthwise layer computed inside its kernel, or -1
   bool fused_away = false;    // depthwise conv that runs inside its consumer's kernel (no launch, no activation)
   int dw_reader = -1;         // depthwise conv that may run inside the 1x1 conv dw_reader's kernel
+  int fuse_block = -1;        // 1x1 conv with fuse_dw set: index of the 1x1 expansion in front of that depthwise
+                              // layer when the whole block (expansion, depthwise, this projection) is one kernel
+  int block_expand = -1;      // depthwise conv: the expansion layer that may join it and dw_reader in one kernel
   void* w_stem = nullptr;     // weights packed for the first-layer kernel
   bool stem = false;          // nchw_in layer that runs the first-layer kernel (whole reduction in LDS)
   int stem_ok = 0;            // that kernel exists for the layer's window and stride
@@ -470,11 +473,60 @@ static int net_run_dwproj(cprune_net* net, int i, int n, void* dst, hipStream_t 
   return CPRUNE_OK;
 }
 
+// Expansion P.fuse_block, depthwise P.fuse_dw and projection i in one kernel: reads the expansion's input.
+static bool mbconv_fits(const cprune_net& net, const NetLayer& E, const NetLayer& D, const NetLayer& P, int* mb_out,
+                        size_t* lds_out) {
+  const int es = (int)dtype_size(net.dtype);
+  if (P.d.c_out > 128) return false;
+  const int mb = P.d.c_out <= 32 ? 2 : (P.d.c_out <= 64 ? 4 : 8);
+  MbConvArgs probe;
+  const size_t lds = mbconv_lds_layout(D.d.k, D.d.stride, mb, E.cp_in, es, &probe);
+  if (lds > 160 * 1024) return false;
+  if ((64 / es) * probe.xq > 512) return false;   // the expansion-weight chunk is staged by two loads per thread
+  if (mb_out) *mb_out = mb;
+  if (lds_out) *lds_out = lds;
+  return true;
+}
+
+static int net_run_mbconv(cprune_net* net, int i, int n, void* dst, hipStream_t s) {
+  const NetLayer& P = net->layers[i];
+  const NetLayer& D = net->layers[P.fuse_dw];
+  const NetLayer& E = net->layers[P.fuse_block];
+  const size_t es = dtype_size(net->dtype);
+  int mb = 0;
+  size_t lds = 0;
+  if (!mbconv_fits(*net, E, D, P, &mb, &lds)) return CPRUNE_ERR_UNSUPPORTED;
+  MbConvArgs a;
+  mbconv_lds_layout(D.d.k, D.d.stride, mb, E.cp_in, (int)es, &a);
+  a.x = net->layers[E.d.input].act;
+  a.we = E.w; a.be = E.b; a.wdw = D.w; a.bdw = D.b; a.wp = P.w; a.bp = P.b;
+  a.res = P.d.residual >= 0 ? net->layers[P.d.residual].act : nullptr;
+  a.y = dst;
+  a.N = n; a.H = D.h_in; a.W = D.w_in; a.Ho = D.h_out; a.Wo = D.w_out;
+  a.Cpi = E.cp_in; a.Ce = D.d.c_out; a.Cpe = D.cp_in; a.O = P.d.c_out; a.Cop = P.cp_out;
+  a.pad = D.d.pad; a.act_e = E.d.act; a.act_dw = D.d.act; a.act_out = P.d.act;
+  a.tiles_y = (a.Ho + 7) / 8; a.tiles_x = (a.Wo + 7) / 8;
+  a.x_bytes = (unsigned)((size_t)n * a.H * a.W * a.Cpi * es);
+  a.we_bytes = (unsigned)((size_t)a.Ce * a.Cpi * es);
+  a.wp_bytes = (unsigned)((size_t)a.O * a.Cpe * es);
+  a.wdw_bytes = (unsigned)((size_t)D.d.k * D.d.k * a.Cpe * es);
+  a.vec_out = (a.Cop % 4) == 0 ? 1 : 0;
+  dim3 grid((unsigned)(n * a.tiles_y * a.tiles_x));
+  int rc;
+  if (net->dtype == CPRUNE_F32) rc = launch_mbconv_f32(D.d.k, D.d.stride, mb, grid, lds, s, a);
+  else if (net->dtype == CPRUNE_F16) rc = launch_mbconv_f16(D.d.k, D.d.stride, mb, grid, lds, s, a);
+  else rc = launch_mbconv_bf16(D.d.k, D.d.stride, mb, grid, lds, s, a);
+  if (rc != CPRUNE_OK) return rc;
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
 static int net_run_layer(cprune_net* net, int i, int n, const void* x, void* out_override, hipStream_t s) {
   NetLayer& L = net->layers[i];
   const void* src = L.d.input < 0 ? (L.nchw_in ? x : net->x_cl) : net->layers[L.d.input].act;
   void* dst = out_override ? out_override : L.act;
   if (L.fused_away) return CPRUNE_OK;
+  if (L.fuse_block >= 0) return net_run_mbconv(net, i, n, dst, s);
   if (L.fuse_dw >= 0) return net_run_dwproj(net, i, n, dst, s);
   if (L.stem) return net_run_stem(net, i, n, src, dst, s);
   switch (L.d.kind) {
@@ -799,6 +851,64 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     P.fuse_dw = fuse ? i : -1;
     if (fuse) P.variant = -1;
   }
+  // When the depthwise layer's input is a 1x1 expansion that nobody else reads, the whole
+  // inverted-residual block can be one kernel, and the expanded activations never reach memory.
+  // It needs the projection's filters in one tile (at most 128) and the input patch with all its
+  // channels in LDS; with tune != 0 it is timed against the layers as decided so far.
+  for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
+    NetLayer& D = net->layers[i];
+    if (D.dw_reader < 0 || D.d.input < 0) continue;
+    NetLayer& E = net->layers[D.d.input];
+    NetLayer& P = net->layers[D.dw_reader];
+    const cprune_layer_desc& ed = E.d;
+    if (!(ed.kind == CPRUNE_LAYER_CONV && ed.groups == 1 && ed.k == 1 && ed.stride == 1 && ed.pad == 0)) continue;
+    if (ed.input < 0 || ed.residual >= 0 || E.nchw_in || E.map2x2 || E.fused_pool || E.fuse_dw >= 0) continue;
+    if (E.cp_out != round_up_vec(ed.c_out, dtype) || E.cp_out != D.cp_in) continue;
+    int readers = 0;
+    for (int j = 0; j < n_layers; ++j) {
+      if (net->layers[j].d.input == D.d.input) ++readers;
+      if (net->layers[j].d.residual == D.d.input) readers += 2;
+    }
+    if (readers != 1 || !mbconv_fits(*net, E, D, P, nullptr, nullptr)) continue;
+    D.block_expand = D.d.input;
+    const long groups = (long)max_batch * ((D.h_out + 7) / 8) * ((D.w_out + 7) / 8);
+    bool fuse = groups >= 256;
+    const bool dw_fused = D.fused_away;
+    if (tune) {
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      hipError_t e = hipEventCreate(&e0);
+      if (e == hipSuccess) e = hipEventCreate(&e1);
+      float ms[2] = {0.f, 0.f};
+      for (int form = 0; form < 2 && rc == CPRUNE_OK && e == hipSuccess; ++form) {   // 0: as decided so far, 1: one kernel
+        E.fused_away = form == 1;
+        D.fused_away = form == 1 || dw_fused;
+        P.fuse_dw = D.fused_away ? i : -1;
+        P.fuse_block = form == 1 ? D.d.input : -1;
+        for (int pass = 0; pass < 3 && rc == CPRUNE_OK && e == hipSuccess; ++pass) {   // first pass untimed
+          e = hipEventRecord(e0, s);
+          for (int it = 0; it < 6 && rc == CPRUNE_OK; ++it) {
+            rc = net_run_layer(net, D.d.input, max_batch, nullptr, nullptr, s);
+            if (rc == CPRUNE_OK) rc = net_run_layer(net, i, max_batch, nullptr, nullptr, s);
+            if (rc == CPRUNE_OK) rc = net_run_layer(net, D.dw_reader, max_batch, nullptr, nullptr, s);
+          }
+          if (e == hipSuccess) e = hipEventRecord(e1, s);
+          if (e == hipSuccess) e = hipEventSynchronize(e1);
+          float t = 0.f;
+          if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+          if (pass == 1 || (pass == 2 && t < ms[form])) ms[form] = t;
+        }
+      }
+      if (e0) hipEventDestroy(e0);
+      if (e1) hipEventDestroy(e1);
+      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
+      fuse = ms[1] < ms[0];
+    }
+    E.fused_away = fuse;
+    D.fused_away = fuse || dw_fused;
+    P.fuse_dw = D.fused_away ? i : -1;
+    P.fuse_block = fuse ? D.d.input : -1;
+    if (fuse) { P.variant = -1; E.variant = -1; }
+  }
   if (rc == CPRUNE_OK) {
     hipError_t e = hipStreamSynchronize(s);
     if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
@@ -909,6 +1019,11 @@ extern "C" int cprune_net_task_table(const cprune_net* net, int* task_of_layer, 
   return CPRUNE_OK;
 }
 
+static void restore_variant(cprune_net* net, NetLayer& L) {
+  if (L.variant < 0 && !L.stem)
+    L.variant = cached_or_heuristic_variant(layer_conv_desc(*net, L, net->max_batch), nullptr, layer_layout(L));
+}
+
 extern "C" int cprune_net_fuse_depthwise(cprune_net* net, int layer, int enable) {
   if (!net || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
   NetLayer& D = net->layers[layer];
@@ -917,12 +1032,36 @@ extern "C" int cprune_net_fuse_depthwise(cprune_net* net, int layer, int enable)
   for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
   net->graphs.clear();
   NetLayer& P = net->layers[D.dw_reader];
+  if (P.fuse_block >= 0) {             // leaves the one-kernel block form either way
+    NetLayer& E = net->layers[P.fuse_block];
+    E.fused_away = false;
+    restore_variant(net, E);
+    P.fuse_block = -1;
+  }
   D.fused_away = enable != 0;
   P.fuse_dw = enable ? layer : -1;
+  if (enable) P.variant = -1;
+  else restore_variant(net, P);
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_net_fuse_block(cprune_net* net, int layer, int enable) {
+  if (!net || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
+  NetLayer& D = net->layers[layer];
+  if (D.dw_reader < 0 || D.block_expand < 0) return CPRUNE_ERR_UNSUPPORTED;
+  CPRUNE_HIP_TRY(hipDeviceSynchronize());
+  for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
+  net->graphs.clear();
+  NetLayer& P = net->layers[D.dw_reader];
+  NetLayer& E = net->layers[D.block_expand];
   if (enable) {
-    P.variant = -1;
-  } else if (P.variant < 0) {
-    P.variant = cached_or_heuristic_variant(layer_conv_desc(*net, P, net->max_batch), nullptr, layer_layout(P));
+    E.fused_away = true; D.fused_away = true;
+    P.fuse_dw = layer; P.fuse_block = D.block_expand;
+    P.variant = -1; E.variant = -1;
+  } else if (P.fuse_block >= 0) {      // back to the depthwise + projection pair in one kernel, expansion on its own
+    E.fused_away = false;
+    restore_variant(net, E);
+    P.fuse_block = -1;
   }
   return CPRUNE_OK;
 }
@@ -937,7 +1076,7 @@ extern "C" int cprune_net_set_layer_variant(cprune_net* net, int layer, int vari
   if (!net || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
   NetLayer& L = net->layers[layer];
   if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) return CPRUNE_ERR_INVALID_ARG;
-  if (L.fuse_dw >= 0) return CPRUNE_ERR_INVALID_ARG;   // runs the fused depthwise + 1x1 kernel: no variants
+  if (L.fuse_dw >= 0 || L.fused_away) return CPRUNE_ERR_INVALID_ARG;   // runs inside a fused kernel: no variants
   if (L.stem) L.stem = false;                          // a pinned variant means the general kernel
   const cprune_conv_desc cd = layer_conv_desc(*net, L, net->max_batch);
   const ConvLayout lay = layer_layout(L);

@@ -119,6 +119,53 @@ int launch_dwproj_f32(int k, int stride, int mb, dim3 grid, hipStream_t s, const
 int launch_dwproj_f16(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a);
 int launch_dwproj_bf16(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a);
 
+// A whole inverted-residual block in one kernel: 1x1 expansion, depthwise k x k, 1x1 projection, channels-last.
+struct MbConvArgs {
+  const void* x;        // [n][h][w][cpi] block input
+  const void* we;       // [ce][cpi] expansion weights (folded)
+  const float* be;      // [ce] or null
+  const void* wdw;      // [k][k][cpe] depthwise weights (folded)
+  const float* bdw;     // [ce] or null
+  const void* wp;       // [o][cpe] projection weights (folded)
+  const float* bp;      // [o] or null
+  const void* res;      // [n][ho][wo][cop] shortcut or null
+  void* y;              // [n][ho][wo][cop]
+  int N, H, W, Ho, Wo, Cpi, Ce, Cpe, O, Cop;
+  int pad, act_e, act_dw, act_out;
+  int tiles_y, tiles_x;
+  unsigned x_bytes, we_bytes, wp_bytes, wdw_bytes;
+  int vec_out;
+  int xq;               // 16-byte quads per staged input row: cpi * sizeof(T) rounded up to 64 bytes, / 16
+  unsigned magic_xq;    // division by xq
+  int off_we, off_e, off_b, off_a, off_w;   // byte offsets of the LDS regions behind the input patch
+};
+
+// LDS bytes the kernel needs (and the offsets of its regions) for a window, stride, filter tile and input width
+inline size_t mbconv_lds_layout(int k, int s, int mb, int cpi, int es, MbConvArgs* a) {
+  const int ph = 7 * s + k, npatch = ph * ph, npatchp = (npatch + 31) / 32 * 32;
+  const int xrow = (cpi * es + 63) / 64 * 64 + 16, row = 64 + 16;
+  const int cc = 64 / es;
+  size_t off = (size_t)npatchp * xrow;
+  const int off_we = (int)off; off += (size_t)2 * cc * xrow;
+  const int off_e = (int)off; off += (size_t)npatchp * row;
+  const int off_b = (int)off; off += (size_t)64 * row;
+  const int off_a = (int)off; off += (size_t)2 * mb * 16 * row;
+  const int off_w = (int)off; off += (size_t)2 * k * k * 64;
+  if (a) {
+    a->xq = (xrow - 16) / 16;
+    a->magic_xq = a->xq <= 1 ? 0u : (unsigned)((0x100000000ull + a->xq - 1) / a->xq);
+    a->off_we = off_we; a->off_e = off_e; a->off_b = off_b; a->off_a = off_a; a->off_w = off_w;
+  }
+  return off;
+}
+
+// k in {3, 5}, stride in {1, 2}, mb in {2, 4, 8} (the projection has at most 16 * mb filters); grid = one
+// work-group per (image, 8x8 output block); lds_bytes from mbconv_lds_layout (at most 160 KiB).
+// CPRUNE_ERR_UNSUPPORTED for other combinations.
+int launch_mbconv_f32(int k, int stride, int mb, dim3 grid, size_t lds_bytes, hipStream_t s, const MbConvArgs& a);
+int launch_mbconv_f16(int k, int stride, int mb, dim3 grid, size_t lds_bytes, hipStream_t s, const MbConvArgs& a);
+int launch_mbconv_bf16(int k, int stride, int mb, dim3 grid, size_t lds_bytes, hipStream_t s, const MbConvArgs& a);
+
 // First-layer convolution: NCHW input with at most 3 channels, OIHW weights, channels-last output.
 struct StemArgs {
   const void* x;        // [n][c][h][w]

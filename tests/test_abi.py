@@ -42,7 +42,7 @@ def test_variant_table():
     seen = set()
     for v in range(nv):
         tm, tp, sk = B.cprune_tile_variant_info(v)
-        assert tm % 16 == 0 and tp % 16 == 0 and sk >= -1
+        assert tm % 16 == 0 and tp % 16 == 0 and sk >= -2
         seen.add((tm, tp, sk))
     with pytest.raises(B.CPruneError):
         B.cprune_tile_variant_info(nv)
@@ -149,5 +149,6 @@ def test_pool_fc_net_reject_bad_args():
     assert L.cprune_net_destroy(None) == B.ERR_INVALID_ARG
     assert L.cprune_net_set_layer_variant(None, C.c_int(0), C.c_int(0)) == B.ERR_INVALID_ARG
     assert L.cprune_net_fuse_depthwise(None, C.c_int(0), C.c_int(1)) == B.ERR_INVALID_ARG
+    assert L.cprune_net_fuse_block(None, C.c_int(0), C.c_int(1)) == B.ERR_INVALID_ARG
     dims = (C.c_int * 3)()
     assert L.cprune_net_output_shape(None, dims, dims, dims) == B.ERR_INVALID_ARG

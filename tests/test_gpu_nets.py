@@ -47,10 +47,11 @@ def _run(orc, net, cid, batch, dtype, tune, check_layers=True, use_graph=False):
             try:
                 a = handle.activation(i, batch, r.shape[1:]).float().cpu().numpy()
             except B.CPruneError as e:
-                # a conv whose max-pool runs in its epilogue is checked at the pool, a depthwise
-                # conv computed inside its 1x1 consumer's kernel at that consumer
+                # a conv whose max-pool runs in its epilogue is checked at the pool; a depthwise conv
+                # (and the expansion in front of it) computed inside the 1x1 consumer's kernel at
+                # that consumer
                 assert e.status == B.ERR_UNSUPPORTED
-                assert net.layers[i + 1].kind == "maxpool" or net.layers[i].groups != 1
+                assert net.layers[i + 1].kind == "maxpool" or handle.layer_fused(i)
                 continue
             e = nmax(a, r)
             assert e < tol, (net.layers[i].name, e)
@@ -299,4 +300,106 @@ def test_depthwise_fused_into_projection(orc, which, dtype):
     out = handle.forward(xd)
     torch.cuda.synchronize()
     assert nmax(out.float().cpu().numpy(), ref) < TOL[dtype]
+    handle.close()
+
+
+@pytest.mark.parametrize("which,dtype,batch", [("mobilenetv2", B.F32, 3), ("mnasnet", B.F32, 2), ("mobilenetv2", B.F16, 2),
+                                               ("mnasnet", B.F16, 3)])
+def test_inverted_residual_block_as_one_kernel(orc, which, dtype, batch):
+    """Every block whose expansion, depthwise layer and projection can run as one kernel is forced
+    into it (3x3 and 5x5 windows, stride 1 and 2, with and without shortcut, ragged pruned
+    expansion widths, maps down to 2x2 that a tile covers only partly), then forced apart
+    again: logits and every stored activation within the bar both ways; graph replay alike."""
+    net = synth.mobilenetv2(100, 64) if which == "mobilenetv2" else synth.mnasnet(100, 64)
+    cid = 4 if which == "mobilenetv2" else 6
+    handle, xd, logits, ref = _run(orc, net, cid, batch, dtype, tune=False, check_layers=False)
+    dws = [i for i, L in enumerate(net.layers) if L.kind == "conv" and L.groups != 1]
+    fused = []
+    for i in dws:
+        try:
+            handle.fuse_block(i, True)
+        except B.CPruneError as e:
+            assert e.status == B.ERR_UNSUPPORTED
+            continue
+        assert handle.layer_fused(i) and handle.layer_fused(net.layers[i].input)
+        fused.append(i)
+    print(which, "blocks as one kernel:", len(fused), "of", len(dws), flush=True)
+    assert len(fused) >= 10
+    params = synth.layer_params(net, cid)
+    x = synth.net_input(net, cid, batch)
+    ref_layers, _ = orc.prune_net(net, params)
+    ref_acts = orc.forward(net, ref_layers, x, return_all=True)
+    for graph in (False, True, True):
+        out = handle.forward(xd, use_graph=graph)
+        torch.cuda.synchronize()
+        assert nmax(out.float().cpu().numpy(), ref) < TOL[dtype]
+    gone = set(fused) | {net.layers[i].input for i in fused}
+    for i, r in enumerate(ref_acts[:-1]):
+        if i in gone:
+            with pytest.raises(B.CPruneError):
+                handle.activation(i, batch, r.shape[1:])
+            continue
+        if dtype != B.F32 or handle.layer_fused(i):   # 16-bit: rounding accumulates over ~50 layers; the logits carry the bar
+            continue
+        a = handle.activation(i, batch, r.shape[1:]).float().cpu().numpy()
+        assert nmax(a, r) < TOL[dtype], net.layers[i].name
+    with pytest.raises(B.CPruneError):
+        handle.set_layer_variant(net.layers[fused[0]].input, 0)      # the expansion has no program of its own now
+    for i in fused:
+        handle.fuse_block(i, False)
+        assert handle.layer_fused(i) and not handle.layer_fused(net.layers[i].input)
+    out = handle.forward(xd)
+    torch.cuda.synchronize()
+    assert nmax(out.float().cpu().numpy(), ref) < TOL[dtype]
+    for i in fused:
+        handle.fuse_depthwise(i, False)
+        assert not handle.layer_fused(i)
+    out = handle.forward(xd)
+    torch.cuda.synchronize()
+    assert nmax(out.float().cpu().numpy(), ref) < TOL[dtype]
+    handle.close()
+
+
+@pytest.mark.parametrize("cfg", [
+    # c_in, c_exp, c_out, hw, k, stride, shortcut, batch, dtype
+    (24, 150, 24, 19, 3, 1, True, 3, B.BF16),      # ragged map (19 = 2 tiles + 3), shortcut, 16-bit
+    (20, 90, 37, 17, 3, 2, False, 2, B.BF16),      # stride 2, odd map
+    (12, 70, 12, 9, 5, 1, True, 2, B.BF16),        # 5x5 window
+    (16, 100, 40, 22, 5, 2, False, 2, B.F16),      # 5x5 / 2
+    (96, 400, 96, 7, 3, 1, True, 5, B.F32),        # wide input (several rounds of the expansion's reduction), 7x7 map
+    (128, 300, 128, 6, 3, 1, False, 2, B.F16),     # widest input and projection the kernel takes
+    (8, 20, 130, 8, 3, 1, False, 2, B.F32),        # projection too wide for one tile: not eligible
+])
+def test_inverted_residual_probe_blocks(orc, cfg):
+    """One block behind a 3x3 conv, as one kernel and apart, on shapes the networks do not have."""
+    c_in, c_exp, c_out, hw, k, stride, shortcut, batch, dtype = cfg
+    print("block probe", cfg, flush=True)
+    net = synth.NetSpec(f"mbprobe_{c_in}_{c_exp}_{c_out}_{hw}_{k}_{stride}", 3, hw, hw)
+    a = net.add(synth.Layer("conv", -1, 3, c_in, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="a"))
+    e = net.add(synth.Layer("conv", a, c_in, c_exp, k=1, stride=1, pad=0, act=synth.ACT_RELU6, bn=True,
+                            prune_out="own", name="e"))
+    d = net.add(synth.Layer("conv", e, c_exp, c_exp, k=k, stride=stride, pad=k // 2, groups=c_exp, act=synth.ACT_RELU6,
+                            bn=True, prune_out=e, name="d"))
+    net.add(synth.Layer("conv", d, c_exp, c_out, k=1, stride=1, pad=0, act=synth.ACT_NONE, bn=True,
+                        residual=(a if shortcut else None), prune_in=e, name="p"))
+    cid = 60 + k + stride
+    params = synth.layer_params(net, cid)
+    x = synth.net_input(net, cid, batch)
+    ref_layers, _ = orc.prune_net(net, params)
+    ref = orc.forward(net, ref_layers, x)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), dtype)
+    handle = pipeline.build_net(net, layers, batch, dtype, tune=False)
+    xd = torch.from_numpy(x).cuda().to(B.TORCH_DTYPE[dtype])
+    if c_out > 128:
+        with pytest.raises(B.CPruneError):
+            handle.fuse_block(d, True)
+        handle.close()
+        return
+    for on in (True, False, True):
+        handle.fuse_block(d, on)
+        assert handle.layer_fused(e) == on
+        out = handle.forward(xd, use_graph=on)
+        torch.cuda.synchronize()
+        err = nmax(out.float().cpu().numpy(), ref)
+        assert err < TOL[dtype], (on, err)
     handle.close()
