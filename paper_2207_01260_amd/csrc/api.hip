@@ -479,10 +479,8 @@ static bool mbconv_fits(const cprune_net& net, const NetLayer& E, const NetLayer
   const int es = (int)dtype_size(net.dtype);
   if (P.d.c_out > 128) return false;
   const int mb = P.d.c_out <= 32 ? 2 : (P.d.c_out <= 64 ? 4 : 8);
-  MbConvArgs probe;
-  const size_t lds = mbconv_lds_layout(D.d.k, D.d.stride, mb, E.cp_in, es, &probe);
-  if (lds > 160 * 1024) return false;
-  if ((64 / es) * probe.xq > 512) return false;   // the expansion-weight chunk is staged by two loads per thread
+  const size_t lds = mbconv_lds_layout(D.d.k, D.d.stride, mb, E.cp_in, D.cp_in, es, nullptr);
+  if (lds > 160 * 1024) return false;      // the block's weights do not fit beside its tiles
   if (mb_out) *mb_out = mb;
   if (lds_out) *lds_out = lds;
   return true;
@@ -497,7 +495,7 @@ static int net_run_mbconv(cprune_net* net, int i, int n, void* dst, hipStream_t 
   size_t lds = 0;
   if (!mbconv_fits(*net, E, D, P, &mb, &lds)) return CPRUNE_ERR_UNSUPPORTED;
   MbConvArgs a;
-  mbconv_lds_layout(D.d.k, D.d.stride, mb, E.cp_in, (int)es, &a);
+  mbconv_lds_layout(D.d.k, D.d.stride, mb, E.cp_in, D.cp_in, (int)es, &a);
   a.x = net->layers[E.d.input].act;
   a.we = E.w; a.be = E.b; a.wdw = D.w; a.bdw = D.b; a.wp = P.w; a.bp = P.b;
   a.res = P.d.residual >= 0 ? net->layers[P.d.residual].act : nullptr;
@@ -511,7 +509,12 @@ static int net_run_mbconv(cprune_net* net, int i, int n, void* dst, hipStream_t 
   a.wp_bytes = (unsigned)((size_t)a.O * a.Cpe * es);
   a.wdw_bytes = (unsigned)((size_t)D.d.k * D.d.k * a.Cpe * es);
   a.vec_out = (a.Cop % 4) == 0 ? 1 : 0;
-  dim3 grid((unsigned)(n * a.tiles_y * a.tiles_x));
+  // as many work-groups as stay resident (LDS decides), each walking over its share of the pixel blocks
+  const long ntiles = (long)n * a.tiles_y * a.tiles_x;
+  long per_cu = (long)(160 * 1024 / lds);
+  per_cu = per_cu > 4 ? 4 : (per_cu < 1 ? 1 : per_cu);
+  const long workers = ntiles < 256 * per_cu ? ntiles : 256 * per_cu;
+  dim3 grid((unsigned)workers);
   int rc;
   if (net->dtype == CPRUNE_F32) rc = launch_mbconv_f32(D.d.k, D.d.stride, mb, grid, lds, s, a);
   else if (net->dtype == CPRUNE_F16) rc = launch_mbconv_f16(D.d.k, D.d.stride, mb, grid, lds, s, a);
@@ -853,8 +856,9 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
   }
   // When the depthwise layer's input is a 1x1 expansion that nobody else reads, the whole
   // inverted-residual block can be one kernel, and the expanded activations never reach memory.
-  // It needs the projection's filters in one tile (at most 128) and the input patch with all its
-  // channels in LDS; with tune != 0 it is timed against the layers as decided so far.
+  // It needs the projection's filters in one tile (at most 128) and all weights of the three layers
+  // in LDS beside the tiles; with tune != 0 it is timed against the layers as decided so far and
+  // taken when faster, otherwise only cprune_net_fuse_block turns it on.
   for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
     NetLayer& D = net->layers[i];
     if (D.dw_reader < 0 || D.d.input < 0) continue;
@@ -871,8 +875,7 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     }
     if (readers != 1 || !mbconv_fits(*net, E, D, P, nullptr, nullptr)) continue;
     D.block_expand = D.d.input;
-    const long groups = (long)max_batch * ((D.h_out + 7) / 8) * ((D.w_out + 7) / 8);
-    bool fuse = groups >= 256;
+    bool fuse = false;   // untimed, the layers stay apart: so far the one-kernel form has not been the faster one
     const bool dw_fused = D.fused_away;
     if (tune) {
       hipEvent_t e0 = nullptr, e1 = nullptr;

@@ -137,30 +137,35 @@ struct MbConvArgs {
   int vec_out;
   int xq;               // 16-byte quads per staged input row: cpi * sizeof(T) rounded up to 64 bytes, / 16
   unsigned magic_xq;    // division by xq
-  int off_we, off_e, off_b, off_a, off_w;   // byte offsets of the LDS regions behind the input patch
+  int nchunk;           // 64-byte chunks of expanded channels
+  int off_e, off_b, off_we, off_a, off_w, off_bias;   // byte offsets of the LDS regions behind the input patch
 };
 
-// LDS bytes the kernel needs (and the offsets of its regions) for a window, stride, filter tile and input width
-inline size_t mbconv_lds_layout(int k, int s, int mb, int cpi, int es, MbConvArgs* a) {
+// LDS bytes the kernel needs (and the offsets of its regions, xq, nchunk) for a window, stride, filter
+// tile (mb 16-filter blocks), input channel stride cpi, expanded channel stride cpe and element size
+inline size_t mbconv_lds_layout(int k, int s, int mb, int cpi, int cpe, int es, MbConvArgs* a) {
   const int ph = 7 * s + k, npatch = ph * ph, npatchp = (npatch + 31) / 32 * 32;
   const int xrow = (cpi * es + 63) / 64 * 64 + 16, row = 64 + 16;
-  const int cc = 64 / es;
+  const int cc = 64 / es, nchunk = (cpe + cc - 1) / cc;
   size_t off = (size_t)npatchp * xrow;
-  const int off_we = (int)off; off += (size_t)2 * cc * xrow;
   const int off_e = (int)off; off += (size_t)npatchp * row;
   const int off_b = (int)off; off += (size_t)64 * row;
-  const int off_a = (int)off; off += (size_t)2 * mb * 16 * row;
-  const int off_w = (int)off; off += (size_t)2 * k * k * 64;
+  const int off_we = (int)off; off += (size_t)nchunk * cc * xrow;
+  const int off_a = (int)off; off += (size_t)nchunk * mb * 16 * row;
+  const int off_w = (int)off; off += (size_t)nchunk * k * k * 64;
+  const int off_bias = (int)off; off += (size_t)2 * nchunk * cc * sizeof(float);
   if (a) {
     a->xq = (xrow - 16) / 16;
-    a->magic_xq = a->xq <= 1 ? 0u : (unsigned)((0x100000000ull + a->xq - 1) / a->xq);
-    a->off_we = off_we; a->off_e = off_e; a->off_b = off_b; a->off_a = off_a; a->off_w = off_w;
+    a->magic_xq = (unsigned)((0x100000000ull + a->xq - 1) / a->xq);
+    a->nchunk = nchunk;
+    a->off_e = off_e; a->off_b = off_b; a->off_we = off_we; a->off_a = off_a; a->off_w = off_w; a->off_bias = off_bias;
   }
   return off;
 }
 
-// k in {3, 5}, stride in {1, 2}, mb in {2, 4, 8} (the projection has at most 16 * mb filters); grid = one
-// work-group per (image, 8x8 output block); lds_bytes from mbconv_lds_layout (at most 160 KiB).
+// k in {3, 5}, stride in {1, 2}, mb in {2, 4, 8} (the projection has at most 16 * mb filters); grid = persistent
+// work-groups that share the (image, 8x8 output block) list round-robin; lds_bytes from mbconv_lds_layout
+// (at most 160 KiB).
 // CPRUNE_ERR_UNSUPPORTED for other combinations.
 int launch_mbconv_f32(int k, int stride, int mb, dim3 grid, size_t lds_bytes, hipStream_t s, const MbConvArgs& a);
 int launch_mbconv_f16(int k, int stride, int mb, dim3 grid, size_t lds_bytes, hipStream_t s, const MbConvArgs& a);

@@ -100,8 +100,16 @@ __global__ __launch_bounds__(256) void dwproj_kernel(DwProjArgs a) {
   const int w_lds = (w_tap * NQ + w_q) * 16;
 
   uint4 inreg[NI_IN], areg[NI_A], wreg;
+  float bd_n[NI_DW][EPI];   // the chunk's depthwise biases travel with its weights, one chunk ahead of their use
   auto gload = [&](int c0) {
     const unsigned soff = (unsigned)(c0 * ES);
+#pragma unroll
+    for (int j = 0; j < NI_DW; ++j)
+#pragma unroll
+      for (int e = 0; e < EPI; ++e) {
+        const int ch = c0 + ((t + NT * j) % NQ) * EPI + e;
+        bd_n[j][e] = (a.bdw && ch < a.Ce) ? a.bdw[ch] : 0.0f;
+      }
 #pragma unroll
     for (int j = 0; j < NI_A; ++j) {
       const unsigned inval = (unsigned)(c0 + a_q[j] * EPI >= a.Cpe) << 31;
@@ -154,10 +162,14 @@ __global__ __launch_bounds__(256) void dwproj_kernel(DwProjArgs a) {
     for (int c = 0; c < nchunk; ++c) {
       __syncthreads();              // previous chunk's MFMAs have read sA / sB, its depthwise pass sIn / sW
       lds_store();
+      float bd[NI_DW][EPI];
+#pragma unroll
+      for (int j = 0; j < NI_DW; ++j)
+#pragma unroll
+        for (int e = 0; e < EPI; ++e) bd[j][e] = bd_n[j][e];
       __syncthreads();
       if (c + 1 < nchunk) gload((c + 1) * CC);
       // depthwise: k x k window over the staged patch, fp32, bias, activation, rounded to T
-      const int c0 = c * CC;
 #pragma unroll
       for (int j = 0; j < NI_DW; ++j) {
         float s[EPI];
@@ -177,11 +189,7 @@ __global__ __launch_bounds__(256) void dwproj_kernel(DwProjArgs a) {
         uint4 o;
         T* oe = reinterpret_cast<T*>(&o);
 #pragma unroll
-        for (int e = 0; e < EPI; ++e) {
-          const int ch = c0 + dw_q[j] * EPI + e;
-          const float b = (a.bdw && ch < a.Ce) ? a.bdw[ch] : 0.0f;
-          oe[e] = (T)apply_act(s[e] + b, a.act_dw);
-        }
+        for (int e = 0; e < EPI; ++e) oe[e] = (T)apply_act(s[e] + bd[j][e], a.act_dw);
         *(uint4*)&sB[dw_out[j]] = o;
       }
       __syncthreads();
