@@ -551,6 +551,35 @@ static int net_run_layer(cprune_net* net, int i, int n, const void* x, void* out
   return CPRUNE_ERR_INVALID_ARG;
 }
 
+// Device time of running the given layers one after the other, as they are configured right now:
+// the faster of two timed passes of six repetitions each, after one untimed pass.  What the
+// create-time choices between two forms of the same layers are decided by.
+static int time_layers(cprune_net* net, const int* layers, int n_layers, int batch, const void* x, hipStream_t s,
+                       float* ms_out) {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  CPRUNE_HIP_TRY(hipEventCreate(&e0));
+  hipError_t e = hipEventCreate(&e1);
+  if (e != hipSuccess) { hipEventDestroy(e0); set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
+  int rc = CPRUNE_OK;
+  float best = 0.f;
+  for (int pass = 0; pass < 3 && rc == CPRUNE_OK && e == hipSuccess; ++pass) {
+    e = hipEventRecord(e0, s);
+    for (int it = 0; it < 6 && rc == CPRUNE_OK; ++it)
+      for (int k = 0; k < n_layers && rc == CPRUNE_OK; ++k) rc = net_run_layer(net, layers[k], batch, x, nullptr, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+    if (pass == 1 || (pass == 2 && t < best)) best = t;
+  }
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  if (rc != CPRUNE_OK) return rc;
+  if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
+  *ms_out = best;
+  return CPRUNE_OK;
+}
+
 // The last layer writes straight into the caller's buffer when its map is 1x1 (its
 // channel stride is then the dense channel count); otherwise its buffer is converted.
 static int net_enqueue(cprune_net* net, const void* x, int n, void* logits, hipStream_t s) {
@@ -777,25 +806,11 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     }
     bool use = true;
     if (tune) {
-      hipEvent_t e0 = nullptr, e1 = nullptr;
-      hipError_t e = hipEventCreate(&e0);
-      if (e == hipSuccess) e = hipEventCreate(&e1);
       float ms[2] = {0.f, 0.f};
-      for (int form = 0; form < 2 && rc == CPRUNE_OK && e == hipSuccess; ++form) {   // 0: general kernel, 1: first-layer kernel
+      for (int form = 0; form < 2 && rc == CPRUNE_OK; ++form) {   // 0: general kernel, 1: first-layer kernel
         L.stem = form == 1;
-        for (int pass = 0; pass < 3 && rc == CPRUNE_OK && e == hipSuccess; ++pass) {   // first pass untimed
-          e = hipEventRecord(e0, s);
-          for (int it = 0; it < 6 && rc == CPRUNE_OK; ++it) rc = net_run_layer(net, i, max_batch, net->x_cl, nullptr, s);
-          if (e == hipSuccess) e = hipEventRecord(e1, s);
-          if (e == hipSuccess) e = hipEventSynchronize(e1);
-          float t = 0.f;
-          if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
-          if (pass == 1 || (pass == 2 && t < ms[form])) ms[form] = t;
-        }
+        rc = time_layers(net, &i, 1, max_batch, net->x_cl, s, &ms[form]);
       }
-      if (e0) hipEventDestroy(e0);
-      if (e1) hipEventDestroy(e1);
-      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
       use = ms[1] < ms[0];
     }
     L.stem = use;
@@ -825,29 +840,13 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     const long groups = (long)max_batch * ((D.h_out + 7) / 8) * ((D.w_out + 7) / 8) * ((pd.c_out + mt - 1) / mt);
     bool fuse = groups >= 512;
     if (tune) {
-      hipEvent_t e0 = nullptr, e1 = nullptr;
-      hipError_t e = hipEventCreate(&e0);
-      if (e == hipSuccess) e = hipEventCreate(&e1);
       float ms[2] = {0.f, 0.f};
-      for (int form = 0; form < 2 && rc == CPRUNE_OK && e == hipSuccess; ++form) {   // 0: two kernels, 1: fused
+      const int pair[2] = {i, reader};
+      for (int form = 0; form < 2 && rc == CPRUNE_OK; ++form) {   // 0: two kernels, 1: fused
         D.fused_away = form == 1;
         P.fuse_dw = form == 1 ? i : -1;
-        for (int pass = 0; pass < 3 && rc == CPRUNE_OK && e == hipSuccess; ++pass) {   // first pass untimed
-          e = hipEventRecord(e0, s);
-          for (int it = 0; it < 6 && rc == CPRUNE_OK; ++it) {
-            rc = net_run_layer(net, i, max_batch, nullptr, nullptr, s);
-            if (rc == CPRUNE_OK) rc = net_run_layer(net, reader, max_batch, nullptr, nullptr, s);
-          }
-          if (e == hipSuccess) e = hipEventRecord(e1, s);
-          if (e == hipSuccess) e = hipEventSynchronize(e1);
-          float t = 0.f;
-          if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
-          if (pass == 1 || (pass == 2 && t < ms[form])) ms[form] = t;
-        }
+        rc = time_layers(net, pair, 2, max_batch, nullptr, s, &ms[form]);
       }
-      if (e0) hipEventDestroy(e0);
-      if (e1) hipEventDestroy(e1);
-      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
       fuse = ms[1] < ms[0];
     }
     D.fused_away = fuse;
@@ -878,32 +877,15 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     bool fuse = false;   // untimed, the layers stay apart: so far the one-kernel form has not been the faster one
     const bool dw_fused = D.fused_away;
     if (tune) {
-      hipEvent_t e0 = nullptr, e1 = nullptr;
-      hipError_t e = hipEventCreate(&e0);
-      if (e == hipSuccess) e = hipEventCreate(&e1);
       float ms[2] = {0.f, 0.f};
-      for (int form = 0; form < 2 && rc == CPRUNE_OK && e == hipSuccess; ++form) {   // 0: as decided so far, 1: one kernel
+      const int block[3] = {D.d.input, i, D.dw_reader};
+      for (int form = 0; form < 2 && rc == CPRUNE_OK; ++form) {   // 0: as decided so far, 1: one kernel
         E.fused_away = form == 1;
         D.fused_away = form == 1 || dw_fused;
         P.fuse_dw = D.fused_away ? i : -1;
         P.fuse_block = form == 1 ? D.d.input : -1;
-        for (int pass = 0; pass < 3 && rc == CPRUNE_OK && e == hipSuccess; ++pass) {   // first pass untimed
-          e = hipEventRecord(e0, s);
-          for (int it = 0; it < 6 && rc == CPRUNE_OK; ++it) {
-            rc = net_run_layer(net, D.d.input, max_batch, nullptr, nullptr, s);
-            if (rc == CPRUNE_OK) rc = net_run_layer(net, i, max_batch, nullptr, nullptr, s);
-            if (rc == CPRUNE_OK) rc = net_run_layer(net, D.dw_reader, max_batch, nullptr, nullptr, s);
-          }
-          if (e == hipSuccess) e = hipEventRecord(e1, s);
-          if (e == hipSuccess) e = hipEventSynchronize(e1);
-          float t = 0.f;
-          if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
-          if (pass == 1 || (pass == 2 && t < ms[form])) ms[form] = t;
-        }
+        rc = time_layers(net, block, 3, max_batch, nullptr, s, &ms[form]);
       }
-      if (e0) hipEventDestroy(e0);
-      if (e1) hipEventDestroy(e1);
-      if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
       fuse = ms[1] < ms[0];
     }
     E.fused_away = fuse;
