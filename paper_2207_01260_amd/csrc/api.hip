@@ -479,8 +479,11 @@ static bool mbconv_fits(const cprune_net& net, const NetLayer& E, const NetLayer
   const int es = (int)dtype_size(net.dtype);
   if (P.d.c_out > 128) return false;
   const int mb = P.d.c_out <= 32 ? 2 : (P.d.c_out <= 64 ? 4 : 8);
-  const size_t lds = mbconv_lds_layout(D.d.k, D.d.stride, mb, E.cp_in, D.cp_in, es, nullptr);
+  MbConvArgs lay;
+  const size_t lds = mbconv_lds_layout(D.d.k, D.d.stride, mb, E.cp_in, D.cp_in, es, &lay);
   if (lds > 160 * 1024) return false;      // the block's weights do not fit beside its tiles
+  const int ph = 7 * D.d.stride + D.d.k, npatchp = (ph * ph + 31) / 32 * 32;
+  if ((long)npatchp * lay.xq > 256L * 10) return false;   // the next patch travels in ten registers per thread
   if (mb_out) *mb_out = mb;
   if (lds_out) *lds_out = lds;
   return true;

@@ -148,8 +148,8 @@ inline size_t mbconv_lds_layout(int k, int s, int mb, int cpi, int cpe, int es, 
   const int xrow = (cpi * es + 63) / 64 * 64 + 16, row = 64 + 16;
   const int cc = 64 / es, nchunk = (cpe + cc - 1) / cc;
   size_t off = (size_t)npatchp * xrow;
-  const int off_e = (int)off; off += (size_t)npatchp * row;
-  const int off_b = (int)off; off += (size_t)64 * row;
+  const int off_e = (int)off; off += (size_t)2 * npatchp * row;   // double buffers of the two chunk tiles
+  const int off_b = (int)off; off += (size_t)2 * 64 * row;
   const int off_we = (int)off; off += (size_t)nchunk * cc * xrow;
   const int off_a = (int)off; off += (size_t)nchunk * mb * 16 * row;
   const int off_w = (int)off; off += (size_t)nchunk * k * k * 64;

@@ -76,10 +76,13 @@ __device__ __forceinline__ unsigned fast_div(unsigned n, unsigned magic) {
   return magic ? __umulhi(n, magic) : n;
 }
 
+// Every activation here is a clamp: none = (-inf, +inf), ReLU = [0, +inf), ReLU6 = [0, 6].  The bounds are
+// uniform and loop-invariant, so an element costs a max and a min; written as branches on `act` the
+// compiler emitted a branch sequence per element (most of the time of a fused kernel's vector steps).
 __device__ __forceinline__ float apply_act(float v, int act) {
-  if (act == CPRUNE_ACT_RELU) return fmaxf(v, 0.0f);
-  if (act == CPRUNE_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
-  return v;
+  const float lo = act == CPRUNE_ACT_NONE ? -__builtin_inff() : 0.0f;
+  const float hi = act == CPRUNE_ACT_RELU6 ? 6.0f : __builtin_inff();
+  return fminf(fmaxf(v, lo), hi);
 }
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {

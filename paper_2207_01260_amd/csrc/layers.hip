@@ -11,10 +11,11 @@ namespace {
 template <typename T> __device__ __forceinline__ float ld(const T* p) { return (float)*p; }
 template <typename T> __device__ __forceinline__ void st(T* p, float v) { *p = (T)v; }
 
+// an activation is a clamp with uniform bounds: a max and a min per element, no branches
 __device__ __forceinline__ float act_f(float v, int act) {
-  if (act == CPRUNE_ACT_RELU) return fmaxf(v, 0.0f);
-  if (act == CPRUNE_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
-  return v;
+  const float lo = act == CPRUNE_ACT_NONE ? -__builtin_inff() : 0.0f;
+  const float hi = act == CPRUNE_ACT_RELU6 ? 6.0f : __builtin_inff();
+  return fminf(fmaxf(v, lo), hi);
 }
 
 // grid.x = n*c planes, grid.y slices the output plane; weights of the plane's

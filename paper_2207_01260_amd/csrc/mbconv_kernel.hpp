@@ -15,7 +15,11 @@
 //   2. depthwise window over that tile, fp32 arithmetic, bias, activation, rounded -> LDS tile
 //      [output pixel][chunk], laid out as the B operand of the projection;
 //   3. projection: the chunk is one 64-byte round of the 1x1 layer's reduction.
-// No global memory is touched inside the chunk loop (two barriers per chunk).  The halo of the
+// The three steps are software-pipelined over the chunks: between two barriers a wavefront runs
+// step 1 of chunk p, step 2 of chunk p - 1 and step 3 of chunk p - 2 (the two LDS tiles are double
+// buffers), so that every interval holds matrix-core work, vector work and LDS traffic that do not
+// depend on each other; one barrier per chunk.  No global memory is touched inside the chunk loop
+// except the next block's input patch, which travels to registers meanwhile.  The halo of the
 // patch is expanded again by the neighbouring blocks ((8+k-1)^2 / 64 of the expansion's
 // multiply-adds at stride 1, (15+k)^2 / 256 at stride 2): matrix-core work that is cheap next
 // to the memory traffic it replaces.
@@ -42,11 +46,13 @@ __global__ __launch_bounds__(256) void mbconv_kernel(MbConvArgs a) {
   constexpr int NPAIR = NPATCHP / 32;      // pairs of 16-pixel blocks the expansion walks over
   constexpr int ROW = 64 + 16;             // bytes per LDS row of the chunk tiles
   constexpr int U = 4;                     // loads in flight per thread while staging
+  constexpr int NPRE = 10;                 // 16-byte pieces of the next input patch a thread holds (host checks the fit)
+  constexpr int SE = NPATCHP * ROW, SB = 64 * ROW;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   unsigned char* sX = lds;                       // [NPATCHP][XROW] input patch
-  unsigned char* sE = lds + a.off_e;             // [NPATCHP][ROW] expanded chunk
-  unsigned char* sB = lds + a.off_b;             // [64][ROW] depthwise output chunk
+  unsigned char* sE = lds + a.off_e;             // [2][NPATCHP][ROW] expanded chunk (double buffer)
+  unsigned char* sB = lds + a.off_b;             // [2][64][ROW] depthwise output chunk (double buffer)
   unsigned char* sWe = lds + a.off_we;           // [nchunk * CC][XROW] expansion weights
   unsigned char* sA = lds + a.off_a;             // [nchunk][MT][ROW] projection weights, chunk-major
   unsigned char* sW = lds + a.off_w;             // [nchunk][K * K][64] depthwise weights, chunk-major
@@ -129,6 +135,38 @@ __global__ __launch_bounds__(256) void mbconv_kernel(MbConvArgs a) {
   }
   const int ntiles = a.N * a.tiles_y * a.tiles_x;
 
+  // the input patch of a block: piece j of this thread is item t + 256 * j of [NPATCHP][XQ]
+  const int npieces = NPATCHP * XQ;
+  uint4 pre[NPRE];
+  auto load_patch = [&](int tile) {
+    const int tx0 = (tile % a.tiles_x) * TW;
+    int rest = tile / a.tiles_x;
+    const int ty0 = (rest % a.tiles_y) * 8;
+    const int n = rest / a.tiles_y;
+    const int iy0 = ty0 * S - a.pad, ix0 = tx0 * S - a.pad;
+#pragma unroll
+    for (int j = 0; j < NPRE; ++j) {
+      const int idx = t + NT * j;
+      const int pp = (int)fast_div((unsigned)idx, a.magic_xq), q = idx - pp * XQ;
+      const int py = pp / PW, px = pp - py * PW;
+      const int iy = iy0 + py, ix = ix0 + px;
+      const bool inside = idx < npieces && pp < NPATCH && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W &&
+                          q * EPI < a.Cpi;
+      pre[j] = load_b128(xr, inside ? (unsigned)(((n * a.H + iy) * a.W + ix) * a.Cpi + q * EPI) * ES : kOutOfRange, 0);
+    }
+  };
+  auto store_patch = [&]() {
+#pragma unroll
+    for (int j = 0; j < NPRE; ++j) {
+      const int idx = t + NT * j;
+      if (idx < npieces) {
+        const int pp = (int)fast_div((unsigned)idx, a.magic_xq), q = idx - pp * XQ;
+        *(uint4*)&sX[pp * XROW + q * 16] = pre[j];
+      }
+    }
+  };
+
+  if (worker < ntiles) load_patch(worker);
   for (int tile = worker; tile < ntiles; tile += (int)gridDim.x) {
     const int tx0 = (tile % a.tiles_x) * TW;
     int rest = tile / a.tiles_x;
@@ -137,102 +175,108 @@ __global__ __launch_bounds__(256) void mbconv_kernel(MbConvArgs a) {
     const int iy0 = ty0 * S - a.pad, ix0 = tx0 * S - a.pad;
 
     __syncthreads();               // the previous block's readers of the patch are done
-    stage(NPATCHP * XQ, xr, sX,
-          [&](int idx) -> unsigned {
-            const int pp = (int)fast_div((unsigned)idx, a.magic_xq), q = idx - pp * XQ;
-            const int py = pp / PW, px = pp - py * PW;
-            const int iy = iy0 + py, ix = ix0 + px;
-            const bool inside = pp < NPATCH && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W && q * EPI < a.Cpi;
-            return inside ? (unsigned)(((n * a.H + iy) * a.W + ix) * a.Cpi + q * EPI) * ES : kOutOfRange;
-          },
-          [&](int idx) -> int {
-            const int pp = (int)fast_div((unsigned)idx, a.magic_xq), q = idx - pp * XQ;
-            return pp * XROW + q * 16;
-          });
+    store_patch();
     __syncthreads();               // patch (and, the first time, the weights) are in LDS
+    if (tile + (int)gridDim.x < ntiles) load_patch(tile + (int)gridDim.x);
 
     float4_t acc[MB][1];
 #pragma unroll
     for (int i = 0; i < MB; ++i) acc[i][0] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
+    // 1. expansion of chunk c at every patch pixel; wavefront w takes pixel-block pairs w, w + 4, ...
+    auto expand = [&](int c, unsigned char* dstE) {
+      const int c0 = c * CC;
+      float4_t eb[MBE];
+#pragma unroll
+      for (int i = 0; i < MBE; ++i) eb[i] = *(const float4_t*)&sBe[c0 + i * 16 + 4 * g4];
+      const unsigned char* wbuf = sWe + c0 * XROW;
+      for (int pair = wave; pair < NPAIR; pair += 4) {
+        float4_t ea[MBE][2];
+#pragma unroll
+        for (int i = 0; i < MBE; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) ea[i][j] = (float4_t){0.f, 0.f, 0.f, 0.f};
+        const int xrow0 = (pair * 32 + r) * XROW + g4 * 16;
+        // operands of round rnd + 1 are fetched from LDS while round rnd is multiplied (two register sets)
+        uint4 af0[MBE], bf0[2], af1[MBE], bf1[2];
+        auto fetch = [&](int rnd, uint4 (&fa)[MBE], uint4 (&fb)[2]) {
+#pragma unroll
+          for (int j = 0; j < 2; ++j) fb[j] = *(const uint4*)&sX[xrow0 + j * 16 * XROW + rnd * 64];
+#pragma unroll
+          for (int i = 0; i < MBE; ++i) fa[i] = *(const uint4*)&wbuf[(i * 16 + r) * XROW + g4 * 16 + rnd * 64];
+        };
+        fetch(0, af0, bf0);
+        for (int rnd = 0; rnd < XR; rnd += 2) {
+          const bool second = rnd + 1 < XR;
+          if (second) fetch(rnd + 1, af1, bf1);
+          mma_slab<T, MBE, 2, MBE>(af0, bf0, ea);
+          if (rnd + 2 < XR) fetch(rnd + 2, af0, bf0);
+          if (second) mma_slab<T, MBE, 2, MBE>(af1, bf1, ea);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int pp = pair * 32 + j * 16 + r;
+          const int py = pp / PW, px = pp - py * PW;
+          const bool inside = pp < NPATCH && (unsigned)(iy0 + py) < (unsigned)a.H && (unsigned)(ix0 + px) < (unsigned)a.W;
+          const float keep = inside ? 1.0f : 0.0f;   // a factor, not a branch: activations are finite
+#pragma unroll
+          for (int i = 0; i < MBE; ++i) {
+            T h[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) h[v] = (T)(keep * apply_act(ea[i][j][v] + eb[i][v], a.act_e));
+            unsigned char* dst = &dstE[pp * ROW + (i * 16 + 4 * g4) * ES];
+            if constexpr (ES == 4) *(uint4*)dst = *(const uint4*)h;
+            else *(uint2*)dst = *(const uint2*)h;
+          }
+        }
+      }
+    };
+    // 2. depthwise window over the expanded tile of chunk c
+    auto depthwise = [&](int c, const unsigned char* srcE, unsigned char* dstB) {
+      float s[EPI];
+#pragma unroll
+      for (int q = 0; q < EPI; ++q) s[q] = 0.0f;
+      const unsigned char* dwb = sW + c * KK * 64;
+#pragma unroll
+      for (int u = 0; u < K; ++u)
+#pragma unroll
+        for (int v = 0; v < K; ++v) {
+          const uint4 xi = *(const uint4*)&srcE[dw_in + (u * PW + v) * ROW];
+          const uint4 wi = *(const uint4*)&dwb[((u * K + v) * 4 + dq) * 16];
+          const T* xe = reinterpret_cast<const T*>(&xi);
+          const T* wv = reinterpret_cast<const T*>(&wi);
+#pragma unroll
+          for (int q = 0; q < EPI; ++q) s[q] += (float)xe[q] * (float)wv[q];
+        }
+      uint4 o;
+      T* oe = reinterpret_cast<T*>(&o);
+#pragma unroll
+      for (int q4 = 0; q4 < EPI / 4; ++q4) {
+        const float4_t bd = *(const float4_t*)&sBd[c * CC + dq * EPI + 4 * q4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) oe[4 * q4 + v] = (T)apply_act(s[4 * q4 + v] + bd[v], a.act_dw);
+      }
+      *(uint4*)&dstB[dw_out] = o;
+    };
+
     auto main_loop = [&](auto mbc_tag) {
       constexpr int MBC = decltype(mbc_tag)::value;
-      for (int c = 0; c < nchunk; ++c) {
-        const int c0 = c * CC;
-        // 1. expansion of the chunk at every patch pixel; wavefront w takes pixel-block pairs w, w + 4, ...
-        float4_t eb[MBE];
-#pragma unroll
-        for (int i = 0; i < MBE; ++i) eb[i] = *(const float4_t*)&sBe[c0 + i * 16 + 4 * g4];
-        const unsigned char* wbuf = sWe + c0 * XROW;
-        for (int pair = wave; pair < NPAIR; pair += 4) {
-          float4_t ea[MBE][2];
-#pragma unroll
-          for (int i = 0; i < MBE; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) ea[i][j] = (float4_t){0.f, 0.f, 0.f, 0.f};
-          const int xrow0 = (pair * 32 + r) * XROW + g4 * 16;
-          for (int rnd = 0; rnd < XR; ++rnd) {
-            uint4 af[MBE], bf[2];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) bf[j] = *(const uint4*)&sX[xrow0 + j * 16 * XROW + rnd * 64];
-#pragma unroll
-            for (int i = 0; i < MBE; ++i) af[i] = *(const uint4*)&wbuf[(i * 16 + r) * XROW + g4 * 16 + rnd * 64];
-            mma_slab<T, MBE, 2, MBE>(af, bf, ea);
-          }
-#pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            const int pp = pair * 32 + j * 16 + r;
-            const int py = pp / PW, px = pp - py * PW;
-            const bool inside = pp < NPATCH && (unsigned)(iy0 + py) < (unsigned)a.H && (unsigned)(ix0 + px) < (unsigned)a.W;
-#pragma unroll
-            for (int i = 0; i < MBE; ++i) {
-              T h[4];
-#pragma unroll
-              for (int v = 0; v < 4; ++v) h[v] = (T)(inside ? apply_act(ea[i][j][v] + eb[i][v], a.act_e) : 0.0f);
-              unsigned char* dst = &sE[pp * ROW + (i * 16 + 4 * g4) * ES];
-              if constexpr (ES == 4) *(uint4*)dst = *(const uint4*)h;
-              else *(uint2*)dst = *(const uint2*)h;
-            }
-          }
-        }
-        __syncthreads();
-
-        // 2. depthwise window over the expanded tile
-        {
-          float s[EPI];
-#pragma unroll
-          for (int q = 0; q < EPI; ++q) s[q] = 0.0f;
-          const unsigned char* dwb = sW + c * KK * 64;
-#pragma unroll
-          for (int u = 0; u < K; ++u)
-#pragma unroll
-            for (int v = 0; v < K; ++v) {
-              const uint4 xi = *(const uint4*)&sE[dw_in + (u * PW + v) * ROW];
-              const uint4 wi = *(const uint4*)&dwb[((u * K + v) * 4 + dq) * 16];
-              const T* xe = reinterpret_cast<const T*>(&xi);
-              const T* wv = reinterpret_cast<const T*>(&wi);
-#pragma unroll
-              for (int q = 0; q < EPI; ++q) s[q] += (float)xe[q] * (float)wv[q];
-            }
-          uint4 o;
-          T* oe = reinterpret_cast<T*>(&o);
-#pragma unroll
-          for (int q = 0; q < EPI; ++q) oe[q] = (T)apply_act(s[q] + sBd[c0 + dq * EPI + q], a.act_dw);
-          *(uint4*)&sB[dw_out] = o;
-        }
-        __syncthreads();
-
-        // 3. projection: one 64-byte round of its reduction.  The next chunk's expansion overwrites
-        // sE (read in step 2, behind a barrier); its depthwise step overwrites sB only after the
-        // barrier that ends that expansion.
-        {
+      // interval p: expansion of chunk p into sE[p & 1] (last read by the depthwise step of chunk
+      // p - 2, one interval ago), depthwise step of chunk p - 1 from sE[(p - 1) & 1] into
+      // sB[(p - 1) & 1] (last read by the projection of chunk p - 3, one interval ago), projection
+      // of chunk p - 2 from sB[p & 1] (written one interval ago)
+      for (int p = 0; p < nchunk + 2; ++p) {
+        if (p < nchunk) expand(p, sE + (p & 1) * SE);
+        if (p >= 1 && p <= nchunk) depthwise(p - 1, sE + ((p - 1) & 1) * SE, sB + ((p - 1) & 1) * SB);
+        if (p >= 2) {
           uint4 af[MB], bf[1];
-          bf[0] = *(const uint4*)&sB[b_frag];
-          const unsigned char* abuf = sA + c * MT * ROW;
+          bf[0] = *(const uint4*)&sB[(p & 1) * SB + b_frag];
+          const unsigned char* abuf = sA + (p - 2) * MT * ROW;
 #pragma unroll
           for (int i = 0; i < MBC; ++i) af[i] = *(const uint4*)&abuf[a_frag + i * 16 * ROW];
           mma_slab<T, MBC, 1, MB>(af, bf, acc);
         }
+        __syncthreads();
       }
     };
     switch (mb_count) {
