@@ -89,6 +89,17 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
+// bias[o .. o + 3] with zeros past the last filter (and for a null bias): four range-checked
+// buffer loads, no branches
+__device__ __forceinline__ float4_t load_bias4(const float* bias, int n_filters, int o) {
+  const __amdgpu_buffer_rsrc_t br = make_rsrc(bias, bias ? (unsigned)n_filters * 4u : 0u);
+  float4_t b;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    b[i] = __uint_as_float((unsigned)__builtin_amdgcn_raw_buffer_load_b32(br, (o + i) * 4, 0, 0));
+  return b;
+}
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
   typedef uint32_t raw_t;
@@ -167,18 +178,19 @@ __device__ __forceinline__ void unit_range(const ConvArgs& a, int g, int& ub, in
 // a lane holds 4 consecutive channels of one pixel.
 template <typename T>
 __device__ __forceinline__ void nhwc_store4(const ConvArgs& a, const float4_t& acc, int p, int o) {
+  const float4_t bias = load_bias4(a.bias, a.O, o);
   if (a.pool4) {
     if (o >= a.O) return;
-    float m = apply_act(acc[0] + (a.bias ? a.bias[o] : 0.0f), a.act);
+    float m = apply_act(acc[0] + bias[0], a.act);
 #pragma unroll
-    for (int i = 1; i < 4; ++i) m = fmaxf(m, apply_act(acc[i] + (a.bias ? a.bias[o + i] : 0.0f), a.act));
+    for (int i = 1; i < 4; ++i) m = fmaxf(m, apply_act(acc[i] + bias[i], a.act));
     ((T*)a.y)[(size_t)p * a.Cop + (o >> 2)] = Elem<T>::from_f32(m);
     return;
   }
   if (o >= a.Cop) return;
   float v[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) v[i] = acc[i] + ((a.bias && o + i < a.O) ? a.bias[o + i] : 0.0f);
+  for (int i = 0; i < 4; ++i) v[i] = acc[i] + bias[i];
   const size_t off = (size_t)p * a.Cop + o;
   if (a.vec_out) {
     if (a.res) {

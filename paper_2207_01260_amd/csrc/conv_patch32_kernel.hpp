@@ -296,9 +296,10 @@ __global__ __launch_bounds__(256) void conv_patch32_kernel(PatchArgs a) {
         for (int vq = 0; vq < 4; ++vq) {
           const int o = o0 + i * 32 + 8 * vq + 4 * h;
           float4_t m;
+          const float4_t bias = load_bias4(a.bias, a.O, o);
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            float x = acc[i][j][4 * vq + c] + ((a.bias && o + c < a.O) ? a.bias[o + c] : 0.0f);
+            float x = acc[i][j][4 * vq + c] + bias[c];
             x = apply_act(x, a.act);
             x = fmaxf(x, __shfl_xor(x, 1, 64));
             x = fmaxf(x, __shfl_xor(x, TW, 64));

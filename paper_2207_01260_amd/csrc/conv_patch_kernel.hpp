@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
     const int iy = ty0 + py - 1, ix = tx0 + px - 1, n = n0 + img;
     const bool inside = item && n < a.N && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
     b_off[j] = inside ? (unsigned)(((n * a.H + iy) * a.W + ix) * a.Cp + q * EPI) * ES : kOutOfRange;
-    b_lds[j] = item ? pp * BROW + q * 16 : -1;
+    b_lds[j] = item ? pp * BROW + q * 16 : NPATCH * BROW - 16;   // no item: the last row's pad, which nobody reads
     b_q[j] = q;
   }
   unsigned a_off[NIA];   // byte offset of (filter, tap, quad) at chunk 0
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
     const bool item = m < MT;
     const int o = o0 + m;
     a_off[j] = (item && o < a.O) ? (unsigned)((o * 9 + tap) * a.Cp + q * EPI) * ES : kOutOfRange;
-    a_lds[j] = item ? m * AROW + tap * (64 * KQ) + q * 16 : -1;
+    a_lds[j] = item ? m * AROW + tap * (64 * KQ) + q * 16 : MT * AROW - 16;
     a_q[j] = q;
   }
 
@@ -171,11 +171,9 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
   };
   auto lds_store = [&]() {
 #pragma unroll
-    for (int j = 0; j < NIA; ++j)
-      if (a_lds[j] >= 0) *(uint4*)&sA[a_lds[j]] = areg[j];
+    for (int j = 0; j < NIA; ++j) *(uint4*)&sA[a_lds[j]] = areg[j];   // unconditional: a branch per item costs more
 #pragma unroll
-    for (int j = 0; j < NIB; ++j)
-      if (b_lds[j] >= 0) *(uint4*)&sB[b_lds[j]] = breg[j];
+    for (int j = 0; j < NIB; ++j) *(uint4*)&sB[b_lds[j]] = breg[j];
   };
 
   // ---- fragment addresses: lane's pixel inside the patch (tap (0,0) corner) ----
@@ -313,11 +311,12 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
     for (int i = 0; i < MB; ++i) {
       const int o = o0 + i * 16 + 4 * g4;
       float4_t v[NB];
+      const float4_t bias = load_bias4(a.bias, a.O, o);
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          float x = acc[i][j][c] + ((a.bias && o + c < a.O) ? a.bias[o + c] : 0.0f);
+          float x = acc[i][j][c] + bias[c];
           x = apply_act(x, a.act);
           x = fmaxf(x, __shfl_xor(x, 1, 64));
           if constexpr (TW < 16) x = fmaxf(x, __shfl_xor(x, TW, 64));
