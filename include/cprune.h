@@ -135,6 +135,9 @@ typedef struct {
  * sched -2: likewise channels-last only, for layers whose reduction is one contiguous run
  * per pixel (1x1 stride 1, fully connected): 16 filters x tile_p pixels per work-group, the
  * wavefronts of the group splitting the reduction; chosen when pixels are few.
+ * sched -3: channels-last 1x1 / stride 1 layers with a short reduction (at most 384 bytes per
+ * pixel): persistent work-groups keep a tile of at most 128 filters in local memory and stream
+ * 64-pixel tiles through it.
  * Ids are 0..n-1
  * and the same for every shape; a variant that cannot run a given shape is
  * CPRUNE_ERR_UNSUPPORTED. */

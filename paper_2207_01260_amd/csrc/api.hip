@@ -215,6 +215,8 @@ extern "C" int cprune_tile_variant_name(int v, int channels_last, cprune_dtype d
   if (tv.sched >= 0)
     n = snprintf(buf, buf_bytes, "%s<%s, %d, %d, %d, %d, %d>", channels_last ? "conv_nhwc_kernel" : "conv_igemm_kernel", t,
                  tv.wm, tv.wn, tv.mb, tv.nb, tv.kq);
+  else if (tv.sched == -3)
+    n = snprintf(buf, buf_bytes, "conv_pw_kernel<%s, %d, %d>", t, tv.mb, tv.nr);
   else if (tv.sched == -2)
     n = snprintf(buf, buf_bytes, "conv_ksplit_kernel<%s, %d, %d>", t, tv.nb, tv.kwaves);
   else if (tv.blk32)

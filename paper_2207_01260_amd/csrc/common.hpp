@@ -37,11 +37,13 @@ struct TileVariant {
   int kq;       // MFMA rounds (64 bytes of k per row each) per slab
   int sched;    // scheduling mode: 0 = one tile per work-group, n = runs for n * 256 groups,
                 // -1 = 3x3 spatial-patch kernel (one th x tw pixel block per work-group),
-                // -2 = reduction-split kernel (16 filters x nb pixel blocks per work-group)
+                // -2 = reduction-split kernel (16 filters x nb pixel blocks per work-group),
+                // -3 = short-reduction 1x1 kernel (persistent groups, filter tile resident in LDS)
   int th = 0, tw = 0, ni = 1, patch_id = -1;
   int blk32 = 0;  // patch kernels: 1 = 32x32 MFMA blocks (patch_id then indexes that kernel's list)
   int ks = 1;     // patch kernels on 16x16 blocks: wave groups per tile
   int kwaves = 0; // reduction-split kernel: wavefronts that share one tile's reduction (patch_id indexes its list)
+  int nr = 0;     // short-reduction 1x1 kernel: 64-byte rounds of the reduction its filter tile holds
   int tile_m() const { return wm * mb * 16; }
   int tile_p() const { return wn * nb * 16; }
 };

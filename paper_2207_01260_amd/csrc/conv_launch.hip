@@ -1,6 +1,7 @@
 // Host side of the dense convolution: the variant table (tile x scheduling
 // mode), what each variant supports and needs, and the launch.
 #include "conv_ksplit_kernel.hpp"
+#include "conv_pw_kernel.hpp"
 #include "conv_patch32_kernel.hpp"
 
 namespace cprune {
@@ -60,11 +61,11 @@ Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv, const ConvLayou
 
 }  // namespace
 
-int num_variants() { return kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit; }
+int num_variants() { return kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw; }
 
 namespace {
 struct VariantTable {
-  TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit];
+  TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw];
   VariantTable() {
 #define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_, KQ_, KS_)                                 \
     {                                                                         \
@@ -90,6 +91,14 @@ struct VariantTable {
     }
     CPRUNE_KSPLIT_LIST(CPRUNE_KSPLIT_ROW)
 #undef CPRUNE_KSPLIT_ROW
+#define CPRUNE_PW_ROW(ID, MB_, NR_)                                                        \
+    {                                                                                      \
+      TileVariant& kv = table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + ID]; \
+      kv.wm = 1; kv.wn = 4; kv.mb = MB_; kv.nb = 1; kv.kq = NR_; kv.sched = -3;            \
+      kv.patch_id = ID; kv.nr = NR_;                                                       \
+    }
+    CPRUNE_PW_LIST(CPRUNE_PW_ROW)
+#undef CPRUNE_PW_ROW
     for (int t = 0; t < kNumTiles; ++t)
       for (int s = 0; s < kNumScheds; ++s) {
         table[t * kNumScheds + s] = kTiles[t];
@@ -108,6 +117,15 @@ bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
   if (v < 0 || v >= num_variants()) return false;
   if (d.groups != 1) return false;
   const TileVariant& tv = variant(v);
+  if (tv.sched == -3) {
+    // 1x1 / stride 1, no pool; exactly one (mb, nr) pair serves a shape: the smallest filter tile that
+    // holds min(c_out, 128) filters and the smallest round count that holds the reduction
+    if (!lay.nhwc || lay.pool || !(d.kh == 1 && d.kw == 1 && d.stride == 1 && d.pad == 0)) return false;
+    const int rounds = (int)(((long)lay.cp_in * (long)dtype_size(d.dtype) + 63) / 64);
+    const int nr = rounds <= 4 ? rounds : (rounds <= 6 ? 6 : 0);
+    const int mb = d.c_out <= 32 ? 2 : (d.c_out <= 64 ? 4 : 8);
+    return tv.nr == nr && tv.mb == mb;
+  }
   if (tv.sched == -2) {
     // the reduction of a pixel is one contiguous run: 1x1 / stride 1, or a window that covers the whole map
     const bool pointwise = d.kh == 1 && d.kw == 1 && d.stride == 1 && d.pad == 0;
@@ -159,6 +177,35 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
                       const void* residual, void* y, int v, void* ws, hipStream_t s, const ConvLayout& lay) {
   const TileVariant& tv = variant(v);
   const size_t es = dtype_size(d.dtype);
+  if (tv.sched == -3) {
+    ConvArgs a;
+    a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.partial = nullptr;
+    a.N = d.n; a.C = d.c_in; a.H = d.h; a.W = d.w; a.O = d.c_out; a.KH = 1; a.KW = 1; a.stride = 1; a.pad = 0;
+    a.Ho = d.h; a.Wo = d.w;
+    a.K = lay.cp_in; a.Cp = lay.cp_in; a.Cop = lay.cp_out;
+    a.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
+    a.pool4 = 0; a.nhwc_out = 0;
+    a.HoWo = d.h * d.w;
+    a.P = d.n * a.HoWo;
+    a.x_bytes = (unsigned)((size_t)a.P * lay.cp_in * es);
+    a.w_bytes = (unsigned)((size_t)d.c_out * lay.cp_in * es);
+    a.act = d.act;
+    a.tiles_m = (d.c_out + tv.tile_m() - 1) / tv.tile_m();
+    a.tiles_p = (a.P + 63) / 64;
+    // persistent groups: as many as stay resident (LDS decides, at most 8 per compute unit), shared between
+    // the filter tiles; each walks over its share of the pixel tiles
+    const long lds = (long)tv.tile_m() * (tv.nr * 64 + 16);
+    long per_cu = (160 * 1024) / lds;
+    per_cu = per_cu > 8 ? 8 : (per_cu < 1 ? 1 : per_cu);
+    long workers = 256 * per_cu / a.tiles_m;
+    workers = workers < 1 ? 1 : (workers > a.tiles_p ? a.tiles_p : workers);
+    dim3 grid((unsigned)workers, (unsigned)a.tiles_m);
+    if (d.dtype == CPRUNE_F32) launch_conv_pw_f32(tv.patch_id, grid, s, a);
+    else if (d.dtype == CPRUNE_F16) launch_conv_pw_f16(tv.patch_id, grid, s, a);
+    else launch_conv_pw_bf16(tv.patch_id, grid, s, a);
+    CPRUNE_LAUNCH_CHECK();
+    return CPRUNE_OK;
+  }
   if (tv.sched == -2) {
     ConvArgs a;
     a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.partial = nullptr;

@@ -1,0 +1,10 @@
+// Instantiations of the short-reduction 1x1 kernel for __bf16 data.
+#include "conv_pw_kernel.hpp"
+
+namespace cprune {
+
+void launch_conv_pw_bf16(int id, dim3 grid, hipStream_t s, const ConvArgs& a) {
+  launch_pw<__bf16>(id, grid, s, a);
+}
+
+}  // namespace cprune
