@@ -343,6 +343,7 @@ struct NetLayer {
   bool alias = false;         // max-pool folded into its producer: no kernel, act is the producer's buffer
   bool map2x2 = false;        // 3x3 / stride 1 / pad 1 conv on a 2x2 map, run as one matrix over the whole map
   int fuse_dw = -1;           // 1x1 conv: index of the depthwise layer computed inside its kernel, or -1
+  int dw_ks = 1;              // ... and how many groups of four wavefronts share one pixel block there
   bool fused_away = false;    // depthwise conv that runs inside its consumer's kernel (no launch, no activation)
   int dw_reader = -1;         // depthwise conv that may run inside the 1x1 conv dw_reader's kernel
   int fuse_block = -1;        // 1x1 conv with fuse_dw set: index of the 1x1 expansion in front of that depthwise
@@ -467,9 +468,9 @@ static int net_run_dwproj(cprune_net* net, int i, int n, void* dst, hipStream_t 
   a.vec_out = (a.Cop % 4) == 0 ? 1 : 0;
   dim3 grid((unsigned)(n * a.tiles_y * a.tiles_x * a.tiles_m));
   int rc;
-  if (net->dtype == CPRUNE_F32) rc = launch_dwproj_f32(D.d.k, D.d.stride, mb, grid, s, a);
-  else if (net->dtype == CPRUNE_F16) rc = launch_dwproj_f16(D.d.k, D.d.stride, mb, grid, s, a);
-  else rc = launch_dwproj_bf16(D.d.k, D.d.stride, mb, grid, s, a);
+  if (net->dtype == CPRUNE_F32) rc = launch_dwproj_f32(D.d.k, D.d.stride, mb, P.dw_ks, grid, s, a);
+  else if (net->dtype == CPRUNE_F16) rc = launch_dwproj_f16(D.d.k, D.d.stride, mb, P.dw_ks, grid, s, a);
+  else rc = launch_dwproj_bf16(D.d.k, D.d.stride, mb, P.dw_ks, grid, s, a);
   if (rc != CPRUNE_OK) return rc;
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
@@ -843,16 +844,26 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     D.dw_reader = reader;
     const int mt = pd.c_out <= 32 ? 32 : (pd.c_out <= 64 ? 64 : 128);
     const long groups = (long)max_batch * ((D.h_out + 7) / 8) * ((D.w_out + 7) / 8) * ((pd.c_out + mt - 1) / mt);
+    // Few pixel blocks (small maps) leave one group of four wavefronts per compute unit, whose channel
+    // loop is a chain of waits: then 2 or 4 groups share a block and split the channel chunks.
+    const int ks_max = (dd.k == 3 && dd.stride == 1) ? 4 : 2;
+    P.dw_ks = groups <= 320 ? ks_max : (groups <= 640 ? 2 : 1);
     bool fuse = groups >= 512;
     if (tune) {
-      float ms[2] = {0.f, 0.f};
       const int pair[2] = {i, reader};
-      for (int form = 0; form < 2 && rc == CPRUNE_OK; ++form) {   // 0: two kernels, 1: fused
-        D.fused_away = form == 1;
-        P.fuse_dw = form == 1 ? i : -1;
-        rc = time_layers(net, pair, 2, max_batch, nullptr, s, &ms[form]);
+      float apart = 0.f, best = 0.f;
+      D.fused_away = false; P.fuse_dw = -1;
+      rc = time_layers(net, pair, 2, max_batch, nullptr, s, &apart);
+      D.fused_away = true; P.fuse_dw = i;
+      int best_ks = 1;
+      for (int ks = 1; ks <= ks_max && rc == CPRUNE_OK; ks *= 2) {
+        float ms = 0.f;
+        P.dw_ks = ks;
+        rc = time_layers(net, pair, 2, max_batch, nullptr, s, &ms);
+        if (ks == 1 || ms < best) { best = ms; best_ks = ks; }
       }
-      fuse = ms[1] < ms[0];
+      P.dw_ks = best_ks;
+      fuse = best < apart;
     }
     D.fused_away = fuse;
     P.fuse_dw = fuse ? i : -1;

@@ -115,11 +115,12 @@ struct DwProjArgs {
   int vec_out;
 };
 
-// k in {3, 5}, stride in {1, 2}, mb in {2, 4, 8} (16-filter blocks per tile); grid = one work-group
-// per (image, 8x8 output block, filter tile).  CPRUNE_ERR_UNSUPPORTED for other combinations.
-int launch_dwproj_f32(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a);
-int launch_dwproj_f16(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a);
-int launch_dwproj_bf16(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a);
+// k in {3, 5}, stride in {1, 2}, mb in {2, 4, 8} (16-filter blocks per tile), ks in {1, 2, 4} (groups of four
+// wavefronts per work-group that split the channel chunks; 4 only with k = 3 at stride 1); grid = one work-group per
+// (image, 8x8 output block, filter tile).  CPRUNE_ERR_UNSUPPORTED for other combinations.
+int launch_dwproj_f32(int k, int stride, int mb, int ks, dim3 grid, hipStream_t s, const DwProjArgs& a);
+int launch_dwproj_f16(int k, int stride, int mb, int ks, dim3 grid, hipStream_t s, const DwProjArgs& a);
+int launch_dwproj_bf16(int k, int stride, int mb, int ks, dim3 grid, hipStream_t s, const DwProjArgs& a);
 
 // A whole inverted-residual block in one kernel: 1x1 expansion, depthwise k x k, 1x1 projection, channels-last.
 struct MbConvArgs {

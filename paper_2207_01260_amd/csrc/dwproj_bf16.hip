@@ -3,8 +3,8 @@
 
 namespace cprune {
 
-int launch_dwproj_bf16(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a) {
-  return launch_dwproj<__bf16>(k, stride, mb, grid, s, a);
+int launch_dwproj_bf16(int k, int stride, int mb, int ks, dim3 grid, hipStream_t s, const DwProjArgs& a) {
+  return launch_dwproj<__bf16>(k, stride, mb, ks, grid, s, a);
 }
 
 }  // namespace cprune

@@ -3,8 +3,8 @@
 
 namespace cprune {
 
-int launch_dwproj_f32(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a) {
-  return launch_dwproj<float>(k, stride, mb, grid, s, a);
+int launch_dwproj_f32(int k, int stride, int mb, int ks, dim3 grid, hipStream_t s, const DwProjArgs& a) {
+  return launch_dwproj<float>(k, stride, mb, ks, grid, s, a);
 }
 
 }  // namespace cprune

@@ -14,14 +14,26 @@
 // layer; bias, shortcut add and activation of the projection run in the epilogue.
 // Values handed from the depthwise stage to the projection are rounded to the
 // activation type, as they are when the depthwise layer stores its output.
+//
+// On small maps a layer has few pixel blocks (a 14x14 map at batch 64: 256, one per compute
+// unit) and a long channel loop whose steps (global load -> LDS -> depthwise -> LDS ->
+// MFMA) wait for each other.  KS > 1 puts KS groups of four wavefronts on one pixel block:
+// group g takes chunks g, g + KS, ... with LDS buffers of its own, so the steps of KS chunks
+// overlap; the groups' sums meet in LDS at the end, in group order.
 #pragma once
 #include "conv_nhwc_kernel.hpp"
 
 namespace cprune {
 
-template <typename T, int K, int S, int MB, int KQ>
-__global__ __launch_bounds__(256) void dwproj_kernel(DwProjArgs a) {
-  constexpr int NT = 256;
+template <int K, int S, int MB, int KQ, int KS>
+constexpr int dwproj_lds_bytes() {
+  constexpr int PH = 7 * S + K, ROW = 64 * KQ + 16;
+  return KS * ((PH * PH + 64 + MB * 16) * ROW + K * K * 64 * KQ) + (KS > 1 ? MB * 4096 : 0);
+}
+
+template <typename T, int K, int S, int MB, int KQ, int KS>
+__global__ __launch_bounds__(256 * KS) void dwproj_kernel(DwProjArgs a) {
+  constexpr int NT = 256;                  // threads of one group
   constexpr int ES = (int)sizeof(T);
   constexpr int EPI = 16 / ES;             // elements per 16-byte quad
   constexpr int CC = 4 * EPI * KQ;         // expanded channels per chunk
@@ -35,14 +47,17 @@ __global__ __launch_bounds__(256) void dwproj_kernel(DwProjArgs a) {
   constexpr int NI_A = (MT * NQ + NT - 1) / NT;
   constexpr int NI_DW = (PT * NQ) / NT;    // depthwise items (pixel, quad) per thread
   static_assert((PT * NQ) % NT == 0 && K * K * NQ <= NT, "item counts");
-  static_assert(NPATCH * ROW + PT * ROW + MT * ROW + K * K * 64 * KQ <= 65536, "LDS budget");
+  constexpr int GROUP = NPATCH * ROW + PT * ROW + MT * ROW + K * K * 64 * KQ;   // LDS bytes of one group
+  static_assert(dwproj_lds_bytes<K, S, MB, KQ, KS>() <= 160 * 1024, "LDS budget");
 
-  __shared__ __attribute__((aligned(16))) unsigned char sIn[NPATCH * ROW];
-  __shared__ __attribute__((aligned(16))) unsigned char sB[PT * ROW];
-  __shared__ __attribute__((aligned(16))) unsigned char sA[MT * ROW];
-  __shared__ __attribute__((aligned(16))) unsigned char sW[K * K * 64 * KQ];
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int t = threadIdx.x & (NT - 1);
+  const int kgrp = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
+  unsigned char* sIn = lds + kgrp * GROUP;
+  unsigned char* sB = sIn + NPATCH * ROW;
+  unsigned char* sA = sB + PT * ROW;
+  unsigned char* sW = sA + MT * ROW;
 
-  const int t = threadIdx.x;
   const int lane = t & 63;
   const int wave = t >> 6;
   const int r = lane & 15, g4 = lane >> 4;
@@ -155,11 +170,15 @@ __global__ __launch_bounds__(256) void dwproj_kernel(DwProjArgs a) {
   int mb_count = (a.O - o0 + 15) / 16;
   mb_count = mb_count > MB ? MB : mb_count;
 
+  // group g takes chunks g, g + KS, ...: every group runs the same number of steps (a step past the last
+  // chunk loads zeros), so the barriers match
   const int nchunk = (a.Cpe + CC - 1) / CC;
+  const int nstep = (nchunk + KS - 1) / KS;
   auto main_loop = [&](auto mbc_tag) {
     constexpr int MBC = decltype(mbc_tag)::value;
-    gload(0);
-    for (int c = 0; c < nchunk; ++c) {
+    gload(kgrp * CC);
+    for (int step = 0; step < nstep; ++step) {
+      const int c = step * KS + kgrp;
       __syncthreads();              // previous chunk's MFMAs have read sA / sB, its depthwise pass sIn / sW
       lds_store();
       float bd[NI_DW][EPI];
@@ -168,7 +187,7 @@ __global__ __launch_bounds__(256) void dwproj_kernel(DwProjArgs a) {
 #pragma unroll
         for (int e = 0; e < EPI; ++e) bd[j][e] = bd_n[j][e];
       __syncthreads();
-      if (c + 1 < nchunk) gload((c + 1) * CC);
+      if (step + 1 < nstep) gload((c + KS) * CC);
       // depthwise: k x k window over the staged patch, fp32, bias, activation, rounded to T
 #pragma unroll
       for (int j = 0; j < NI_DW; ++j) {
@@ -213,6 +232,24 @@ __global__ __launch_bounds__(256) void dwproj_kernel(DwProjArgs a) {
     default: break;
   }
 
+  if constexpr (KS > 1) {
+    // the other groups hand their sums over one after the other through one exchange tile
+    float4_t* xch = (float4_t*)(lds + KS * GROUP) + (size_t)wave * (MB * 64) + lane;
+    for (int g = 1; g < KS; ++g) {
+      __syncthreads();
+      if (kgrp == g) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) xch[i * 64] = acc[i][0];
+      }
+      __syncthreads();
+      if (kgrp == 0) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) acc[i][0] += xch[i * 64];
+      }
+    }
+    if (kgrp != 0) return;
+  }
+
   // ---- epilogue of the projection ----
   ConvArgs e;
   e.bias = a.bp; e.res = a.res; e.y = a.y; e.O = a.O; e.Cop = a.Cop; e.act = a.act_out; e.vec_out = a.vec_out;
@@ -225,18 +262,29 @@ __global__ __launch_bounds__(256) void dwproj_kernel(DwProjArgs a) {
   }
 }
 
-// Instantiations: k in {3, 5}, stride in {1, 2}, MB in {2, 4, 8} (tile of 32 / 64 / 128 filters)
+// Instantiations: k in {3, 5}, stride in {1, 2}, MB in {2, 4, 8} (tile of 32 / 64 / 128 filters), KS in {1, 2, 4}
+// (4 only for the 3x3 window at stride 1: the 5x5 one needs more registers than 16 wavefronts leave, the
+// stride-2 patch more LDS than four groups leave)
 template <typename T>
-inline int launch_dwproj(int k, int stride, int mb, dim3 grid, hipStream_t s, const DwProjArgs& a) {
-#define CPRUNE_DWP(K_, S_, MB_)                                                                       \
-  if (k == K_ && stride == S_ && mb == MB_) {                                                         \
-    hipLaunchKernelGGL((dwproj_kernel<T, K_, S_, MB_, 1>), grid, dim3(256), 0, s, a);                 \
-    return CPRUNE_OK;                                                                                 \
+inline int launch_dwproj(int k, int stride, int mb, int ks, dim3 grid, hipStream_t s, const DwProjArgs& a) {
+#define CPRUNE_DWP(K_, S_, MB_, KS_)                                                                       \
+  if (k == K_ && stride == S_ && mb == MB_ && ks == KS_) {                                                 \
+    constexpr int lds = dwproj_lds_bytes<K_, S_, MB_, 1, KS_>();                                           \
+    static bool raised = false;   /* more than the default 64 KiB of LDS has to be asked for once */       \
+    if (lds > 65536 && !raised) {                                                                          \
+      CPRUNE_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&dwproj_kernel<T, K_, S_, MB_, 1, KS_>), \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));         \
+      raised = true;                                                                                       \
+    }                                                                                                      \
+    hipLaunchKernelGGL((dwproj_kernel<T, K_, S_, MB_, 1, KS_>), grid, dim3(256 * KS_), lds, s, a);         \
+    return CPRUNE_OK;                                                                                      \
   }
-  CPRUNE_DWP(3, 1, 2) CPRUNE_DWP(3, 1, 4) CPRUNE_DWP(3, 1, 8)
-  CPRUNE_DWP(3, 2, 2) CPRUNE_DWP(3, 2, 4) CPRUNE_DWP(3, 2, 8)
-  CPRUNE_DWP(5, 1, 2) CPRUNE_DWP(5, 1, 4) CPRUNE_DWP(5, 1, 8)
-  CPRUNE_DWP(5, 2, 2) CPRUNE_DWP(5, 2, 4) CPRUNE_DWP(5, 2, 8)
+#define CPRUNE_DWP3(K_, S_, KS_) CPRUNE_DWP(K_, S_, 2, KS_) CPRUNE_DWP(K_, S_, 4, KS_) CPRUNE_DWP(K_, S_, 8, KS_)
+  CPRUNE_DWP3(3, 1, 1) CPRUNE_DWP3(3, 1, 2) CPRUNE_DWP3(3, 1, 4)
+  CPRUNE_DWP3(3, 2, 1) CPRUNE_DWP3(3, 2, 2)
+  CPRUNE_DWP3(5, 1, 1) CPRUNE_DWP3(5, 1, 2)
+  CPRUNE_DWP3(5, 2, 1) CPRUNE_DWP3(5, 2, 2)
+#undef CPRUNE_DWP3
 #undef CPRUNE_DWP
   return CPRUNE_ERR_UNSUPPORTED;
 }
