@@ -36,6 +36,7 @@ TRAFFIC = {
     ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, 4): 8888483,     # conv3-6; algorithmic 6.4e6
     ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, 5): 9535513,     # conv3-7
     ("conv_patch_kernel<float, 1, 4, 4, 4, 1, 1>", 64, 2): 10282022,
+    ("conv_patch_kernel<float, 1, 4, 4, 4, 2, 1>", 64, 3): 11839806,    # conv8-10; algorithmic 4.1e6
 }
 
 
