@@ -266,7 +266,8 @@ int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out)
 int cprune_net_fuse_depthwise(cprune_net* net, int layer, int enable);
 int cprune_net_layer_fused(const cprune_net* net, int layer, int* fused_out);
 /* When the input of such a depthwise conv is a 1x1 / stride 1 conv that nobody else reads (the
- * expansion of an inverted-residual block, whose filters are the pruned ones), and the 1x1
+ * expansion of an inverted-residual block of MobileNetV2 / MnasNet1.0, Sec. 4.1 and Table 1 of the
+ * paper; its filters are the ones Sec. 3.5 prunes), and the 1x1
  * reader has at most 128 filters, all three layers can run as one kernel: the expanded
  * activations, the block's largest tensor, then never reach memory.  cprune_net_create decides
  * per block (by size, or by timing when tune != 0); this call overrides the decision for the
