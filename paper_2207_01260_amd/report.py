@@ -3,7 +3,10 @@ on CIFAR-sized inputs, ResNet-18, MobileNetV2 and MnasNet1.0 on ImageNet-sized i
 synthetic, channel-pruned network, plus the single pruned layer and the measured ceilings of
 the device.  One JSON object per line.
 
-    python -m paper_2207_01260_amd.report [--quick]
+    python -m paper_2207_01260_amd.report [--quick] [--only NAME [--batch N] [--dtype f32|f16|bf16]]
+
+--only keeps the networks whose name contains NAME (and, with --batch / --dtype, that one run) and
+skips the device ceilings and the single layer: the form a profiler run of one workload uses.
 
 For each network and batch: images/s and ms per forward (at batch 1 also with the caches scrubbed
 before every run: back-to-back replays keep the weights in the last-level cache) (HIP graph replay or eager launches,
@@ -131,12 +134,33 @@ def single_layer_report(steps):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--quick", action="store_true", help="fewer timed steps, small batches only")
+    ap.add_argument("--only", default="", help="only the networks whose name contains this (case-insensitive)")
+    ap.add_argument("--batch", type=int, default=0, help="with --only: only this batch size")
+    ap.add_argument("--dtype", default="", choices=["", "f32", "f16", "bf16"], help="with --only: only this dtype")
     args = ap.parse_args()
     steps = 20 if args.quick else 100
     props = torch.cuda.get_device_properties(0)
     print(json.dumps({"device": props.name, "compute_units": props.multi_processor_count,
                       "clock_mhz": getattr(props, "clock_rate", 0) // 1000,
                       "hbm_gib": round(props.total_memory / 2 ** 30, 1)}), flush=True)
+    if not args.only:
+        report_device(steps)
+    cases = [("pruned VGG-16 32x32", synth.vgg16(10, 32), 2, [(1, B.F32), (64, B.F32), (1, B.F16), (64, B.F16)]),
+             ("pruned ResNet-18 224x224", synth.resnet18(1000, 224), 3, [(1, B.F32), (32, B.F32), (1, B.BF16), (32, B.BF16)]),
+             ("pruned MobileNetV2 224x224", synth.mobilenetv2(1000, 224), 4, [(1, B.F32), (64, B.F32)]),
+             ("pruned MnasNet1.0 224x224", synth.mnasnet(1000, 224), 6, [(1, B.F32), (64, B.F32)])]
+    for name, net, cid, runs in cases:
+        if args.only and args.only.lower() not in name.lower():
+            continue
+        for batch, dtype in runs:
+            if args.quick and not args.only and batch > 1 and "VGG" not in name:
+                continue
+            if args.only and ((args.batch and batch != args.batch) or (args.dtype and DT_NAME[dtype] != args.dtype)):
+                continue
+            print(json.dumps(net_report(name, net, cid, batch, dtype, steps)), flush=True)
+
+
+def report_device(steps):
     ceil = {"mfma_f32_tflops": round(B.cprune_probe_mfma(B.F32), 1),
             "mfma_f16_tflops": round(B.cprune_probe_mfma(B.F16), 1),
             "mfma_bf16_tflops": round(B.cprune_probe_mfma(B.BF16), 1),
@@ -145,15 +169,6 @@ def main():
     print(json.dumps({"measured_ceilings": ceil}), flush=True)
     for row in single_layer_report(steps):
         print(json.dumps(row), flush=True)
-    cases = [("pruned VGG-16 32x32", synth.vgg16(10, 32), 2, [(1, B.F32), (64, B.F32), (1, B.F16), (64, B.F16)]),
-             ("pruned ResNet-18 224x224", synth.resnet18(1000, 224), 3, [(1, B.F32), (32, B.F32), (1, B.BF16), (32, B.BF16)]),
-             ("pruned MobileNetV2 224x224", synth.mobilenetv2(1000, 224), 4, [(1, B.F32), (64, B.F32)]),
-             ("pruned MnasNet1.0 224x224", synth.mnasnet(1000, 224), 6, [(1, B.F32), (64, B.F32)])]
-    for name, net, cid, runs in cases:
-        for batch, dtype in runs:
-            if args.quick and batch > 1 and "VGG" not in name:
-                continue
-            print(json.dumps(net_report(name, net, cid, batch, dtype, steps)), flush=True)
 
 
 if __name__ == "__main__":
