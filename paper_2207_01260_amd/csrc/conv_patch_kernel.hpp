@@ -210,8 +210,10 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
       // the operands of round r + 1 are fetched from LDS while round r is multiplied;
       // wave group kgrp takes rounds [kgrp * NR / KS, (kgrp + 1) * NR / KS)
       constexpr int NR = 9 * KQ;
-      auto rounds = [&](auto lo_tag, auto hi_tag) {
-        constexpr int LO = decltype(lo_tag)::value, HI = decltype(hi_tag)::value;
+      // ST = 1: every round of [LO, HI).  ST = KQ: only the first 64-byte round of each tap, for a
+      // last chunk whose channels end inside that round (the rest of the chunk is zero fill)
+      auto rounds = [&](auto lo_tag, auto hi_tag, auto step_tag) {
+        constexpr int LO = decltype(lo_tag)::value, HI = decltype(hi_tag)::value, ST = decltype(step_tag)::value;
         // fragments are fetched PF rounds ahead of their use (PF + 1 register sets)
         constexpr int PF = 1;
         uint4 af[PF + 1][MB], bf[PF + 1][NB];
@@ -225,25 +227,30 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
         };
 #pragma unroll
         for (int p = 0; p < PF; ++p)
-          if (LO + p < HI) fetch(LO + p, af[p], bf[p]);
+          if (LO + p * ST < HI) fetch(LO + p * ST, af[p], bf[p]);
 #pragma unroll
-        for (int rnd = LO; rnd < HI; ++rnd) {
-          if (rnd + PF < HI) fetch(rnd + PF, af[(rnd + PF - LO) % (PF + 1)], bf[(rnd + PF - LO) % (PF + 1)]);
+        for (int rnd = LO; rnd < HI; rnd += ST) {
+          const int idx = (rnd - LO) / ST;
+          if (rnd + PF * ST < HI) fetch(rnd + PF * ST, af[(idx + PF) % (PF + 1)], bf[(idx + PF) % (PF + 1)]);
           // Multi-image tiles serve small maps, whose grids leave one wavefront per SIMD: there
           // the fetch is pinned ahead of the multiplies (left alone, the scheduler sinks every LDS
           // read to just before its first use and the four wavefronts take turns on the LDS and
           // the matrix pipes).  With many resident wavefronts the scheduler's own order is faster.
           if constexpr (NI > 1) __builtin_amdgcn_sched_barrier(0);
-          mma_round<T, MBC, NB, MB, NS>(af[(rnd - LO) % (PF + 1)], bf[(rnd - LO) % (PF + 1)], accs, rnd);
+          mma_round<T, MBC, NB, MB, NS>(af[idx % (PF + 1)], bf[idx % (PF + 1)], accs, idx);
           if constexpr (NI > 1) __builtin_amdgcn_sched_barrier(0);
         }
       };
+      using One = std::integral_constant<int, 1>;
       if constexpr (KS == 1) {
-        rounds(std::integral_constant<int, 0>{}, std::integral_constant<int, NR>{});
+        if (KQ > 1 && c + 1 == nchunk && (a.Cp - c * CC) * ES <= 64)
+          rounds(std::integral_constant<int, 0>{}, std::integral_constant<int, NR>{}, std::integral_constant<int, KQ>{});
+        else
+          rounds(std::integral_constant<int, 0>{}, std::integral_constant<int, NR>{}, One{});
       } else {
         constexpr int MID = (NR + 1) / 2;
-        if (kgrp == 0) rounds(std::integral_constant<int, 0>{}, std::integral_constant<int, MID>{});
-        else rounds(std::integral_constant<int, MID>{}, std::integral_constant<int, NR>{});
+        if (kgrp == 0) rounds(std::integral_constant<int, 0>{}, std::integral_constant<int, MID>{}, One{});
+        else rounds(std::integral_constant<int, MID>{}, std::integral_constant<int, NR>{}, One{});
       }
     }
   };
