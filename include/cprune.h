@@ -138,6 +138,9 @@ typedef struct {
  * sched -3: channels-last 1x1 / stride 1 layers with a short reduction (at most 384 bytes per
  * pixel): persistent work-groups keep a tile of at most 128 filters in local memory and stream
  * 64-pixel tiles through it.
+ * sched -4: channels-last 3x3 / stride 1 / pad 1 layers on maps of at most 16 x 16: 16 filters x
+ * tile_p pixels (4 x 4 blocks) per work-group, one wavefront per (block, slice of the
+ * reduction), the slices summed inside the group; chosen for small maps with many channels.
  * Ids are 0..n-1
  * and the same for every shape; a variant that cannot run a given shape is
  * CPRUNE_ERR_UNSUPPORTED. */

@@ -215,6 +215,8 @@ extern "C" int cprune_tile_variant_name(int v, int channels_last, cprune_dtype d
   if (tv.sched >= 0)
     n = snprintf(buf, buf_bytes, "%s<%s, %d, %d, %d, %d, %d>", channels_last ? "conv_nhwc_kernel" : "conv_igemm_kernel", t,
                  tv.wm, tv.wn, tv.mb, tv.nb, tv.kq);
+  else if (tv.sched == -4)
+    n = snprintf(buf, buf_bytes, "conv_wave_kernel<%s, %d, %d, %d>", t, tv.wn, tv.nb, tv.ks);
   else if (tv.sched == -3)
     n = snprintf(buf, buf_bytes, "conv_pw_kernel<%s, %d, %d>", t, tv.mb, tv.nr);
   else if (tv.sched == -2)
@@ -350,6 +352,8 @@ struct NetLayer {
                               // layer when the whole block (expansion, depthwise, this projection) is one kernel
   int block_expand = -1;      // depthwise conv: the expansion layer that may join it and dw_reader in one kernel
   void* w_stem = nullptr;     // weights packed for the first-layer kernel
+  void* w_wave = nullptr;     // 3x3 / stride 1 / pad 1 layer on a small map: weights once more, packed for the
+                              // independent-wavefront kernel
   bool stem = false;          // nchw_in layer that runs the first-layer kernel (whole reduction in LDS)
   int stem_ok = 0;            // that kernel exists for the layer's window and stride
   bool nchw_in = false;       // dense conv on the network input: reads the caller's NCHW tensor and its own
@@ -401,6 +405,7 @@ static cprune_conv_desc layer_conv_desc(const cprune_net& net, const NetLayer& L
 static ConvLayout layer_layout(const NetLayer& L) {
   ConvLayout lay;
   lay.nhwc = 1; lay.cp_in = L.cp_in; lay.cp_out = L.cp_out; lay.pool = L.fused_pool ? 1 : 0;
+  lay.w_wave = L.w_wave;
   if (L.nchw_in) { lay.nhwc = 0; lay.nhwc_out = 1; lay.cp_in = 0; return lay; }
   if (L.map2x2) {
     lay.cp_in = 4 * L.cp_in;
@@ -777,6 +782,15 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
       hipError_t e = hipMemsetAsync(net->x_cl, 0, ib, s);
       if (e != hipSuccess) { set_last_hip_error(e); rc = CPRUNE_ERR_DEVICE; }
     }
+  }
+  // 3x3 layers on small maps: a second copy of the weights in the operand order of the kernel made for them
+  for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
+    NetLayer& L = net->layers[i];
+    const cprune_layer_desc& d = L.d;
+    if (!(d.kind == CPRUNE_LAYER_CONV && d.groups == 1 && d.k == 3 && d.stride == 1 && d.pad == 1)) continue;
+    if (L.map2x2 || L.nchw_in || L.h_in < 3 || L.w_in < 3 || L.h_in > 16 || L.w_in > 16) continue;
+    rc = dev_alloc(wave_packed_bytes(d.c_out, L.cp_in, dtype), &L.w_wave);
+    if (rc == CPRUNE_OK) rc = launch_repack_wave(L.w, d.c_out, L.cp_in, dtype, L.w_wave, s);
   }
   // variant per dense layer
   for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {

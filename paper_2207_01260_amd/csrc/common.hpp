@@ -38,7 +38,9 @@ struct TileVariant {
   int sched;    // scheduling mode: 0 = one tile per work-group, n = runs for n * 256 groups,
                 // -1 = 3x3 spatial-patch kernel (one th x tw pixel block per work-group),
                 // -2 = reduction-split kernel (16 filters x nb pixel blocks per work-group),
-                // -3 = short-reduction 1x1 kernel (persistent groups, filter tile resident in LDS)
+                // -3 = short-reduction 1x1 kernel (persistent groups, filter tile resident in LDS),
+                // -4 = independent-wavefront 3x3 kernel (16 filters x wn * nb 4x4 pixel blocks x ks slices of
+                //      the reduction per work-group; wn * ks wavefronts of nb blocks each)
   int th = 0, tw = 0, ni = 1, patch_id = -1;
   int blk32 = 0;  // patch kernels: 1 = 32x32 MFMA blocks (patch_id then indexes that kernel's list)
   int ks = 1;     // patch kernels on 16x16 blocks: wave groups per tile
@@ -60,6 +62,8 @@ struct ConvLayout {
   int cp_out = 0;
   int nhwc_out = 0;  // with nhwc = 0: NCHW input and OIHW weights (the boundary's layout) but a channels-last
                      // output of channel stride cp_out: the first layer of a network handle
+  const void* w_wave = nullptr;  // the weights once more, in the order of the independent-wavefront 3x3
+                                 // kernel (launch_repack_wave); that kernel runs only where this is set
   int pool = 0;  // 1: channels-last 3x3 layer with a 2x2/2 max-pool fused behind the activation (patch kernels);
                  // 2: rows are (channel, position of a 2x2 map) and each group of four rows is reduced to its
                  //    maximum behind the activation; cp_out is the stride of the pooled output
@@ -96,6 +100,10 @@ int launch_repack_weights(const void* w, int o, int c, int khw, int cp, int dt, 
 // 3x3 / stride 1 / pad 1 on a 2x2 map as one matrix over the whole map: w [o][c][3][3] ->
 // [rows][4 * cp_in], column (input pixel, channel), row (output pixel, channel) with channel
 // stride cp_out, or (channel, output pixel) when rows_by_channel; bias [o] -> [4 * cp_out] alike
+// w [o][9][cp] (channels-last 3x3 weights) -> the operand order of the independent-wavefront 3x3 kernel:
+// [filter tile of 16][64-byte channel chunk][tap][lane][16 bytes], zero padded; wave_packed_bytes: its size
+size_t wave_packed_bytes(int o, int cp, int dt);
+int launch_repack_wave(const void* w_khwc, int o, int cp, int dt, void* y, hipStream_t s);
 int launch_repack_map2x2(const void* w, const float* bias, int o, int c, int cp_in, int cp_out,
                          int rows_by_channel, int dt, void* w_out, float* bias_out, hipStream_t s);
 

@@ -2,6 +2,7 @@
 // mode), what each variant supports and needs, and the launch.
 #include "conv_ksplit_kernel.hpp"
 #include "conv_pw_kernel.hpp"
+#include "conv_wave_kernel.hpp"
 #include "conv_patch32_kernel.hpp"
 
 namespace cprune {
@@ -19,6 +20,7 @@ const int kScheds[] = {0, 1, 2, 3, 4, 6, 8};
 constexpr int kNumScheds = sizeof(kScheds) / sizeof(kScheds[0]);
 constexpr int kMinUnitsPerGroup = 4;
 constexpr long kMaxKsplitGroups = 8192;
+constexpr int kMaxWaveMap = 16;
 
 unsigned magic_for(unsigned d) {
   if (d <= 1) return 0;
@@ -61,11 +63,11 @@ Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv, const ConvLayou
 
 }  // namespace
 
-int num_variants() { return kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw; }
+int num_variants() { return kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw + kNumWave; }
 
 namespace {
 struct VariantTable {
-  TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw];
+  TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw + kNumWave];
   VariantTable() {
 #define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_, KQ_, KS_)                                 \
     {                                                                         \
@@ -99,6 +101,14 @@ struct VariantTable {
     }
     CPRUNE_PW_LIST(CPRUNE_PW_ROW)
 #undef CPRUNE_PW_ROW
+#define CPRUNE_WAVE_ROW(ID, NP_, NB_, KS_)                                                 \
+    {                                                                                      \
+      TileVariant& kv = table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw + ID]; \
+      kv.wm = 1; kv.wn = NP_; kv.mb = 1; kv.nb = NB_; kv.kq = 1; kv.sched = -4;            \
+      kv.th = 4; kv.tw = 4; kv.patch_id = ID; kv.ks = KS_;                                 \
+    }
+    CPRUNE_WAVE_LIST(CPRUNE_WAVE_ROW)
+#undef CPRUNE_WAVE_ROW
     for (int t = 0; t < kNumTiles; ++t)
       for (int s = 0; s < kNumScheds; ++s) {
         table[t * kNumScheds + s] = kTiles[t];
@@ -117,6 +127,13 @@ bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
   if (v < 0 || v >= num_variants()) return false;
   if (d.groups != 1) return false;
   const TileVariant& tv = variant(v);
+  if (tv.sched == -4) {
+    // 3x3 / stride 1 / pad 1 on small maps (every wavefront fetches its own weights: with many pixels the
+    // tiled kernels, which share them through LDS, are the ones to use)
+    if (!(lay.nhwc && lay.w_wave && d.kh == 3 && d.kw == 3 && d.stride == 1 && d.pad == 1)) return false;
+    if (lay.pool == 2 || (lay.pool && ((d.h | d.w) & 1))) return false;
+    return d.h >= 3 && d.w >= 3 && d.h <= kMaxWaveMap && d.w <= kMaxWaveMap;
+  }
   if (tv.sched == -3) {
     // 1x1 / stride 1, no pool; exactly one (mb, nr) pair serves a shape: the smallest filter tile that
     // holds min(c_out, 128) filters and the smallest round count that holds the reduction
@@ -177,6 +194,30 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
                       const void* residual, void* y, int v, void* ws, hipStream_t s, const ConvLayout& lay) {
   const TileVariant& tv = variant(v);
   const size_t es = dtype_size(d.dtype);
+  if (tv.sched == -4) {
+    PatchArgs pa;
+    pa.x = x; pa.w = lay.w_wave; pa.bias = bias; pa.res = residual; pa.y = y;
+    pa.N = d.n; pa.H = d.h; pa.W = d.w; pa.O = d.c_out; pa.Cp = lay.cp_in; pa.Cop = lay.cp_out;
+    pa.pool = lay.pool;
+    pa.tiles_y = (d.h + 3) / 4;
+    pa.tiles_x = (d.w + 3) / 4;
+    const long blocks = (long)d.n * pa.tiles_y * pa.tiles_x;
+    pa.tiles_n = (int)((blocks + tv.wn * tv.nb - 1) / (tv.wn * tv.nb));   // groups along the block list
+    pa.tiles_m = (d.c_out + 15) / 16;
+    pa.x_bytes = (unsigned)((size_t)d.n * lay.cp_in * d.h * d.w * es);
+    pa.w_bytes = (unsigned)wave_packed_bytes(d.c_out, lay.cp_in, d.dtype);
+    pa.act = d.act;
+    pa.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
+    pa.m_major = pa.w_bytes > pa.x_bytes ? 1 : 0;
+    dim3 grid((unsigned)(pa.tiles_n * pa.tiles_m));
+    int rc;
+    if (d.dtype == CPRUNE_F32) rc = launch_conv_wave_f32(tv.patch_id, grid, s, pa);
+    else if (d.dtype == CPRUNE_F16) rc = launch_conv_wave_f16(tv.patch_id, grid, s, pa);
+    else rc = launch_conv_wave_bf16(tv.patch_id, grid, s, pa);
+    if (rc != CPRUNE_OK) return rc;
+    CPRUNE_LAUNCH_CHECK();
+    return CPRUNE_OK;
+  }
   if (tv.sched == -3) {
     ConvArgs a;
     a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.partial = nullptr;

@@ -358,6 +358,28 @@ __global__ __launch_bounds__(256) void repack_weights_kernel(const T* __restrict
   y[i] = v;
 }
 
+// [o][9][cp] -> the order in which the independent-wavefront 3x3 kernel's lanes fetch their MFMA
+// operands: [filter tile of 16][64-byte channel chunk][tap][lane = quad * 16 + filter][16 bytes], so
+// that one wavefront-wide load reads 1 KiB of consecutive memory; zero past the last filter / channel
+template <typename T>
+__global__ __launch_bounds__(256) void repack_wave_kernel(const T* __restrict__ w, T* __restrict__ y, long total,
+                                                          int o_count, int cp, int nchunk) {
+  constexpr int EPI = 16 / (int)sizeof(T);
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;   // one element of the output
+  if (i >= total) return;
+  const int e = (int)(i % EPI);
+  long q = i / EPI;
+  const int lane = (int)(q & 63); q >>= 6;
+  const int tap = (int)(q % 9); q /= 9;
+  const int chunk = (int)(q % nchunk);
+  const long tm = q / nchunk;
+  const long o = tm * 16 + (lane & 15);
+  const int ch = chunk * 4 * EPI + (lane >> 4) * EPI + e;
+  T v = (T)0.0f;
+  if (o < o_count && ch < cp) v = w[(o * 9 + tap) * cp + ch];
+  y[i] = v;
+}
+
 // Every input pixel of a 2x2 map lies inside the 3x3 window (pad 1) of every output pixel, so
 // the layer is one dense matrix from the whole input map to the whole output map: the tap that
 // links input pixel (iy, ix) to output pixel (oy, ox) is (iy - oy + 1, ix - ox + 1).
@@ -576,6 +598,21 @@ int launch_repack_weights(const void* w, int o, int c, int khw, int cp, int dt, 
   const long total = (long)o * khw * cp;
   CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_weights_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w,
                                          (T*)y, total, c, khw, cp));
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+size_t wave_packed_bytes(int o, int cp, int dt) {
+  const int cc = dt == CPRUNE_F32 ? 16 : 32;   // channels per 64-byte chunk
+  return (size_t)((o + 15) / 16) * ((cp + cc - 1) / cc) * 9 * 1024;
+}
+
+int launch_repack_wave(const void* w_khwc, int o, int cp, int dt, void* y, hipStream_t s) {
+  const int cc = dt == CPRUNE_F32 ? 16 : 32;
+  const int nchunk = (cp + cc - 1) / cc;
+  const long total = (long)(wave_packed_bytes(o, cp, dt) / dtype_size(dt));
+  CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_wave_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w_khwc,
+                                         (T*)y, total, o, cp, nchunk));
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }

@@ -42,7 +42,7 @@ def test_variant_table():
     seen = set()
     for v in range(nv):
         tm, tp, sk = B.cprune_tile_variant_info(v)
-        assert tm % 16 == 0 and tp % 16 == 0 and sk >= -3
+        assert tm % 16 == 0 and tp % 16 == 0 and sk >= -4
         seen.add((tm, tp, sk))
     with pytest.raises(B.CPruneError):
         B.cprune_tile_variant_info(nv)
