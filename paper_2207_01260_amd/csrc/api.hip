@@ -352,6 +352,7 @@ struct NetLayer {
                               // layer when the whole block (expansion, depthwise, this projection) is one kernel
   int block_expand = -1;      // depthwise conv: the expansion layer that may join it and dw_reader in one kernel
   void* w_stem = nullptr;     // weights packed for the first-layer kernel
+  void* w_rows = nullptr;     // layer the reduction-split kernel can run: weights once more, in its operand order
   void* w_wave = nullptr;     // 3x3 / stride 1 / pad 1 layer on a small map: weights once more, packed for the
                               // independent-wavefront kernel
   bool stem = false;          // nchw_in layer that runs the first-layer kernel (whole reduction in LDS)
@@ -406,6 +407,7 @@ static ConvLayout layer_layout(const NetLayer& L) {
   ConvLayout lay;
   lay.nhwc = 1; lay.cp_in = L.cp_in; lay.cp_out = L.cp_out; lay.pool = L.fused_pool ? 1 : 0;
   lay.w_wave = L.w_wave;
+  lay.w_rows = L.w_rows;
   if (L.nchw_in) { lay.nhwc = 0; lay.nhwc_out = 1; lay.cp_in = 0; return lay; }
   if (L.map2x2) {
     lay.cp_in = 4 * L.cp_in;
@@ -791,6 +793,20 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     if (L.map2x2 || L.nchw_in || L.h_in < 3 || L.w_in < 3 || L.h_in > 16 || L.w_in > 16) continue;
     rc = dev_alloc(wave_packed_bytes(d.c_out, L.cp_in, dtype), &L.w_wave);
     if (rc == CPRUNE_OK) rc = launch_repack_wave(L.w, d.c_out, L.cp_in, dtype, L.w_wave, s);
+  }
+  // layers the reduction-split kernel can run (1x1 / stride 1, fully connected, 2x2 maps as one matrix; few
+  // pixels): likewise a copy in its operand order
+  for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
+    NetLayer& L = net->layers[i];
+    if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1)) || L.nchw_in) continue;
+    const cprune_conv_desc cd = layer_conv_desc(*net, L, max_batch);
+    const ConvLayout lay = layer_layout(L);
+    bool any = false;
+    for (int v = 0; v < num_variants() && !any; ++v) any = variant(v).sched == -2 && variant_supports(cd, v, lay);
+    if (!any) continue;
+    const int k = lay.cp_in * cd.kh * cd.kw;
+    rc = dev_alloc(rows_packed_bytes(cd.c_out, k, dtype), &L.w_rows);
+    if (rc == CPRUNE_OK) rc = launch_repack_rows(L.w, cd.c_out, k, dtype, L.w_rows, s);
   }
   // variant per dense layer
   for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {

@@ -64,6 +64,8 @@ struct ConvLayout {
                      // output of channel stride cp_out: the first layer of a network handle
   const void* w_wave = nullptr;  // the weights once more, in the order of the independent-wavefront 3x3
                                  // kernel (launch_repack_wave); that kernel runs only where this is set
+  const void* w_rows = nullptr;  // the weights once more as [16-row tile][64-byte round of the reduction][lane][16
+                                 // bytes] (launch_repack_rows): the reduction-split kernel reads these when set
   int pool = 0;  // 1: channels-last 3x3 layer with a 2x2/2 max-pool fused behind the activation (patch kernels);
                  // 2: rows are (channel, position of a 2x2 map) and each group of four rows is reduced to its
                  //    maximum behind the activation; cp_out is the stride of the pooled output
@@ -104,6 +106,9 @@ int launch_repack_weights(const void* w, int o, int c, int khw, int cp, int dt, 
 // [filter tile of 16][64-byte channel chunk][tap][lane][16 bytes], zero padded; wave_packed_bytes: its size
 size_t wave_packed_bytes(int o, int cp, int dt);
 int launch_repack_wave(const void* w_khwc, int o, int cp, int dt, void* y, hipStream_t s);
+// w [rows][k], k contiguous -> the operand order of the reduction-split kernel, zero padded; rows_packed_bytes: size
+size_t rows_packed_bytes(int rows, int k, int dt);
+int launch_repack_rows(const void* w, int rows, int k, int dt, void* y, hipStream_t s);
 int launch_repack_map2x2(const void* w, const float* bias, int o, int c, int cp_in, int cp_out,
                          int rows_by_channel, int dt, void* w_out, float* bias_out, hipStream_t s);
 

@@ -68,6 +68,7 @@ struct ConvArgs {
   int slabs;          // reduction slabs per output tile
   int units;          // tiles * slabs: the work, in slab iterations
   int units_per_wg;   // contiguous run of units each work-group takes
+  int w_packed = 0;   // reduction-split kernel: w is in fragment order, [16-row tile][round][lane][16 bytes]
 };
 
 constexpr unsigned kOutOfRange = 0x80000000u;  // beyond any buffer this kernel accepts

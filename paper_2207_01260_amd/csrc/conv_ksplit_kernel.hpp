@@ -47,7 +47,12 @@ __global__ __launch_bounds__(64 * KW) void conv_ksplit_kernel(ConvArgs a) {
   const int rounds = (int)((row_bytes + 63) / 64);
   const int lo = (int)((long)wave * rounds / KW), hi = (int)((long)(wave + 1) * rounds / KW);
 
-  const unsigned a_off = (o0 + r < a.O) ? (unsigned)(o0 + r) * row_bytes + g4 * 16 : kOutOfRange;
+  // weights: rows of the reduction, or (w_packed) the fragment-ordered copy, where one wavefront-wide load is
+  // 1 KiB of consecutive memory instead of 16 half cache lines
+  const unsigned a_off = a.w_packed ? (unsigned)lane * 16u
+                                    : ((o0 + r < a.O) ? (unsigned)(o0 + r) * row_bytes + g4 * 16 : kOutOfRange);
+  const unsigned a_tile = a.w_packed ? (unsigned)(tile_m * rounds) * 1024u : 0u;
+  const unsigned a_step = a.w_packed ? 1024u : 64u;
   unsigned b_off[NB];
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
@@ -68,7 +73,7 @@ __global__ __launch_bounds__(64 * KW) void conv_ksplit_kernel(ConvArgs a) {
     for (int u = 0; u < U; ++u) {
       const int rnd = r0 + u;
       const unsigned inval = (unsigned)(rnd >= hi || (unsigned)rnd * 64 + g4 * 16 >= row_bytes) << 31;
-      fa[u][0] = load_b128(wr, a_off | inval, (unsigned)rnd * 64);
+      fa[u][0] = load_b128(wr, a_off | inval, a_tile + (unsigned)rnd * a_step);
 #pragma unroll
       for (int j = 0; j < NB; ++j) fb[u][j] = load_b128(xr, b_off[j] | inval, (unsigned)rnd * 64);
     }

@@ -266,6 +266,11 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     a.act = d.act;
     a.tiles_m = (d.c_out + 15) / 16;
     a.tiles_p = (a.P + tv.tile_p() - 1) / tv.tile_p();
+    if (lay.w_rows) {
+      a.w = lay.w_rows;
+      a.w_bytes = (unsigned)rows_packed_bytes(d.c_out, a.K, d.dtype);
+      a.w_packed = 1;
+    }
     dim3 grid((unsigned)(a.tiles_m * a.tiles_p));
     if (d.dtype == CPRUNE_F32) launch_conv_ksplit_f32(tv.patch_id, grid, s, a);
     else if (d.dtype == CPRUNE_F16) launch_conv_ksplit_f16(tv.patch_id, grid, s, a);

@@ -380,6 +380,26 @@ __global__ __launch_bounds__(256) void repack_wave_kernel(const T* __restrict__ 
   y[i] = v;
 }
 
+// [rows][k] (k contiguous) -> the order in which the reduction-split kernel's lanes fetch their MFMA
+// operands: [16-row tile][64-byte round of k][lane = quad * 16 + row][16 bytes]; zero past the last row / k
+template <typename T>
+__global__ __launch_bounds__(256) void repack_rows_kernel(const T* __restrict__ w, T* __restrict__ y, long total,
+                                                          int rows, int k, int rounds) {
+  constexpr int EPI = 16 / (int)sizeof(T);
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;   // one element of the output
+  if (i >= total) return;
+  const int e = (int)(i % EPI);
+  long q = i / EPI;
+  const int lane = (int)(q & 63); q >>= 6;
+  const int rnd = (int)(q % rounds);
+  const long tm = q / rounds;
+  const long row = tm * 16 + (lane & 15);
+  const int kk = rnd * 4 * EPI + (lane >> 4) * EPI + e;
+  T v = (T)0.0f;
+  if (row < rows && kk < k) v = w[row * k + kk];
+  y[i] = v;
+}
+
 // Every input pixel of a 2x2 map lies inside the 3x3 window (pad 1) of every output pixel, so
 // the layer is one dense matrix from the whole input map to the whole output map: the tap that
 // links input pixel (iy, ix) to output pixel (oy, ox) is (iy - oy + 1, ix - ox + 1).
@@ -613,6 +633,21 @@ int launch_repack_wave(const void* w_khwc, int o, int cp, int dt, void* y, hipSt
   const long total = (long)(wave_packed_bytes(o, cp, dt) / dtype_size(dt));
   CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_wave_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w_khwc,
                                          (T*)y, total, o, cp, nchunk));
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+size_t rows_packed_bytes(int rows, int k, int dt) {
+  const size_t per_round = 64 / dtype_size(dt);
+  return (size_t)((rows + 15) / 16) * ((k + per_round - 1) / per_round) * 1024;
+}
+
+int launch_repack_rows(const void* w, int rows, int k, int dt, void* y, hipStream_t s) {
+  const int per_round = (int)(64 / dtype_size(dt));
+  const int rounds = (k + per_round - 1) / per_round;
+  const long total = (long)(rows_packed_bytes(rows, k, dt) / dtype_size(dt));
+  CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_rows_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w, (T*)y,
+                                         total, rows, k, rounds));
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }
