@@ -21,6 +21,7 @@
 //
 // Same MFMA blocks, lane layout and k-permutation as the other dense kernels.
 #pragma once
+#include <atomic>
 #include "conv_patch_kernel.hpp"
 
 namespace cprune {
@@ -246,11 +247,11 @@ inline int launch_wave(int id, dim3 grid, hipStream_t s, const PatchArgs& a) {
   case ID: {                                                                                               \
     constexpr size_t lds = wave_lds_bytes(NP_, NB_, KS_);                                                  \
     static_assert(lds <= 160 * 1024, "patches (the sums at the end need less)");                           \
-    static bool raised = false;   /* more than the default 64 KiB of LDS has to be asked for once */       \
-    if (lds > 65536 && !raised) {                                                                          \
+    static std::atomic<bool> raised{false};   /* more than the default 64 KiB of LDS has to be asked for once */ \
+    if (lds > 65536 && !raised.load(std::memory_order_relaxed)) {                                             \
       CPRUNE_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wave_kernel<T, NP_, NB_, KS_>), \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));           \
-      raised = true;                                                                                       \
+      raised.store(true, std::memory_order_relaxed);                                                          \
     }                                                                                                      \
     hipLaunchKernelGGL((conv_wave_kernel<T, NP_, NB_, KS_>), grid, dim3(64 * NP_ * KS_), lds, s, a);       \
     break;                                                                                                 \

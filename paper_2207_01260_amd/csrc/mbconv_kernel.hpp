@@ -26,6 +26,7 @@
 //
 // Same MFMA blocks, lane layout and k-permutation as the other dense kernels.
 #pragma once
+#include <atomic>
 #include "conv_nhwc_kernel.hpp"
 
 namespace cprune {
@@ -304,11 +305,11 @@ template <typename T>
 inline int launch_mbconv(int k, int stride, int mb, dim3 grid, size_t lds_bytes, hipStream_t s, const MbConvArgs& a) {
 #define CPRUNE_MBC(K_, S_, MB_)                                                                         \
   if (k == K_ && stride == S_ && mb == MB_) {                                                           \
-    static bool raised = false;   /* more than the default 64 KiB of LDS has to be asked for once */    \
-    if (lds_bytes > 65536 && !raised) {                                                                 \
+    static std::atomic<bool> raised{false};   /* more than the default 64 KiB of LDS has to be asked for once */ \
+    if (lds_bytes > 65536 && !raised.load(std::memory_order_relaxed)) {                                       \
       CPRUNE_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&mbconv_kernel<T, K_, S_, MB_>), \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));      \
-      raised = true;                                                                                    \
+      raised.store(true, std::memory_order_relaxed);                                                          \
     }                                                                                                   \
     hipLaunchKernelGGL((mbconv_kernel<T, K_, S_, MB_>), grid, dim3(256), lds_bytes, s, a);              \
     return CPRUNE_OK;                                                                                   \
