@@ -257,6 +257,46 @@ def test_channels_last_layer_every_variant(orc, cfg):
     assert ran >= 100 or (k == 3 and stride == 1 and ran >= 110)
 
 
+@pytest.mark.parametrize("cfg", [
+    # c0, c1, c2, hw, batch, dtype: 3x3 conv + 2x2 max-pool (run in the conv's epilogue), every variant
+    (6, 40, 52, 6, 5, B.F32),      # 6x6 map: ragged 4x4 blocks, windows never straddle a block
+    (5, 33, 21, 10, 3, B.F32),     # 10x10
+    (8, 48, 40, 14, 2, B.BF16),    # 14x14, 16-bit
+    (7, 150, 70, 4, 11, B.F32),    # 4x4 map, many channels, ragged last group of images
+])
+def test_pooled_layer_every_variant(orc, cfg):
+    c0, c1, c2, hw, batch, dtype = cfg
+    print("pooled probe", cfg, flush=True)
+    net = synth.NetSpec(f"poolprobe_{c0}_{c1}_{c2}_{hw}", c0, hw, hw)
+    a = net.add(synth.Layer("conv", -1, c0, c1, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="a"))
+    b = net.add(synth.Layer("conv", a, c1, c2, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="b"))
+    net.add(synth.Layer("maxpool", b, c2, c2, k=2, stride=2, name="pool"))
+    cid = 60 + hw
+    params = synth.layer_params(net, cid)
+    x = synth.net_input(net, cid, batch)
+    ref_layers, _ = orc.prune_net(net, params)
+    ref = orc.forward(net, ref_layers, x)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), dtype)
+    handle = pipeline.build_net(net, layers, batch, dtype, tune=False)
+    xd = torch.from_numpy(x).cuda().to(B.TORCH_DTYPE[dtype])
+    ran, names = 0, set()
+    for v in range(B.cprune_num_tile_variants()):
+        try:
+            handle.set_layer_variant(1, v)
+        except B.CPruneError as e:
+            assert e.status == B.ERR_UNSUPPORTED
+            continue
+        ran += 1
+        names.add(B.cprune_tile_variant_name(v, True, dtype).split("<")[0])
+        out = handle.forward(xd)
+        torch.cuda.synchronize()
+        err = nmax(out.float().cpu().numpy(), ref)
+        assert err < TOL[dtype], (v, B.cprune_tile_variant_name(v, True, dtype), err)
+    handle.close()
+    # a fused pool is run by the patch kernels and the independent-wavefront kernel
+    assert ran >= 12 and "conv_wave_kernel" in names and "conv_patch_kernel" in names, (ran, names)
+
+
 @pytest.mark.parametrize("which,dtype", [("mobilenetv2", B.F32), ("mnasnet", B.F32), ("mobilenetv2", B.F16),
                                          ("mnasnet", B.F16)])
 def test_depthwise_fused_into_projection(orc, which, dtype):
