@@ -34,6 +34,8 @@ PEAK = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}   # dense MFMA TFLOP/s, MI3
 # that differs from the profiled run the figure does not apply and null is reported.
 TRAFFIC = {
     ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, 3): 8482171,     # conv3, 5, 6; algorithmic 5.8e6
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, 4): 9387897,     # conv3, 5, 6, 7 (a second counter run with
+                                                                        # conv7 pinned to this tile); algorithmic 5.5e6
     ("conv_wave_kernel<float, 5, 1, 3>", 64, 2): 10504387,              # conv8, 10; algorithmic 3.7e6
     ("conv_wave_kernel<float, 2, 2, 2>", 64, 1): 13512898,              # conv7; algorithmic 4.7e6
     ("conv_wave_kernel<float, 2, 2, 4>", 64, 1): 15068063,              # conv9; algorithmic 4.8e6
