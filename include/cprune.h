@@ -329,11 +329,19 @@ int cprune_net_task_table(const cprune_net* net, int* task_of_layer, int* n_task
  * operands, no memory traffic (the better of the 16x16 and the 32x32 block forms); scratch: device, >= cprune_probe_scratch_bytes() (values
  * written there are meaningless); tflops_out: host.  cprune_probe_copy: rate of a plain
  * copy of `bytes` (a multiple of 16) from src to dst (device, 16-byte aligned, not
- * overlapping), counted as bytes read + bytes written; gbps_out: host.  Both synchronise. */
+ * overlapping), counted as bytes read + bytes written; gbps_out: host.  cprune_probe_l2_read:
+ * GB/s one compute unit reads from L2-resident data with 16-byte-per-lane loads, the form in
+ * which a kernel takes MFMA operands straight from global memory; pattern 0: each wavefront-wide
+ * load covers 1 KiB of consecutive memory, pattern 1: 16 rows x 64 bytes (an operand tile of a
+ * row-major matrix).  buf: device, >= cprune_probe_l2_bytes(), contents irrelevant; scratch:
+ * device, one float; gbps_per_cu_out: host.  All synchronise. */
 size_t cprune_probe_scratch_bytes(void);
 int cprune_probe_mfma(cprune_dtype dtype, void* scratch, size_t scratch_bytes, float* tflops_out,
                       void* stream);
 int cprune_probe_copy(const void* src, void* dst, size_t bytes, float* gbps_out, void* stream);
+size_t cprune_probe_l2_bytes(void);
+int cprune_probe_l2_read(int pattern, const void* buf, size_t buf_bytes, float* scratch,
+                         float* gbps_per_cu_out, void* stream);
 
 #ifdef __cplusplus
 }

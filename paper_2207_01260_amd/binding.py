@@ -51,6 +51,7 @@ EXPORTS = [
     "cprune_net_set_layer_variant", "cprune_net_fuse_depthwise", "cprune_net_fuse_block", "cprune_net_layer_fused",
     "cprune_net_destroy",
     "cprune_probe_scratch_bytes", "cprune_probe_mfma", "cprune_probe_copy",
+    "cprune_probe_l2_bytes", "cprune_probe_l2_read",
     "cprune_lcm_step", "cprune_prune_count", "cprune_variant_filter_splits",
     "cprune_variant_prune_step", "cprune_order_tasks", "cprune_net_task_table",
 ]
@@ -78,7 +79,7 @@ def lib():
         L.cprune_status_string.restype = C.c_char_p
         L.cprune_status_string.argtypes = [C.c_int]
         for name in ("cprune_rank_filters_workspace_bytes", "cprune_conv_workspace_bytes",
-                     "cprune_fc_workspace_bytes", "cprune_probe_scratch_bytes"):
+                     "cprune_fc_workspace_bytes", "cprune_probe_scratch_bytes", "cprune_probe_l2_bytes"):
             getattr(L, name).restype = C.c_size_t
         L.cprune_clear_tile_cache.restype = None
         _lib = L
@@ -355,6 +356,18 @@ def cprune_probe_copy(nbytes: int = 1 << 30, stream=None) -> float:
     out = C.c_float(0.0)
     st = lib().cprune_probe_copy(_ptr(src), _ptr(dst), C.c_size_t(nbytes), C.byref(out), _stream(stream))
     _check(st, "cprune_probe_copy")
+    return float(out.value)
+
+
+def cprune_probe_l2_read(pattern: int, stream=None) -> float:
+    """GB/s one compute unit reads from L2-resident data with 16-byte-per-lane loads; pattern 0: 1 KiB of
+    consecutive memory per wavefront-wide load, 1: 16 rows x 64 bytes."""
+    buf = torch.zeros(lib().cprune_probe_l2_bytes(), dtype=torch.uint8, device="cuda")
+    scratch = torch.zeros(1, dtype=torch.float32, device="cuda")
+    out = C.c_float(0.0)
+    st = lib().cprune_probe_l2_read(C.c_int(pattern), _ptr(buf), C.c_size_t(buf.numel()), _ptr(scratch),
+                                    C.byref(out), _stream(stream))
+    _check(st, "cprune_probe_l2_read")
     return float(out.value)
 
 

@@ -69,6 +69,39 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict
   for (; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Reads of L2-resident data by 16-byte-per-lane buffer loads, as the kernels that take MFMA operands straight
+// from global memory issue them.  Every work-group (4 wavefronts) walks `passes` times over a region of
+// 16 rows x row_bytes (larger than the vector cache); 16 work-groups share a region, as the work-groups of
+// one filter tile do.  PAT 0: a wavefront-wide load covers 1 KiB of consecutive memory (8 whole cache
+// lines).  PAT 1: 16 rows x 64 bytes (16 half lines), the shape of an operand tile in a row-major matrix.
+template <int PAT>
+__global__ __launch_bounds__(256) void l2_probe_kernel(const char* base, unsigned row_bytes, int regions, int passes,
+                                                       float* out) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const unsigned region = 16u * row_bytes;
+  const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(base) + (size_t)(blockIdx.x % regions) * region, 0, (int)region, 0x00020000);
+  const unsigned steps = region / 1024 / 4;   // loads per wavefront and pass (a ragged rest is not read)
+  const unsigned cols = row_bytes / 64;
+  uint4 acc = {0u, 0u, 0u, 0u};
+  for (int p = 0; p < passes; ++p) {
+    for (unsigned i = 0; i + 4 <= steps; i += 4) {
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const unsigned step = (i + u) * 4 + wave;
+        unsigned off;
+        if (PAT == 0) off = step * 1024 + lane * 16;
+        else off = (unsigned)(lane & 15) * row_bytes + (step % cols) * 64 + (lane >> 4) * 16;
+        v[u] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0));
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+    }
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345u) out[0] = 1.f;   // keeps the loads alive
+}
+
 int timed(hipStream_t s, int reps, float* ms_out, const std::function<void()>& launch) {
   hipEvent_t e0, e1;
   CPRUNE_HIP_TRY(hipEventCreate(&e0));
@@ -139,5 +172,30 @@ extern "C" int cprune_probe_copy(const void* src, void* dst, size_t bytes, float
   });
   if (rc != CPRUNE_OK) return rc;
   *gbps_out = (float)(2.0 * (double)bytes / (ms * 1e-3) / 1e9);   // bytes read + bytes written
+  return CPRUNE_OK;
+}
+
+extern "C" size_t cprune_probe_l2_bytes(void) { return (size_t)16 * 16 * 10944; }   // 16 regions of 16 rows
+
+extern "C" int cprune_probe_l2_read(int pattern, const void* buf, size_t buf_bytes, float* scratch,
+                                    float* gbps_per_cu_out, void* stream) {
+  if (!buf || !scratch || !gbps_per_cu_out || (pattern != 0 && pattern != 1)) return CPRUNE_ERR_INVALID_ARG;
+  if (buf_bytes < cprune_probe_l2_bytes()) return CPRUNE_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  int dev = 0, cus = 0;
+  CPRUNE_HIP_TRY(hipGetDevice(&dev));
+  CPRUNE_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const unsigned row_bytes = 10944;   // 171 columns of 64 bytes: the filter row of a 304-channel 3x3 layer
+  const int passes = 20;
+  float ms = 0.f;
+  int rc = timed(s, 3, &ms, [&]() {
+    if (pattern == 0) hipLaunchKernelGGL(l2_probe_kernel<0>, dim3((unsigned)cus), dim3(256), 0, s, (const char*)buf, row_bytes, 16, passes, scratch);
+    else hipLaunchKernelGGL(l2_probe_kernel<1>, dim3((unsigned)cus), dim3(256), 0, s, (const char*)buf, row_bytes, 16, passes, scratch);
+  });
+  if (rc != CPRUNE_OK) return rc;
+  // bytes one work-group (= one compute unit: the grid has one group per unit) reads
+  const double steps = (double)((16u * row_bytes / 1024 / 4) / 4 * 4);
+  const double bytes = steps * 4 * 1024 * passes;
+  *gbps_per_cu_out = (float)(bytes / (ms * 1e-3) / 1e9);
   return CPRUNE_OK;
 }

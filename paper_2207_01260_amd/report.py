@@ -165,6 +165,8 @@ def report_device(steps):
             "mfma_f16_tflops": round(B.cprune_probe_mfma(B.F16), 1),
             "mfma_bf16_tflops": round(B.cprune_probe_mfma(B.BF16), 1),
             "copy_gbs": round(B.cprune_probe_copy(1 << 30), 1),
+            "l2_read_gbs_per_cu": {"consecutive_kib": round(B.cprune_probe_l2_read(0), 1),
+                                   "rows_of_64_bytes": round(B.cprune_probe_l2_read(1), 1)},
             "datasheet": {"mfma_f32_tflops": 157.3, "mfma_f16_bf16_tflops": 2500.0, "hbm_gbs": 8000.0}}
     print(json.dumps({"measured_ceilings": ceil}), flush=True)
     for row in single_layer_report(steps):

@@ -130,6 +130,15 @@ def test_gather_rejects_bad_args():
                                     FAKE, C.c_int(5), FAKE, None) == B.ERR_INVALID_ARG
 
 
+def test_probe_rejects_bad_args():
+    L = B.lib()
+    out = C.c_float(0.0)
+    assert L.cprune_probe_l2_bytes() > 0
+    assert L.cprune_probe_l2_read(C.c_int(2), FAKE, C.c_size_t(1 << 30), FAKE, C.byref(out), None) == B.ERR_INVALID_ARG
+    assert L.cprune_probe_l2_read(C.c_int(0), None, C.c_size_t(1 << 30), FAKE, C.byref(out), None) == B.ERR_INVALID_ARG
+    assert L.cprune_probe_l2_read(C.c_int(0), FAKE, C.c_size_t(16), FAKE, C.byref(out), None) == B.ERR_WORKSPACE
+
+
 def test_pool_fc_net_reject_bad_args():
     L = B.lib()
     assert L.cprune_maxpool2d(FAKE, C.c_int(1), C.c_int(1), C.c_int(4), C.c_int(4), C.c_int(0),

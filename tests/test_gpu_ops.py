@@ -304,3 +304,14 @@ def test_rank_filter_group(orc):
     assert torch.equal(s1, s2) and torch.equal(o1, o2) and torch.equal(k1, k2)
     with pytest.raises(B.CPruneError):
         B.cprune_rank_filter_group([da, db], 97)
+
+
+def test_measured_ceilings():
+    """The device probes next to which kernel rates are reported: they run, return finite positive rates below
+    the datasheet peaks, and loads of consecutive kilobytes are served faster than rows of 64 bytes."""
+    tf = B.cprune_probe_mfma(B.F32)
+    assert 50.0 < tf < 157.3 * 1.02, tf
+    gbs = B.cprune_probe_copy(1 << 28)
+    assert 500.0 < gbs < 2 * 8000.0, gbs
+    consecutive, rows = B.cprune_probe_l2_read(0), B.cprune_probe_l2_read(1)
+    assert 5.0 < rows < consecutive < 400.0, (consecutive, rows)
