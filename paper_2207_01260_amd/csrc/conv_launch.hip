@@ -132,7 +132,12 @@ bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
     // tiled kernels, which share them through LDS, are the ones to use)
     if (!(lay.nhwc && lay.w_wave && d.kh == 3 && d.kw == 3 && d.stride == 1 && d.pad == 1)) return false;
     if (lay.pool == 2 || (lay.pool && ((d.h | d.w) & 1))) return false;
-    return d.h >= 3 && d.w >= 3 && d.h <= kMaxWaveMap && d.w <= kMaxWaveMap;
+    if (!(d.h >= 3 && d.w >= 3 && d.h <= kMaxWaveMap && d.w <= kMaxWaveMap)) return false;
+    // multiply-high divisions in the group decode: exact while groups x divisor < 2^32
+    const long blocks = (long)d.n * ((d.h + 3) / 4) * ((d.w + 3) / 4);
+    const long tiles_n = (blocks + tv.wn * tv.nb - 1) / (tv.wn * tv.nb);
+    const long groups = tiles_n * ((d.c_out + 15) / 16);
+    return groups * tiles_n < (1L << 32) && (blocks + 16) * 16 < (1L << 32);
   }
   if (tv.sched == -3) {
     // 1x1 / stride 1, no pool; exactly one (mb, nr) pair serves a shape: the smallest filter tile that
@@ -158,8 +163,11 @@ bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
     if (!(lay.nhwc && d.kh == 3 && d.kw == 3 && d.stride == 1 && d.pad == 1)) return false;
     if (lay.pool == 2 || (lay.pool && ((d.h | d.w) & 1))) return false;
     // multi-image tiles are for maps that fit one tile; single-image tiles for the rest
-    if (tv.ni > 1) return d.h <= tv.th && d.w <= tv.tw;
-    return d.h * 2 > tv.th && d.w * 2 > tv.tw;
+    if (tv.ni > 1 ? !(d.h <= tv.th && d.w <= tv.tw) : !(d.h * 2 > tv.th && d.w * 2 > tv.tw)) return false;
+    // the kernels decode their tile with multiply-high divisions, exact while groups x divisor < 2^32
+    const long tiles_s = (long)((d.n + tv.ni - 1) / tv.ni) * ((d.h + tv.th - 1) / tv.th) * ((d.w + tv.tw - 1) / tv.tw);
+    const long groups = tiles_s * ((d.c_out + tv.tile_m() - 1) / tv.tile_m());
+    return groups * tiles_s < (1L << 32);
   }
   if (lay.pool == 1) return false;                // only the patch kernels fuse a spatial pool
   if (lay.pool && lay.nhwc_out && !lay.nhwc) return false;
@@ -209,6 +217,9 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     pa.act = d.act;
     pa.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
     pa.m_major = pa.w_bytes > pa.x_bytes ? 1 : 0;
+    pa.magic_s = magic_for((unsigned)pa.tiles_n); pa.magic_m = magic_for((unsigned)pa.tiles_m);
+    pa.magic_x = magic_for((unsigned)pa.tiles_x); pa.magic_y = magic_for((unsigned)pa.tiles_y);
+    pa.magic_xy = magic_for((unsigned)(pa.tiles_x * pa.tiles_y));
     dim3 grid((unsigned)(pa.tiles_n * pa.tiles_m));
     int rc;
     if (d.dtype == CPRUNE_F32) rc = launch_conv_wave_f32(tv.patch_id, grid, s, pa);
@@ -292,6 +303,9 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     pa.act = d.act;
     pa.vec_out = (lay.cp_out % 4) == 0 ? 1 : 0;
     pa.m_major = pa.w_bytes > pa.x_bytes ? 1 : 0;
+    pa.magic_s = magic_for((unsigned)(pa.tiles_n * pa.tiles_y * pa.tiles_x)); pa.magic_m = magic_for((unsigned)pa.tiles_m);
+    pa.magic_x = magic_for((unsigned)pa.tiles_x); pa.magic_y = magic_for((unsigned)pa.tiles_y);
+    pa.magic_xy = 0;
     dim3 pgrid((unsigned)(pa.tiles_n * pa.tiles_y * pa.tiles_x * pa.tiles_m));
     if (tv.blk32) {
       if (d.dtype == CPRUNE_F32) launch_conv_patch32_f32(tv.patch_id, pgrid, s, pa);

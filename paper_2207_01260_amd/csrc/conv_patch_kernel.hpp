@@ -34,6 +34,10 @@ struct PatchArgs {
   unsigned x_bytes, w_bytes;
   int act, vec_out;
   int pool;   // 1: 2x2 / stride 2 max-pool fused behind the activation; y is [n][h/2][w/2][cop]
+  // ceil(2^32 / d) for the divisions of the tile decode (0 when d == 1): by tiles_n * tiles_y * tiles_x, tiles_m,
+  // tiles_x, tiles_y; for the independent-wavefront kernel magic_s divides by tiles_n and magic_xy by
+  // tiles_x * tiles_y.  Exact while (number of groups) x (divisor) < 2^32, which the host checks.
+  unsigned magic_s, magic_m, magic_x, magic_y, magic_xy;
   int m_major;  // tile order: 0 = filter tiles fastest (each chip quarter's L2 sees few input patches, all
                 // weights), 1 = pixel tiles fastest (few filters, all patches): whichever operand is larger
                 // is the one split between the L2s
@@ -112,13 +116,17 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
     const int q = G >> 3, rem = G & 7;
     tile = xcd * q + (xcd < rem ? xcd : rem) + local;
   }
+  // (divisions by multiplication: a scalar division is a chain of some thirty dependent instructions, and
+  // five of them in front of the first load are a tenth of a short layer's tile)
   const int tiles_s = a.tiles_n * a.tiles_y * a.tiles_x;
-  const int tile_m = a.m_major ? tile / tiles_s : tile % a.tiles_m;
-  int rest = a.m_major ? tile % tiles_s : tile / a.tiles_m;
-  const int tx0 = (rest % a.tiles_x) * TW;
-  rest /= a.tiles_x;
-  const int ty0 = (rest % a.tiles_y) * TH;
-  const int n0 = (rest / a.tiles_y) * NI;
+  const int q_s = (int)fast_div((unsigned)tile, a.magic_s), q_m = (int)fast_div((unsigned)tile, a.magic_m);
+  const int tile_m = a.m_major ? q_s : tile - q_m * a.tiles_m;
+  const int rest = a.m_major ? tile - q_s * tiles_s : q_m;
+  const int q_x = (int)fast_div((unsigned)rest, a.magic_x);
+  const int q_y = (int)fast_div((unsigned)q_x, a.magic_y);
+  const int tx0 = (rest - q_x * a.tiles_x) * TW;
+  const int ty0 = (q_x - q_y * a.tiles_y) * TH;
+  const int n0 = q_y * NI;
   const int o0 = tile_m * MT;
 
   const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);

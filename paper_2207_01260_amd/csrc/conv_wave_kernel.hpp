@@ -58,8 +58,9 @@ __global__ __launch_bounds__(64 * NP * KS) void conv_wave_kernel(PatchArgs a) {
     grp = xcd * q + (xcd < rem ? xcd : rem) + local;
   }
   // a.tiles_n: groups along the block list (blocks = images x tiles_y x tiles_x, NBLK per group)
-  const int tile_m = a.m_major ? grp / a.tiles_n : grp % a.tiles_m;
-  const int gp = a.m_major ? grp % a.tiles_n : grp / a.tiles_m;
+  const int q_s = (int)fast_div((unsigned)grp, a.magic_s), q_m = (int)fast_div((unsigned)grp, a.magic_m);
+  const int tile_m = a.m_major ? q_s : grp - q_m * a.tiles_m;
+  const int gp = a.m_major ? grp - q_s * a.tiles_n : q_m;
   const int o0 = tile_m * 16;
   const int blocks = a.N * a.tiles_y * a.tiles_x;
   const int txy = a.tiles_x * a.tiles_y;
@@ -82,8 +83,9 @@ __global__ __launch_bounds__(64 * NP * KS) void conv_wave_kernel(PatchArgs a) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
       const int u = u0 + j;
-      const int n = u / txy, rest = u - n * txy;
-      const int iy = (rest / a.tiles_x) * 4 + py - 1, ix = (rest % a.tiles_x) * 4 + px - 1;
+      const int n = (int)fast_div((unsigned)u, a.magic_xy), rest = u - n * txy;
+      const int by = (int)fast_div((unsigned)rest, a.magic_x);
+      const int iy = by * 4 + py - 1, ix = (rest - by * a.tiles_x) * 4 + px - 1;
       const bool inside = item && u < blocks && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
       b_off[j][i] = inside ? (unsigned)(((n * a.H + iy) * a.W + ix) * a.Cp + q * EPI) * ES : kOutOfRange;
     }
@@ -196,8 +198,9 @@ __global__ __launch_bounds__(64 * NP * KS) void conv_wave_kernel(PatchArgs a) {
     float4_t acc = red[(size_t)b * 64 + lane];
 #pragma unroll
     for (int k = 1; k < KS; ++k) acc += red[((size_t)k * NBLK + b) * 64 + lane];
-    const int n = u / txy, rest = u - n * txy;
-    const int oy = (rest / a.tiles_x) * 4 + ty, ox = (rest % a.tiles_x) * 4 + tx;
+    const int n = (int)fast_div((unsigned)u, a.magic_xy), rest = u - n * txy;
+    const int by = (int)fast_div((unsigned)rest, a.magic_x);
+    const int oy = by * 4 + ty, ox = (rest - by * a.tiles_x) * 4 + tx;
     if (!a.pool) {
       if (oy < a.H && ox < a.W) nhwc_store4<T>(e, acc, (n * a.H + oy) * a.W + ox, o);
     } else {
