@@ -434,6 +434,8 @@ static int net_run_stem(cprune_net* net, int i, int n, const void* x, void* dst,
   const int mb = L.d.c_out <= 32 ? 2 : 4;
   a.tiles_y = (a.Ho + 7) / 8; a.tiles_x = (a.Wo + 15) / 16; a.tiles_m = (a.O + mb * 16 - 1) / (mb * 16);
   a.vec_out = (a.Cop % 4) == 0 ? 1 : 0;
+  a.magic_x = a.tiles_x > 1 ? (unsigned)((0x100000000ull + a.tiles_x - 1) / a.tiles_x) : 0u;
+  a.magic_y = a.tiles_y > 1 ? (unsigned)((0x100000000ull + a.tiles_y - 1) / a.tiles_y) : 0u;
   const long ptiles = (long)n * a.tiles_y * a.tiles_x;
   // as many workers as stay resident: LDS per work-group = weight tile + patch + offset table
   const int es = (int)dtype_size(net->dtype), kp = stem_packed_k(L.d.k, net->dtype);

@@ -197,6 +197,8 @@ struct StemArgs {
   int N, C, H, W, Ho, Wo, O, Cop;
   int pad, act;
   int tiles_y, tiles_x, tiles_m;
+  unsigned magic_x, magic_y;   // ceil(2^32 / tiles_x), ceil(2^32 / tiles_y), 0 for a divisor of 1 (exact while
+                               // pixel blocks x divisor < 2^32: always, for tensors below 2^31 bytes)
   int vec_out;
 };
 // (k, stride) in {(3, 1), (3, 2), (7, 2)}, mb in {2, 4} (16-filter blocks per tile); grid.x = workers

@@ -68,6 +68,7 @@ struct ConvArgs {
   int slabs;          // reduction slabs per output tile
   int units;          // tiles * slabs: the work, in slab iterations
   int units_per_wg;   // contiguous run of units each work-group takes
+  unsigned magic_tp = 0;  // reduction-split kernel: division by tiles_p (exact while groups x tiles_p < 2^32)
   int w_packed = 0;   // reduction-split kernel: w is in fragment order, [16-row tile][round][lane][16 bytes]
 };
 

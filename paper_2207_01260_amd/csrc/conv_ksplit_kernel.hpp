@@ -38,7 +38,7 @@ __global__ __launch_bounds__(64 * KW) void conv_ksplit_kernel(ConvArgs a) {
     const int q = G >> 3, rem = G & 7;
     g = xcd * q + (xcd < rem ? xcd : rem) + local;
   }
-  const int tile_m = g / a.tiles_p, tile_p = g - tile_m * a.tiles_p;
+  const int tile_m = (int)fast_div((unsigned)g, a.magic_tp), tile_p = g - tile_m * a.tiles_p;
   const int o0 = tile_m * 16, p0 = tile_p * (16 * NB);
 
   const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);

@@ -277,6 +277,7 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     a.act = d.act;
     a.tiles_m = (d.c_out + 15) / 16;
     a.tiles_p = (a.P + tv.tile_p() - 1) / tv.tile_p();
+    a.magic_tp = magic_for((unsigned)a.tiles_p);   // at most kMaxKsplitGroups groups: exact
     if (lay.w_rows) {
       a.w = lay.w_rows;
       a.w_bytes = (unsigned)rows_packed_bytes(d.c_out, a.K, d.dtype);

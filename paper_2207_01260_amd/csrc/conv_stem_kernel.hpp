@@ -90,10 +90,10 @@ __global__ __launch_bounds__(256) void conv_stem_kernel(StemArgs a) {
   T pre[NL];
   const int plimit = a.C * PH * PWP;
   auto load_patch = [&](int tile) {
-    const int tx0 = (tile % a.tiles_x) * TW;
-    int rest = tile / a.tiles_x;
-    const int ty0 = (rest % a.tiles_y) * TH;
-    const int n = rest / a.tiles_y;
+    const int rest = (int)fast_div((unsigned)tile, a.magic_x);   // multiply-high: no scalar division chains
+    const int n = (int)fast_div((unsigned)rest, a.magic_y);
+    const int tx0 = (tile - rest * a.tiles_x) * TW;
+    const int ty0 = (rest - n * a.tiles_y) * TH;
     const int iy0 = ty0 * S - a.pad, ix0 = tx0 * S - a.pad;
 #pragma unroll
     for (int j = 0; j < NL; ++j) {
@@ -112,10 +112,10 @@ __global__ __launch_bounds__(256) void conv_stem_kernel(StemArgs a) {
   const int ptiles = a.N * a.tiles_y * a.tiles_x;
   if (worker < ptiles) load_patch(worker);
   for (int tile = worker; tile < ptiles; tile += gridDim.x) {
-    const int tx0 = (tile % a.tiles_x) * TW;
-    int rest = tile / a.tiles_x;
-    const int ty0 = (rest % a.tiles_y) * TH;
-    const int n = rest / a.tiles_y;
+    const int rest = (int)fast_div((unsigned)tile, a.magic_x);   // multiply-high: no scalar division chains
+    const int n = (int)fast_div((unsigned)rest, a.magic_y);
+    const int tx0 = (tile - rest * a.tiles_x) * TW;
+    const int ty0 = (rest - n * a.tiles_y) * TH;
 
     __syncthreads();          // the previous block's reads of the patch are done
 #pragma unroll
