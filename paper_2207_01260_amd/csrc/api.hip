@@ -793,6 +793,7 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     const cprune_layer_desc& d = L.d;
     if (!(d.kind == CPRUNE_LAYER_CONV && d.groups == 1 && d.k == 3 && d.stride == 1 && d.pad == 1)) continue;
     if (L.map2x2 || L.nchw_in || L.h_in < 3 || L.w_in < 3 || L.h_in > 16 || L.w_in > 16) continue;
+    if (wave_packed_bytes(d.c_out, L.cp_in, dtype) >= ((size_t)1 << 31)) continue;   // 31-bit offsets in the kernel
     rc = dev_alloc(wave_packed_bytes(d.c_out, L.cp_in, dtype), &L.w_wave);
     if (rc == CPRUNE_OK) rc = launch_repack_wave(L.w, d.c_out, L.cp_in, dtype, L.w_wave, s);
   }
@@ -807,6 +808,7 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     for (int v = 0; v < num_variants() && !any; ++v) any = variant(v).sched == -2 && variant_supports(cd, v, lay);
     if (!any) continue;
     const int k = lay.cp_in * cd.kh * cd.kw;
+    if (rows_packed_bytes(cd.c_out, k, dtype) >= ((size_t)1 << 31)) continue;   // the kernel then reads the row layout
     rc = dev_alloc(rows_packed_bytes(cd.c_out, k, dtype), &L.w_rows);
     if (rc == CPRUNE_OK) rc = launch_repack_rows(L.w, cd.c_out, k, dtype, L.w_rows, s);
   }
