@@ -58,6 +58,9 @@ def main():
                     help="comma-separated tile variants of the dense layers in network order (the "
                          "`variants` list an earlier run printed): applied instead of timing, so that a run "
                          "under a profiler, which disturbs the timing, executes the same kernels")
+    ap.add_argument("--fuse-first", type=int, default=-1, choices=[-1, 0, 1],
+                    help="first two layers as one kernel: 1 yes, 0 no, -1 (default) as the timed selection decides "
+                         "(no with --no-tune or --variants)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip batch-1 and fp16 side figures")
     ap.add_argument("--cpu-images", type=int, default=0, help="oracle sample size (0 = auto)")
@@ -122,6 +125,8 @@ def main():
         for i, v in zip(dense, pinned):
             if v >= 0:                           # -1: a layer without tile variants (first-layer kernel)
                 handle.set_layer_variant(i, v)
+    if args.fuse_first >= 0:
+        handle.fuse_first_layers(bool(args.fuse_first))
     variants = [handle.layer_variant(i) for i in dense]
     kept_counts = {i: int(k.numel()) for i, k in kept.items()}
     x = torch.from_numpy(synth.net_input(net, cid, args.batch)).cuda().to(B.TORCH_DTYPE[dt])
@@ -142,20 +147,32 @@ def main():
     per_layer = []
     by_kernel = {}        # kernel instantiation -> [launches, ms, flop]
     shp = synth.shapes(net, kept_counts)
+    tname = {"f32": "float", "f16": "_Float16", "bf16": "__bf16"}[args.dtype]
+    carried = 0.0          # FLOP of a layer that runs inside its reader's kernel
+    fused_first = False
     for i, (L, m) in enumerate(zip(net.layers, layer_ms)):
         if L.kind != "conv":
             continue
         cin, cout, ho, wo = shp[i]
         fl = 2.0 * args.batch * cout * cin * 9 * ho * wo
+        if handle.layer_fused(i):                # the first layer inside the second layer's kernel
+            carried, fused_first = fl, True
+            per_layer.append({"layer": L.name, "c_in": cin, "c_out": cout, "hw": ho, "us": 0.0, "tflops": None,
+                              "tile": "-", "kernel": "(inside the next layer's kernel)"})
+            continue
         v = handle.layer_variant(i)
         first = L.input < 0 and cin <= 4         # reads the NCHW input itself
-        if v < 0:                                # the first-layer kernel: no tile variants
+        if v < 0 and carried:                    # first two layers in one kernel: no tile variants
+            mb = 1 if cout <= 16 else (2 if cout <= 32 else 4)
+            tm, tp, sk = 16 * mb, 128, 0
+            kern = "conv_stem2_kernel<%s, %d>" % (tname, mb)
+        elif v < 0:                              # the first-layer kernel: no tile variants
             tm, tp, sk = 16 * (2 if cout <= 32 else 4), 128, 0
-            kern = "conv_stem_kernel<%s, %d, %d, %d>" % ({"f32": "float", "f16": "_Float16", "bf16": "__bf16"}[args.dtype],
-                                                          L.k, L.stride, tm // 16)
+            kern = "conv_stem_kernel<%s, %d, %d, %d>" % (tname, L.k, L.stride, tm // 16)
         else:
             tm, tp, sk = B.cprune_tile_variant_info(v)
             kern = B.cprune_tile_variant_name(v, channels_last=not first, dtype=dt)
+        fl, carried = fl + carried, 0.0
         note = (" + fix-up" if sk > 0 else "") + (" (2x2 map as one matrix)" if (ho == 2 and sk >= 0) else "")
         g = by_kernel.setdefault(kern, [0, 0.0, 0.0])
         g[0] += 1; g[1] += m; g[2] += fl
@@ -176,6 +193,7 @@ def main():
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"pruned VGG-16 (13 conv + FC), 32x32x3 inputs, keep ratios U(0.4,0.9), "
                                f"batch {args.batch}", "batch": args.batch, "hip_graph": graph,
+                   "first_two_layers_one_kernel": fused_first,
                    "kept_filters": [kept_counts[i] for i in sorted(kept_counts)]},
         "useful_gflop_per_step": round(total_flops / 1e9, 3),
         "whole_net_tflops": round(total_flops / (ms * 1e-3) / 1e12, 2),
@@ -188,7 +206,7 @@ def main():
                      "avg_launch_us": round(d_ms / d_n * 1e3, 2),
                      "useful_gflop_per_launch": round(d_fl / d_n / 1e9, 3),
                      "share_of_step": round(d_ms / ms, 3)},
-        "conv_layers": {"launches_per_step": n_conv, "tflops": round(agg, 2),
+        "conv_layers": {"layers": n_conv, "launches_per_step": n_conv - (1 if fused_first else 0), "tflops": round(agg, 2),
                         "frac_of_peak": round(agg / PEAK[args.dtype], 4),
                         "avg_layer_us": round(conv_ms / n_conv * 1e3, 2),
                         "useful_gflop_per_layer_avg": round(conv_flops / n_conv / 1e9, 3)},

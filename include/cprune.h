@@ -260,6 +260,14 @@ int cprune_net_copy_activation(cprune_net* net, int layer, int n, void* dst, siz
 int cprune_net_output_shape(const cprune_net* net, int* c_out, int* h_out, int* w_out);
 /* The tile variant in use for layer `layer` (-1 for layers without one); host out. */
 int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out);
+/* The first two layers in one kernel, where the network opens with two 3x3 / stride 1 / pad 1 convolutions,
+ * the first on the image (at most 3 channels) with at most 32 filters and read by the second only (the
+ * VGG-16 of Sec. 4.1, Table 2; channel counts as Sec. 3.5 leaves them): the first layer's output, the
+ * largest activation of such a network, is then never written.  cprune_net_create(tune = 1) times both
+ * forms and keeps the faster; this call forces one.  enable: 0 / 1.  CPRUNE_ERR_UNSUPPORTED when the
+ * network does not open that way.  Synchronises; recorded graphs are dropped. */
+int cprune_net_fuse_first_layers(cprune_net* net, int enable);
+
 /* A depthwise conv (3x3 or 5x5, stride 1 or 2, "same" padding) whose only reader is a 1x1
  * conv can run inside that conv's kernel (the tensor between them is then never stored).
  * cprune_net_create decides per pair (by size, or by timing both forms when tune != 0);

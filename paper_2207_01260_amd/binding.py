@@ -48,7 +48,8 @@ EXPORTS = [
     "cprune_fc_workspace_bytes", "cprune_fc",
     "cprune_net_create", "cprune_net_forward", "cprune_net_layer_times",
     "cprune_net_copy_activation", "cprune_net_output_shape", "cprune_net_layer_variant",
-    "cprune_net_set_layer_variant", "cprune_net_fuse_depthwise", "cprune_net_fuse_block", "cprune_net_layer_fused",
+    "cprune_net_set_layer_variant", "cprune_net_fuse_depthwise", "cprune_net_fuse_block",
+    "cprune_net_fuse_first_layers", "cprune_net_layer_fused",
     "cprune_net_destroy",
     "cprune_probe_scratch_bytes", "cprune_probe_mfma", "cprune_probe_copy",
     "cprune_probe_l2_bytes", "cprune_probe_l2_read",
@@ -434,6 +435,10 @@ class Net:
     def fuse_block(self, layer: int, enable: bool):
         _check(lib().cprune_net_fuse_block(self._h, C.c_int(layer), C.c_int(1 if enable else 0)),
                "cprune_net_fuse_block")
+
+    def fuse_first_layers(self, enable: bool):
+        _check(lib().cprune_net_fuse_first_layers(self._h, C.c_int(1 if enable else 0)),
+               "cprune_net_fuse_first_layers")
 
     def layer_fused(self, layer: int) -> bool:
         f = C.c_int(0)

@@ -351,6 +351,8 @@ struct NetLayer {
   int fuse_block = -1;        // 1x1 conv with fuse_dw set: index of the 1x1 expansion in front of that depthwise
                               // layer when the whole block (expansion, depthwise, this projection) is one kernel
   int block_expand = -1;      // depthwise conv: the expansion layer that may join it and dw_reader in one kernel
+  int fuse_stem = -1;         // 3x3 conv: index of the first layer (on the image) computed inside its kernel, or -1
+  int stem_reader = -1;       // first layer that may run inside the 3x3 conv stem_reader's kernel
   void* w_stem = nullptr;     // weights packed for the first-layer kernel
   void* w_rows = nullptr;     // layer the reduction-split kernel can run: weights once more, in its operand order
   void* w_wave = nullptr;     // 3x3 / stride 1 / pad 1 layer on a small map: weights once more, packed for the
@@ -456,6 +458,14 @@ static int net_run_stem(cprune_net* net, int i, int n, const void* x, void* dst,
   return CPRUNE_OK;
 }
 
+// First layer L.fuse_stem and the 3x3 layer i in one kernel: reads the caller's NCHW image.
+static int net_run_stem2(cprune_net* net, int i, int n, const void* x, void* dst, hipStream_t s) {
+  const NetLayer& L = net->layers[i];
+  const NetLayer& F = net->layers[L.fuse_stem];
+  const cprune_conv_desc d2 = layer_conv_desc(*net, L, n);
+  return launch_conv_stem2(d2, layer_layout(L), x, F.d.c_in, F.w_stem, F.b, F.d.c_out, F.d.act, L.w, L.b, dst, s);
+}
+
 // Depthwise layer P.fuse_dw and the 1x1 layer i in one kernel: reads the depthwise layer's input.
 static int net_run_dwproj(cprune_net* net, int i, int n, void* dst, hipStream_t s) {
   const NetLayer& P = net->layers[i];
@@ -546,6 +556,7 @@ static int net_run_layer(cprune_net* net, int i, int n, const void* x, void* out
   if (L.fused_away) return CPRUNE_OK;
   if (L.fuse_block >= 0) return net_run_mbconv(net, i, n, dst, s);
   if (L.fuse_dw >= 0) return net_run_dwproj(net, i, n, dst, s);
+  if (L.fuse_stem >= 0) return net_run_stem2(net, i, n, x, dst, s);
   if (L.stem) return net_run_stem(net, i, n, src, dst, s);
   switch (L.d.kind) {
     case CPRUNE_LAYER_CONV:
@@ -857,6 +868,38 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     if (use) L.variant = -1;
   }
 
+  // A first layer (3x3 / stride 1, at most 32 filters) whose only reader is another 3x3 / stride 1 conv can run
+  // inside that conv's kernel: the largest activation of a VGG-style network is then never written.  With
+  // tune != 0 both forms are timed and the faster kept; otherwise only cprune_net_fuse_first_layers turns it on.
+  for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
+    NetLayer& F = net->layers[i];
+    if (!(F.stem_ok && F.nchw_in && F.d.k == 3 && F.d.stride == 1 && F.d.pad == 1 && F.d.residual < 0 && !F.fused_pool)) continue;
+    int reader = -1, readers = 0;
+    for (int j = 0; j < n_layers; ++j) {
+      if (net->layers[j].d.input == i) { reader = j; ++readers; }
+      if (net->layers[j].d.residual == i) readers += 2;
+    }
+    if (readers != 1 || i == n_layers - 1) continue;
+    NetLayer& L = net->layers[reader];
+    if (!(L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1 && L.d.residual < 0 && !L.map2x2 && !L.nchw_in)) continue;
+    if (!conv_stem2_supported(layer_conv_desc(*net, L, max_batch), layer_layout(L), F.d.c_in, F.d.c_out)) continue;
+    F.stem_reader = reader;
+    bool fuse = false;
+    if (tune) {
+      const int pair[2] = {i, reader};
+      float ms[2] = {0.f, 0.f};
+      for (int form = 0; form < 2 && rc == CPRUNE_OK; ++form) {   // 0: layers apart as decided so far, 1: one kernel
+        F.fused_away = form == 1;
+        L.fuse_stem = form == 1 ? i : -1;
+        rc = time_layers(net, pair, 2, max_batch, net->x_cl, s, &ms[form]);
+      }
+      fuse = ms[1] < ms[0];
+    }
+    F.fused_away = fuse;
+    L.fuse_stem = fuse ? i : -1;
+    if (fuse) L.variant = -1;
+  }
+
   // A depthwise conv whose only reader is a 1x1 conv can run inside that conv's kernel: the
   // expanded activations are then read once and never written.  It pays on large maps (enough
   // 8x8 pixel blocks to fill the chip); with tune != 0 both forms are timed and the faster kept.
@@ -1059,6 +1102,24 @@ static void restore_variant(cprune_net* net, NetLayer& L) {
     L.variant = cached_or_heuristic_variant(layer_conv_desc(*net, L, net->max_batch), nullptr, layer_layout(L));
 }
 
+extern "C" int cprune_net_fuse_first_layers(cprune_net* net, int enable) {
+  if (!net) return CPRUNE_ERR_INVALID_ARG;
+  int first = -1;
+  for (int i = 0; i < (int)net->layers.size(); ++i)
+    if (net->layers[i].stem_reader >= 0) { first = i; break; }
+  if (first < 0) return CPRUNE_ERR_UNSUPPORTED;
+  CPRUNE_HIP_TRY(hipDeviceSynchronize());
+  for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
+  net->graphs.clear();
+  NetLayer& F = net->layers[first];
+  NetLayer& L = net->layers[F.stem_reader];
+  F.fused_away = enable != 0;
+  L.fuse_stem = enable ? first : -1;
+  if (enable) L.variant = -1;
+  else restore_variant(net, L);
+  return CPRUNE_OK;
+}
+
 extern "C" int cprune_net_fuse_depthwise(cprune_net* net, int layer, int enable) {
   if (!net || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
   NetLayer& D = net->layers[layer];
@@ -1111,7 +1172,7 @@ extern "C" int cprune_net_set_layer_variant(cprune_net* net, int layer, int vari
   if (!net || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
   NetLayer& L = net->layers[layer];
   if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) return CPRUNE_ERR_INVALID_ARG;
-  if (L.fuse_dw >= 0 || L.fused_away) return CPRUNE_ERR_INVALID_ARG;   // runs inside a fused kernel: no variants
+  if (L.fuse_dw >= 0 || L.fuse_stem >= 0 || L.fused_away) return CPRUNE_ERR_INVALID_ARG;   // runs inside a fused kernel: no variants
   if (L.stem) L.stem = false;                          // a pinned variant means the general kernel
   const cprune_conv_desc cd = layer_conv_desc(*net, L, net->max_batch);
   const ConvLayout lay = layer_layout(L);

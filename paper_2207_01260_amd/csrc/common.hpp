@@ -187,6 +187,15 @@ int launch_mbconv_f32(int k, int stride, int mb, dim3 grid, size_t lds_bytes, hi
 int launch_mbconv_f16(int k, int stride, int mb, dim3 grid, size_t lds_bytes, hipStream_t s, const MbConvArgs& a);
 int launch_mbconv_bf16(int k, int stride, int mb, dim3 grid, size_t lds_bytes, hipStream_t s, const MbConvArgs& a);
 
+// The first two layers of a network in one kernel: both 3x3 / stride 1 / pad 1, the first on the NCHW image
+// (at most 3 channels) with c1 <= 32 filters, the second dense and channels-last.  d2 / lay2 describe the second
+// layer (c_in = c1, cp_in = its channel stride in w2 <= 32, pool = 0 / 1); w1_packed from launch_repack_stem
+// with 32 rows; y as for that layer.  CPRUNE_ERR_UNSUPPORTED outside these limits.
+bool conv_stem2_supported(const cprune_conv_desc& d2, const ConvLayout& lay2, int c_in, int c1);
+int launch_conv_stem2(const cprune_conv_desc& d2, const ConvLayout& lay2, const void* x_nchw, int c_in,
+                      const void* w1_packed, const float* b1, int c1, int act1, const void* w2, const float* b2,
+                      void* y, hipStream_t s);
+
 // First-layer convolution: NCHW input with at most 3 channels, OIHW weights, channels-last output.
 struct StemArgs {
   const void* x;        // [n][c][h][w]

@@ -3,6 +3,7 @@
 #include "conv_ksplit_kernel.hpp"
 #include "conv_pw_kernel.hpp"
 #include "conv_wave_kernel.hpp"
+#include "conv_stem2_kernel.hpp"
 #include "conv_patch32_kernel.hpp"
 
 namespace cprune {
@@ -357,6 +358,50 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     else if (d.dtype == CPRUNE_F16) launch_conv_f16(tile, grid, s, a, p.fixup);
     else launch_conv_bf16(tile, grid, s, a, p.fixup);
   }
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+bool conv_stem2_supported(const cprune_conv_desc& d2, const ConvLayout& lay2, int c_in, int c1) {
+  if (!(c_in >= 1 && c_in <= 3 && c1 >= 1 && c1 <= 32 && d2.c_in == c1 && lay2.cp_in <= 32)) return false;
+  if (!(lay2.nhwc && d2.groups == 1 && d2.kh == 3 && d2.kw == 3 && d2.stride == 1 && d2.pad == 1)) return false;
+  if (d2.has_residual || lay2.pool == 2 || (lay2.pool && ((d2.h | d2.w) & 1))) return false;
+  const long tiles = (long)d2.n * ((d2.h + 7) / 8) * ((d2.w + 15) / 16);
+  const int mb = d2.c_out <= 16 ? 1 : (d2.c_out <= 32 ? 2 : 4);
+  const long groups = tiles * ((d2.c_out + mb * 16 - 1) / (mb * 16));
+  return groups * tiles < (1L << 32);   // multiply-high tile decode
+}
+
+int launch_conv_stem2(const cprune_conv_desc& d2, const ConvLayout& lay2, const void* x_nchw, int c_in,
+                      const void* w1_packed, const float* b1, int c1, int act1, const void* w2, const float* b2,
+                      void* y, hipStream_t s) {
+  if (!conv_stem2_supported(d2, lay2, c_in, c1)) return CPRUNE_ERR_UNSUPPORTED;
+  const size_t es = dtype_size(d2.dtype);
+  const int mb = d2.c_out <= 16 ? 1 : (d2.c_out <= 32 ? 2 : 4);
+  Stem2Args a;
+  a.x = x_nchw; a.w1 = w1_packed; a.b1 = b1; a.C = c_in; a.C1 = c1; a.Cp1 = lay2.cp_in; a.act1 = act1;
+  PatchArgs& pa = a.p;
+  pa.x = nullptr; pa.w = w2; pa.bias = b2; pa.res = nullptr; pa.y = y;
+  pa.N = d2.n; pa.H = d2.h; pa.W = d2.w; pa.O = d2.c_out; pa.Cp = lay2.cp_in; pa.Cop = lay2.cp_out;
+  pa.tiles_n = d2.n;
+  pa.pool = lay2.pool;
+  pa.tiles_y = (d2.h + 7) / 8;
+  pa.tiles_x = (d2.w + 15) / 16;
+  pa.tiles_m = (d2.c_out + mb * 16 - 1) / (mb * 16);
+  pa.x_bytes = 0;
+  pa.w_bytes = (unsigned)((size_t)d2.c_out * 9 * lay2.cp_in * es);
+  pa.act = d2.act;
+  pa.vec_out = (lay2.cp_out % 4) == 0 ? 1 : 0;
+  pa.m_major = 0;
+  pa.magic_s = 0; pa.magic_xy = 0;
+  pa.magic_m = magic_for((unsigned)pa.tiles_m);
+  pa.magic_x = magic_for((unsigned)pa.tiles_x); pa.magic_y = magic_for((unsigned)pa.tiles_y);
+  dim3 grid((unsigned)(pa.tiles_n * pa.tiles_y * pa.tiles_x * pa.tiles_m));
+  int rc;
+  if (d2.dtype == CPRUNE_F32) rc = launch_conv_stem2_f32(mb, grid, s, a);
+  else if (d2.dtype == CPRUNE_F16) rc = launch_conv_stem2_f16(mb, grid, s, a);
+  else rc = launch_conv_stem2_bf16(mb, grid, s, a);
+  if (rc != CPRUNE_OK) return rc;
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }

@@ -80,6 +80,68 @@ __device__ __forceinline__ void mma_round(const uint4 (&af)[MB], const uint4 (&b
   }
 }
 
+// Epilogue of the patch tilings: wavefront `wave` holds NB 16-pixel blocks (pixel id = wave * NB * 16 + j * 16 + r in
+// the (image, row, column) order of a TH x TW tile) x MB filter blocks; bias, residual, activation, 16-byte
+// channels-last stores, or the 2x2 / stride-2 max-pool fused behind the activation.
+template <typename T, int MB, int TH, int TW, int NB>
+__device__ __forceinline__ void patch_epilogue(const PatchArgs& a, float4_t (&acc)[MB][NB], int wave, int r, int g4,
+                                               int n0, int ty0, int tx0, int o0) {
+  ConvArgs e;
+  e.bias = a.bias; e.res = a.res; e.y = a.y; e.O = a.O; e.Cop = a.Cop; e.act = a.act; e.vec_out = a.vec_out; e.pool4 = 0;
+  if (!a.pool) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const int id = wave * (NB * 16) + j * 16 + r;
+      const int img = id / (TH * TW), ir = id % (TH * TW);
+      const int oy = ty0 + ir / TW, ox = tx0 + ir % TW, n = n0 + img;
+      if (n >= a.N || oy >= a.H || ox >= a.W) continue;
+      const int p = (n * a.H + oy) * a.W + ox;
+#pragma unroll
+      for (int i = 0; i < MB; ++i) nhwc_store4<T>(e, acc[i][j], p, o0 + i * 16 + 4 * g4);
+    }
+  } else {
+    // bias + activation, then the max over each 2x2 window.  Horizontal partner: lane
+    // r ^ 1.  Vertical partner: lane r ^ TW when a 16-pixel block holds several rows,
+    // else the same lane of the neighbouring block.  The activation is monotone, so
+    // max(act(.)) equals act-then-pool.  The even/even corner of each window stores.
+    e.act = CPRUNE_ACT_NONE;
+    e.bias = nullptr;
+    const int hp = a.H >> 1, wp = a.W >> 1;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      const int o = o0 + i * 16 + 4 * g4;
+      float4_t v[NB];
+      const float4_t bias = load_bias4(a.bias, a.O, o);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          float x = acc[i][j][c] + bias[c];
+          x = apply_act(x, a.act);
+          x = fmaxf(x, __shfl_xor(x, 1, 64));
+          if constexpr (TW < 16) x = fmaxf(x, __shfl_xor(x, TW, 64));
+          v[j][c] = x;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        float4_t m = v[j];
+        if constexpr (TW == 16) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) m[c] = fmaxf(m[c], v[j ^ 1][c]);
+        }
+        const int id = wave * (NB * 16) + j * 16 + r;
+        const int img = id / (TH * TW), ir = id % (TH * TW);
+        const int ty = ir / TW, tx = ir % TW;
+        const int oy = ty0 + ty, ox = tx0 + tx, n = n0 + img;
+        if ((ty & 1) || (tx & 1) || n >= a.N || oy >= a.H || ox >= a.W) continue;
+        const int p = (n * hp + (oy >> 1)) * wp + (ox >> 1);
+        nhwc_store4<T>(e, m, p, o);
+      }
+    }
+  }
+}
+
 template <typename T, int MB, int TH, int TW, int NI, int KQ, int KS>
 __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
   constexpr int NT = 256 * KS;            // KS groups of 4 wavefronts share a tile: each takes 1/KS of the rounds
@@ -301,60 +363,7 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
   }
 
   // ---- epilogue ----
-  ConvArgs e;
-  e.bias = a.bias; e.res = a.res; e.y = a.y; e.O = a.O; e.Cop = a.Cop; e.act = a.act; e.vec_out = a.vec_out; e.pool4 = 0;
-  if (!a.pool) {
-#pragma unroll
-    for (int j = 0; j < NB; ++j) {
-      const int id = wave * (NB * 16) + j * 16 + r;
-      const int img = id / (TH * TW), ir = id % (TH * TW);
-      const int oy = ty0 + ir / TW, ox = tx0 + ir % TW, n = n0 + img;
-      if (n >= a.N || oy >= a.H || ox >= a.W) continue;
-      const int p = (n * a.H + oy) * a.W + ox;
-#pragma unroll
-      for (int i = 0; i < MB; ++i) nhwc_store4<T>(e, acc[i][j], p, o0 + i * 16 + 4 * g4);
-    }
-  } else {
-    // bias + activation, then the max over each 2x2 window.  Horizontal partner: lane
-    // r ^ 1.  Vertical partner: lane r ^ TW when a 16-pixel block holds several rows,
-    // else the same lane of the neighbouring block.  The activation is monotone, so
-    // max(act(.)) equals act-then-pool.  The even/even corner of each window stores.
-    e.act = CPRUNE_ACT_NONE;
-    e.bias = nullptr;
-    const int hp = a.H >> 1, wp = a.W >> 1;
-#pragma unroll
-    for (int i = 0; i < MB; ++i) {
-      const int o = o0 + i * 16 + 4 * g4;
-      float4_t v[NB];
-      const float4_t bias = load_bias4(a.bias, a.O, o);
-#pragma unroll
-      for (int j = 0; j < NB; ++j) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          float x = acc[i][j][c] + bias[c];
-          x = apply_act(x, a.act);
-          x = fmaxf(x, __shfl_xor(x, 1, 64));
-          if constexpr (TW < 16) x = fmaxf(x, __shfl_xor(x, TW, 64));
-          v[j][c] = x;
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        float4_t m = v[j];
-        if constexpr (TW == 16) {
-#pragma unroll
-          for (int c = 0; c < 4; ++c) m[c] = fmaxf(m[c], v[j ^ 1][c]);
-        }
-        const int id = wave * (NB * 16) + j * 16 + r;
-        const int img = id / (TH * TW), ir = id % (TH * TW);
-        const int ty = ir / TW, tx = ir % TW;
-        const int oy = ty0 + ty, ox = tx0 + tx, n = n0 + img;
-        if ((ty & 1) || (tx & 1) || n >= a.N || oy >= a.H || ox >= a.W) continue;
-        const int p = (n * hp + (oy >> 1)) * wp + (ox >> 1);
-        nhwc_store4<T>(e, m, p, o);
-      }
-    }
-  }
+  patch_epilogue<T, MB, TH, TW, NB>(a, acc, wave, r, g4, n0, ty0, tx0, o0);
 }
 
 // Patch variants: id, mb, th, tw, ni (images per tile, for maps smaller than the tile),

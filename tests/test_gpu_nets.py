@@ -297,6 +297,60 @@ def test_pooled_layer_every_variant(orc, cfg):
     assert ran >= 12 and "conv_wave_kernel" in names and "conv_patch_kernel" in names, (ran, names)
 
 
+@pytest.mark.parametrize("cfg", [
+    # c0, c1, c2, hw, pool, batch, dtype: image -> 3x3 conv -> 3x3 conv [-> 2x2 pool] as one kernel
+    (3, 28, 29, 32, True, 5, B.F32),      # the opening of the benchmark's network
+    (3, 19, 45, 13, False, 3, B.F32),     # ragged tiles, two filter tiles of the second layer
+    (1, 7, 12, 10, True, 2, B.F32),       # one image channel, one filter block
+    (2, 32, 70, 18, True, 2, B.BF16),     # 16-bit, 32 first-layer filters, more than one filter tile
+    (3, 30, 33, 24, False, 4, B.F16),
+])
+def test_first_two_layers_as_one_kernel(orc, cfg):
+    c0, c1, c2, hw, pool, batch, dtype = cfg
+    print("stem2 probe", cfg, flush=True)
+    net = synth.NetSpec(f"stem2probe_{c0}_{c1}_{c2}_{hw}_{int(pool)}", c0, hw, hw)
+    a = net.add(synth.Layer("conv", -1, c0, c1, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="a"))
+    b = net.add(synth.Layer("conv", a, c1, c2, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="b"))
+    if pool:
+        net.add(synth.Layer("maxpool", b, c2, c2, k=2, stride=2, name="pool"))
+    cid = 80 + hw
+    params = synth.layer_params(net, cid)
+    x = synth.net_input(net, cid, batch)
+    ref_layers, _ = orc.prune_net(net, params)
+    ref = orc.forward(net, ref_layers, x)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), dtype)
+    handle = pipeline.build_net(net, layers, batch, dtype, tune=False)
+    xd = torch.from_numpy(x).cuda().to(B.TORCH_DTYPE[dtype])
+    assert not handle.layer_fused(0)
+    apart = handle.forward(xd).float().cpu().numpy()
+    handle.fuse_first_layers(True)
+    assert handle.layer_fused(0)
+    with pytest.raises(B.CPruneError):
+        handle.set_layer_variant(1, 0)          # runs inside the fused kernel: no variants
+    fused = handle.forward(xd).float().cpu().numpy()
+    fused_graph = handle.forward(xd, use_graph=True).float().cpu().numpy()
+    small = handle.forward(xd[:1]).float().cpu().numpy()
+    handle.fuse_first_layers(False)
+    again = handle.forward(xd).float().cpu().numpy()
+    handle.close()
+    tol = TOL[dtype]
+    assert nmax(apart, ref) < tol and nmax(fused, ref) < tol, (nmax(apart, ref), nmax(fused, ref))
+    assert np.array_equal(fused, fused_graph) and np.array_equal(apart, again)
+    assert nmax(small, ref[:1]) < tol
+
+
+def test_first_two_layers_fusion_needs_the_shape(orc):
+    """A network that opens with a strided first layer has no such form."""
+    net = synth.resnet18(10, 32)
+    params = synth.layer_params(net, 3)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), B.F32)
+    handle = pipeline.build_net(net, layers, 1, B.F32, tune=False)
+    with pytest.raises(B.CPruneError) as e:
+        handle.fuse_first_layers(True)
+    assert e.value.status == B.ERR_UNSUPPORTED
+    handle.close()
+
+
 @pytest.mark.parametrize("which,dtype", [("mobilenetv2", B.F32), ("mnasnet", B.F32), ("mobilenetv2", B.F16),
                                          ("mnasnet", B.F16)])
 def test_depthwise_fused_into_projection(orc, which, dtype):
