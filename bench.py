@@ -28,18 +28,19 @@ if ROOT not in sys.path:
 
 PEAK = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}   # dense MFMA TFLOP/s, MI355X
 # Bytes between L2 and fabric per launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the counter
-# reads for a copy kernel of known size), by (kernel instantiation, batch, layers it ran per step), for
-# the default workload: from the rocprofv3 counter runs summarised in
-# profiles/vgg16_b64_f32_hbm_traffic.md.  The timed selection decides which layers a kernel runs; when
-# that differs from the profiled run the figure does not apply and null is reported.
+# reads for a copy kernel of known size), by (kernel instantiation, batch, layers it ran), for the default
+# workload: from the rocprofv3 counter runs summarised in profiles/vgg16_b64_f32_hbm_traffic.md.  The
+# timed selection decides which layers a kernel runs; when that differs from the profiled runs the
+# figure does not apply and null is reported.
 TRAFFIC = {
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, 3): 8473989,     # conv3, 5, 6; algorithmic 5.8e6
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, 4): 9379725,     # conv3, 5, 6, 7 (a second counter run with
-                                                                        # conv7 pinned to this tile); algorithmic 5.5e6
-    ("conv_wave_kernel<float, 5, 1, 3>", 64, 2): 10499286,              # conv8, 10; algorithmic 3.7e6
-    ("conv_wave_kernel<float, 2, 2, 2>", 64, 1): 13501660,              # conv7; algorithmic 4.7e6
-    ("conv_wave_kernel<float, 2, 2, 4>", 64, 1): 15049661,              # conv9; algorithmic 4.8e6
-    ("conv_patch32_kernel<float, 1, 1, 4, 8, 16, 1, 1>", 64, 1): 10119905,   # conv4; algorithmic 8.2e6
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, ("conv3", "conv4", "conv5", "conv6")): 8865762,   # algorithmic 6.4e6
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, ("conv3", "conv5", "conv6")): 8473989,            # algorithmic 5.8e6
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, ("conv3", "conv5", "conv6", "conv7")): 9379725,   # algorithmic 5.5e6
+    ("conv_wave_kernel<float, 5, 1, 3>", 64, ("conv8", "conv10")): 10499292,                             # algorithmic 3.7e6
+    ("conv_wave_kernel<float, 2, 2, 2>", 64, ("conv7",)): 13501668,                                      # algorithmic 4.7e6
+    ("conv_wave_kernel<float, 2, 2, 4>", 64, ("conv9",)): 15049669,                                      # algorithmic 4.8e6
+    ("conv_patch32_kernel<float, 1, 1, 4, 8, 16, 1, 1>", 64, ("conv4",)): 10119905,                      # algorithmic 8.2e6
+    ("conv_stem2_kernel<float, 2>", 64, ("conv2",)): 3351374,             # conv1 + conv2; algorithmic 2.7e6
 }
 
 
@@ -174,14 +175,14 @@ def main():
             kern = B.cprune_tile_variant_name(v, channels_last=not first, dtype=dt)
         fl, carried = fl + carried, 0.0
         note = (" + fix-up" if sk > 0 else "") + (" (2x2 map as one matrix)" if (ho == 2 and sk >= 0) else "")
-        g = by_kernel.setdefault(kern, [0, 0.0, 0.0])
-        g[0] += 1; g[1] += m; g[2] += fl
+        g = by_kernel.setdefault(kern, [0, 0.0, 0.0, []])
+        g[0] += 1; g[1] += m; g[2] += fl; g[3].append(L.name)
         per_layer.append({"layer": L.name, "c_in": cin, "c_out": cout, "hw": ho, "us": round(m * 1e3, 2),
                           "tflops": round(fl / (m * 1e-3) / 1e12, 2), "tile": f"{tm}x{tp}/s{sk}",
                           "kernel": kern + note})
     # the dominant kernel: the instantiation with the most device time per step
     dom = max(by_kernel, key=lambda k: by_kernel[k][1])
-    d_n, d_ms, d_fl = by_kernel[dom]
+    d_n, d_ms, d_fl, d_layers = by_kernel[dom]
     achieved = d_fl / (d_ms * 1e-3) / 1e12
     agg = conv_flops / (conv_ms * 1e-3) / 1e12
 
@@ -201,7 +202,8 @@ def main():
         "roofline": {"bound": "mfma", "kernel": dom, "launches_per_step": d_n,
                      "achieved": round(achieved, 2), "peak": PEAK[args.dtype], "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK[args.dtype], 4),
-                     "traffic": TRAFFIC.get((dom, args.batch, d_n)),
+                     "layers": d_layers,
+                     "traffic": TRAFFIC.get((dom, args.batch, tuple(d_layers))),
                      "traffic_unit": "bytes per launch between L2 and fabric (FETCH_SIZE + WRITE_SIZE, scaled)",
                      "avg_launch_us": round(d_ms / d_n * 1e3, 2),
                      "useful_gflop_per_launch": round(d_fl / d_n / 1e9, 3),
