@@ -307,7 +307,11 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
           // read to just before its first use and the four wavefronts take turns on the LDS and
           // the matrix pipes).  With many resident wavefronts the scheduler's own order is faster.
           if constexpr (NI > 1) __builtin_amdgcn_sched_barrier(0);
+          // a wavefront that has its operands goes first: with several tiles resident, their staging instructions
+          // otherwise take issue slots between the MFMAs (1-3 % on the layers of this kernel)
+          __builtin_amdgcn_s_setprio(1);
           mma_round<T, MBC, NB, MB, NS>(af[idx % (PF + 1)], bf[idx % (PF + 1)], accs, idx);
+          __builtin_amdgcn_s_setprio(0);
           if constexpr (NI > 1) __builtin_amdgcn_sched_barrier(0);
         }
       };
