@@ -216,7 +216,9 @@ __global__ __launch_bounds__(256) void conv_stem2_kernel(Stem2Args a) {
 #pragma unroll
     for (int rnd = 0; rnd < NR; ++rnd) {
       if (rnd + 1 < NR) fetch(rnd + 1, af[(rnd + 1) & 1], bf[(rnd + 1) & 1]);
+      __builtin_amdgcn_s_setprio(1);
       mma_slab<T, MBC, NB, MB>(af[rnd & 1], bf[rnd & 1], acc);
+      __builtin_amdgcn_s_setprio(0);
     }
   };
   switch (mb_count) {
