@@ -100,6 +100,51 @@ int cprune_gather_pruned_weights(const float* w, int c_out, int c_in, int kh, in
                                  cprune_dtype out_dtype, void* w_out, float* bias_out,
                                  void* stream);
 
+/* The ranking and gather of a whole network as one plan (the pruning step of Algorithm 1:
+ * the filters chosen per Section 3.5 are removed from every layer they touch and the next
+ * layers' input channels follow, Section 2.1 / Fig. 2).  Same arithmetic as the two calls
+ * above, layer by layer; three launches per run whatever the number of layers: every ranked
+ * layer's scores, every ranked layer's kept list, every layer's gathered and folded weights.
+ *
+ * One entry per layer, in network order (host array):
+ *   w            device, raw fp32 weights [c_out][c_in][kh][kw] (c_in = channels per filter;
+ *                a fully connected layer behind a c x h x w map is c_in = c, kh x kw = h x w);
+ *                NULL = a layer without weights (a pool): every other field 0 / -1 / NULL
+ *   keep         > 0: the layer's filters are ranked and `keep` survive (rows_from must be the
+ *                layer's own index); 0: not ranked
+ *   score_with   host [n_score_with] indices of layers with the same c_out whose filter sums
+ *                are added to this ranked layer's, in this order (cprune_rank_filter_group)
+ *   rows_from    -1: every filter stays; else the ranked layer whose kept list selects this
+ *                layer's filters
+ *   cols_from    -1: every input channel stays; else the ranked layer whose kept list selects
+ *                this layer's input channels (that layer's c_out = this layer's c_in)
+ *   gamma..var, conv_bias   device fp32 [c_out] or NULL, as cprune_gather_pruned_weights
+ *   w_out        device [rows kept][columns kept][kh][kw] in the plan's dtype
+ *   bias_out     device fp32 [rows kept]; may be NULL when there is neither BN nor conv_bias
+ *   kept_out     device int32 [keep], ascending; required for ranked layers
+ * The plan owns a few KB of device memory (its tables and the scores); inputs and outputs
+ * stay the caller's and must outlive it.  create and destroy synchronise; run only enqueues. */
+typedef struct {
+  const float* w;
+  int32_t c_out, c_in, kh, kw;
+  int32_t keep;
+  int32_t rows_from, cols_from;
+  const int32_t* score_with;
+  int32_t n_score_with;
+  const float *gamma, *beta, *mean, *var, *conv_bias;
+  void* w_out;
+  float* bias_out;
+  int32_t* kept_out;
+} cprune_prune_layer;
+typedef struct cprune_prune_plan cprune_prune_plan;
+int cprune_prune_plan_create(const cprune_prune_layer* layers, int n_layers, float eps,
+                             cprune_dtype out_dtype, cprune_prune_plan** out);
+int cprune_prune_plan_run(cprune_prune_plan* plan, void* stream);
+/* Weight elements one run reads (scoring + gather) and writes; host outs. */
+int cprune_prune_plan_traffic(const cprune_prune_plan* plan, int64_t* weights_read_out,
+                              int64_t* weights_written_out);
+int cprune_prune_plan_destroy(cprune_prune_plan* plan);
+
 /* Activation channel gather (Section 2.1: removing input channels c_i):
  * y[n][i][h][w] = x[n][idx[i]][h][w]; x [n][c][h][w], y [n][n_idx][h][w], same dtype. */
 int cprune_gather_channels(const void* x, int n, int c, int h, int w, cprune_dtype dtype,

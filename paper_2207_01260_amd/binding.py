@@ -37,9 +37,19 @@ class LayerDesc(C.Structure):
                  "act")] + [("weight", C.c_void_p), ("bias", C.c_void_p)]
 
 
+class PruneLayer(C.Structure):
+    _fields_ = [("w", C.c_void_p)] + [(n, C.c_int32) for n in
+                                      ("c_out", "c_in", "kh", "kw", "keep", "rows_from", "cols_from")] + \
+               [("score_with", C.POINTER(C.c_int32)), ("n_score_with", C.c_int32)] + \
+               [(n, C.c_void_p) for n in ("gamma", "beta", "mean", "var", "conv_bias", "w_out", "bias_out",
+                                          "kept_out")]
+
+
 EXPORTS = [
     "cprune_status_string", "cprune_last_hip_error",
     "cprune_rank_filters_workspace_bytes", "cprune_rank_filters", "cprune_rank_filter_group",
+    "cprune_prune_plan_create", "cprune_prune_plan_run", "cprune_prune_plan_traffic",
+    "cprune_prune_plan_destroy",
     "cprune_gather_pruned_weights", "cprune_gather_channels",
     "cprune_num_tile_variants", "cprune_tile_variant_info", "cprune_tile_variant_name",
     "cprune_conv_workspace_bytes",
@@ -126,6 +136,82 @@ def cprune_rank_filters(w: torch.Tensor, keep: int, want_scores=True, want_order
                                    C.c_size_t(ws.numel()), _stream(stream))
     _check(st, "cprune_rank_filters")
     return scores, order, kept
+
+
+class PrunePlan:
+    """Owner of a cprune_prune_plan: the ranking and gather of a whole network in three launches.
+    `entries`: one dict per layer in network order, None for layers without weights; keys w (fp32
+    device tensor, 4-d), keep (0 = not ranked), rows_from, cols_from (-1 = all), score_with (list),
+    bn (gamma, beta, mean, var) or None, conv_bias or None.  Outputs are allocated here once:
+    .w_out[i], .bias_out[i], .kept[i] (ranked layers)."""
+
+    def __init__(self, entries, eps: float, out_dtype: int = F32):
+        n = len(entries)
+        arr = (PruneLayer * n)()
+        self.w_out, self.bias_out, self.kept = {}, {}, {}
+        self._keep_alive = []
+        dev = None
+        keep_of = {i: int(e["keep"]) for i, e in enumerate(entries) if e is not None and e.get("keep", 0) > 0}
+        for i, e in enumerate(entries):
+            a = arr[i]
+            a.rows_from = a.cols_from = -1
+            if e is None:
+                continue
+            w = e["w"]
+            assert w.dtype == torch.float32 and w.dim() == 4 and w.is_cuda and w.is_contiguous()
+            dev = w.device
+            c_out, c_in, kh, kw = w.shape
+            a.w = w.data_ptr()
+            a.c_out, a.c_in, a.kh, a.kw = c_out, c_in, kh, kw
+            a.keep = int(e.get("keep", 0))
+            a.rows_from = int(e.get("rows_from", -1))
+            a.cols_from = int(e.get("cols_from", -1))
+            sw = list(e.get("score_with") or [])
+            if sw:
+                lst = (C.c_int32 * len(sw))(*sw)
+                self._keep_alive.append(lst)
+                a.score_with = C.cast(lst, C.POINTER(C.c_int32))
+            a.n_score_with = len(sw)
+            bn = e.get("bn")
+            if bn is not None:
+                a.gamma, a.beta, a.mean, a.var = (t.data_ptr() for t in bn)
+            cb = e.get("conv_bias")
+            if cb is not None:
+                a.conv_bias = cb.data_ptr()
+            n_out = keep_of.get(a.rows_from, c_out) if a.rows_from >= 0 else c_out
+            n_in = keep_of.get(a.cols_from, c_in) if a.cols_from >= 0 else c_in
+            self.w_out[i] = torch.empty((n_out, n_in, kh, kw), dtype=TORCH_DTYPE[out_dtype], device=dev)
+            a.w_out = self.w_out[i].data_ptr()
+            if bn is not None or cb is not None:
+                self.bias_out[i] = torch.empty(n_out, dtype=torch.float32, device=dev)
+                a.bias_out = self.bias_out[i].data_ptr()
+            if a.keep > 0:
+                self.kept[i] = torch.empty(a.keep, dtype=torch.int32, device=dev)
+                a.kept_out = self.kept[i].data_ptr()
+            self._keep_alive.append((w, bn, cb))
+        self._h = C.c_void_p(None)
+        st = lib().cprune_prune_plan_create(arr, C.c_int(n), C.c_float(eps), C.c_int(out_dtype), C.byref(self._h))
+        _check(st, "cprune_prune_plan_create")
+
+    def run(self, stream=None) -> None:
+        _check(lib().cprune_prune_plan_run(self._h, _stream(stream)), "cprune_prune_plan_run")
+
+    def traffic(self):
+        """-> (weight elements read, weight elements written) per run."""
+        r, w = C.c_int64(0), C.c_int64(0)
+        _check(lib().cprune_prune_plan_traffic(self._h, C.byref(r), C.byref(w)), "cprune_prune_plan_traffic")
+        return int(r.value), int(w.value)
+
+    def close(self):
+        if self._h:
+            lib().cprune_prune_plan_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def cprune_rank_filter_group(ws_list, keep: int, want_scores=True, want_order=True, stream=None):

@@ -65,6 +65,44 @@ def prune_net(net: synth.NetSpec, dev_params: List[dict], dtype: int = B.F32,
     return layers, kept
 
 
+def prune_plan(net: synth.NetSpec, dev_params: List[dict], dtype: int = B.F32,
+               keep_override: Optional[Dict[int, int]] = None) -> B.PrunePlan:
+    """The same pruning as prune_net, as one plan over the whole network: built once (outputs
+    allocated once), every run is three launches.  plan_layers(net, dev_params, plan) gives the
+    per-layer dicts prune_net returns."""
+    entries = []
+    for i, (L, p) in enumerate(zip(net.layers, dev_params)):
+        if L.kind == "conv":
+            own = L.prune_out == "own"
+            entries.append({
+                "w": p["w"], "keep": (keep_override or {}).get(i, p["keep"]) if own else 0,
+                "rows_from": i if own else (L.prune_out if isinstance(L.prune_out, int) else -1),
+                "cols_from": L.prune_in if (L.prune_in is not None and L.groups == 1) else -1,
+                "score_with": list(L.score_with or []) if own else [],
+                "bn": (p["gamma"], p["beta"], p["mean"], p["var"]) if L.bn else None})
+        elif L.kind == "fc":
+            w = p["w"]
+            entries.append({"w": w.reshape(w.shape[0], w.shape[1], 1, 1), "keep": 0, "rows_from": -1,
+                            "cols_from": L.prune_in if L.prune_in is not None else -1})
+        else:
+            entries.append(None)
+    return B.PrunePlan(entries, BN_EPS, dtype)
+
+
+def plan_layers(net: synth.NetSpec, dev_params: List[dict], plan: B.PrunePlan):
+    """(layers, kept) of a plan's outputs, in the form prune_net returns them."""
+    layers = []
+    for i, (L, p) in enumerate(zip(net.layers, dev_params)):
+        q: dict = {}
+        if L.kind == "conv":
+            q["w"], q["b"] = plan.w_out[i], plan.bias_out.get(i)
+        elif L.kind == "fc":
+            w = plan.w_out[i]
+            q["w"], q["b"] = w.reshape(w.shape[0], w.shape[1]), p["b"]
+        layers.append(q)
+    return layers, dict(plan.kept)
+
+
 def layer_descs(net: synth.NetSpec, layers: List[dict]) -> List[B.LayerDesc]:
     """cprune_layer_desc array for a pruned network (channel counts read off the weights)."""
     kind = {"conv": B.LAYER_CONV, "maxpool": B.LAYER_MAXPOOL, "gavgpool": B.LAYER_GAVGPOOL,

@@ -142,7 +142,7 @@ def test_gather_with_conv_bias(orc):
     assert np.array_equal(b_only.cpu().numpy(), cb[ko])
 
 
-@pytest.mark.parametrize("dt", [B.F32, B.F16])
+@pytest.mark.parametrize("dt", [B.F32, B.F16, B.BF16])
 def test_gather_channels(orc, dt):
     x = synth.tensor_normal((3, 37, 9, 11), 115)
     idx = np.array([0, 5, 6, 20, 36], np.int32)
@@ -284,6 +284,53 @@ def test_maxpool_gavgpool_fc(orc):
         bf = synth.tensor_normal((c,), 144, std=0.1)
         y = B.cprune_fc(dev(xf), dev(wf), dev(bf)).cpu().numpy()
         assert nmax(y, orc.fc(xf, wf, bf)) < 1e-4
+
+
+@pytest.mark.parametrize("which,dtype", [("vgg16", B.F32), ("vgg16", B.F16), ("resnet18_shortcuts", B.F32),
+                                         ("mobilenetv2", B.BF16), ("resnet18", B.F32)])
+def test_prune_plan_bit_exact(orc, which, dtype):
+    """The whole-network plan (three launches) against the oracle's layer-by-layer pruning: kept
+    lists, folded weights and biases bit for bit; 16-bit weights = the fp32 result rounded to
+    nearest even.  Run twice: the second run overwrites the same outputs with the same bits."""
+    from paper_2207_01260_amd import pipeline
+    print("prune plan", which, dtype, flush=True)
+    net, cid = {"vgg16": (synth.vgg16(10, 32), 2), "resnet18": (synth.resnet18(1000, 64), 3),
+                "resnet18_shortcuts": (synth.resnet18(100, 64, prune_shortcuts=True), 3),
+                "mobilenetv2": (synth.mobilenetv2(1000, 64), 4)}[which]
+    params = synth.layer_params(net, cid)
+    ref_layers, ref_kept = orc.prune_net(net, params)
+    dparams = pipeline.upload_params(params)
+    plan = pipeline.prune_plan(net, dparams, dtype)
+    for rep in range(2):
+        plan.run()
+        torch.cuda.synchronize()
+        layers, kept = pipeline.plan_layers(net, dparams, plan)
+        assert sorted(kept) == sorted(ref_kept)
+        for i in kept:
+            assert np.array_equal(kept[i].cpu().numpy(), ref_kept[i]), (which, i, rep)
+        for i, (q, r) in enumerate(zip(layers, ref_layers)):
+            if "w" not in r:
+                assert "w" not in q
+                continue
+            want = torch.from_numpy(np.ascontiguousarray(r["w"])).to(B.TORCH_DTYPE[dtype])
+            got = q["w"].cpu().reshape(want.shape)
+            assert int((got != want).sum()) == 0, (which, i, rep)
+            if r.get("b") is not None:
+                assert np.array_equal(q["b"].cpu().numpy(), r["b"]), (which, i, rep)
+    rd, wr = plan.traffic()
+    assert rd > 0 and wr > 0
+    plan.close()
+
+
+def test_prune_plan_rejects_bad_references():
+    w = dev(synth.tensor_normal((8, 4, 3, 3), 140))
+    ok = {"w": w, "keep": 5, "rows_from": 0, "cols_from": -1}
+    B.PrunePlan([ok], EPS).close()
+    for bad in ({"w": w, "keep": 9, "rows_from": 0, "cols_from": -1},        # keep > c_out
+                {"w": w, "keep": 5, "rows_from": -1, "cols_from": -1},       # ranked layer must select its own rows
+                {"w": w, "keep": 0, "rows_from": 0, "cols_from": -1}):       # refers to a layer that is not ranked
+        with pytest.raises(B.CPruneError):
+            B.PrunePlan([bad], EPS)
 
 
 def test_rank_filter_group(orc):
