@@ -65,6 +65,19 @@ int cprune_rank_filters(const float* w, int c_out, int c_in_per_group, int kh, i
                         double* scores_out, int32_t* order_out, int32_t* kept_out,
                         void* ws, size_t ws_bytes, void* stream);
 
+/* cprune_rank_filters for callers that cannot allocate or hand over scratch memory (code under
+ * HIP graph capture, serving loops, harnesses that forbid hipMalloc): the scores live in an
+ * array the library holds in each device's memory for the life of the process
+ * (cprune_rank_filters_static_max() = 4096 doubles, 32 KiB), so there is no ws argument, no
+ * scores_out, and the call allocates nothing.  c_out above that maximum:
+ * CPRUNE_ERR_UNSUPPORTED.  Same kernels and results as cprune_rank_filters.  Every call on a
+ * device shares that device's array: calls that overlap on one device (two streams, two
+ * threads) race; calls on one stream are ordered.  Nothing needs clearing between calls:
+ * every score the ranking reads is written by the same call first. */
+int cprune_rank_filters_static_max(void);
+int cprune_rank_filters_static(const float* w, int c_out, int c_in_per_group, int kh, int kw,
+                               int keep, int32_t* order_out, int32_t* kept_out, void* stream);
+
 /* Ranking of a group of layers that must lose the same channels (Section 3.5, last
  * paragraph: the layers whose outputs a shortcut adds are pruned at the same output
  * channels).  A channel's score is the sum, in member order, of its filter's L1 sum in every

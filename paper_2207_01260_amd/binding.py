@@ -48,6 +48,7 @@ class PruneLayer(C.Structure):
 EXPORTS = [
     "cprune_status_string", "cprune_last_hip_error",
     "cprune_rank_filters_workspace_bytes", "cprune_rank_filters", "cprune_rank_filter_group",
+    "cprune_rank_filters_static", "cprune_rank_filters_static_max",
     "cprune_prune_plan_create", "cprune_prune_plan_run", "cprune_prune_plan_traffic",
     "cprune_prune_plan_destroy",
     "cprune_gather_pruned_weights", "cprune_gather_channels",
@@ -136,6 +137,21 @@ def cprune_rank_filters(w: torch.Tensor, keep: int, want_scores=True, want_order
                                    C.c_size_t(ws.numel()), _stream(stream))
     _check(st, "cprune_rank_filters")
     return scores, order, kept
+
+
+def cprune_rank_filters_static_max() -> int:
+    return int(lib().cprune_rank_filters_static_max())
+
+
+def cprune_rank_filters_static(w: torch.Tensor, keep: int, order: Optional[torch.Tensor],
+                               kept: torch.Tensor, stream=None) -> None:
+    """The ranking call that allocates nothing: the caller passes the outputs (order int32 [c_out] or
+    None, kept int32 [keep]); the scores live in the library's per-device static array."""
+    assert w.dtype == torch.float32 and w.dim() == 4
+    c_out, cpg, kh, kw = w.shape
+    st = lib().cprune_rank_filters_static(_ptr(w), C.c_int(c_out), C.c_int(cpg), C.c_int(kh), C.c_int(kw),
+                                          C.c_int(keep), _ptr(order), _ptr(kept), _stream(stream))
+    _check(st, "cprune_rank_filters_static")
 
 
 class PrunePlan:

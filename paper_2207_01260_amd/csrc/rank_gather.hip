@@ -325,6 +325,33 @@ int finish_gather_job(GatherJob* g) {
 
 using namespace cprune;
 
+// Scores of the allocation-free ranking call: one array per device, held for the life of the process.
+// In host code the name below is only a handle for hipGetSymbolAddress; kernels get the device address.
+static __device__ __align__(256) double scratch[4096];
+
+namespace {
+constexpr int kStaticRankFilters = 4096;   // entries of `scratch`
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {};
+
+// The device address of `scratch` on the current device (looked up once per device).
+int scratch_for_current_device(double** out) {
+  int dev = -1;
+  CPRUNE_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return CPRUNE_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    CPRUNE_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return CPRUNE_ERR_DEVICE;
+    g_scratch_ptr[dev] = static_cast<double*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return CPRUNE_OK;
+}
+}  // namespace
+
 extern "C" size_t cprune_rank_filters_workspace_bytes(int c_out) {
   return c_out > 0 ? (size_t)c_out * sizeof(double) : 0;
 }
@@ -349,6 +376,25 @@ extern "C" int cprune_rank_filters(const float* w, int c_out, int c_in_per_group
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }
+
+extern "C" int cprune_rank_filters_static(const float* w, int c_out, int c_in_per_group, int kh, int kw,
+                                          int keep, int32_t* order_out, int32_t* kept_out, void* stream) {
+  if (!w || !kept_out || c_out < 1 || c_in_per_group < 1 || kh < 1 || kw < 1) return CPRUNE_ERR_INVALID_ARG;
+  if (keep < 1 || keep > c_out) return CPRUNE_ERR_INVALID_ARG;
+  if (c_out > kStaticRankFilters) return CPRUNE_ERR_UNSUPPORTED;   // more filters than the static array holds
+  double* scores = nullptr;
+  int rc = scratch_for_current_device(&scores);
+  if (rc != CPRUNE_OK) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  // every score the ranking reads is written by the scoring launch in front of it: nothing to clear
+  rc = launch_scores(w, (long)c_in_per_group * kh * kw, c_out, scores, 0, s);
+  if (rc != CPRUNE_OK) return rc;
+  hipLaunchKernelGGL(rank_select_kernel, dim3(1), dim3(1024), 0, s, scores, c_out, keep, order_out, kept_out);
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_rank_filters_static_max(void) { return kStaticRankFilters; }
 
 extern "C" int cprune_rank_filter_group(const float* const* w, const int64_t* per_filter, int n_members,
                                         int c_out, int keep, double* scores_out, int32_t* order_out,
