@@ -221,7 +221,7 @@ int cprune_conv2d_bn_relu(const cprune_conv_desc* desc, const void* x, const voi
                           void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
- * Variant selection by timing on the device (paper Section 3.2, Fig. 3: for each
+ * Variant selection by timing on the device (paper Section 3.1, Fig. 3: for each
  * task the compiler generates candidate programs and keeps the one that runs
  * fastest on the target; layers of equal shape share a task).  Times every
  * variant that supports desc with `warmup` untimed and `iters` timed launches on
@@ -240,8 +240,8 @@ void cprune_clear_tile_cache(void);
 int cprune_cached_tile(const cprune_conv_desc* desc, int* variant_out, int* was_timed_out);
 
 /* ------------------------------------------------------------------------
- * Memory-bound layers of the evaluated networks (paper Section 4: VGG-16,
- * ResNet-18, MobileNetV2).
+ * Memory-bound layers of the evaluated networks (the VGG-16 of the motivating
+ * experiment of Section 3, Fig. 1; ResNet-18 and MobileNetV2 of Section 4, Table 1).
  */
 /* max over the in-bounds elements of each k x k window; y [n][c][ho][wo] */
 int cprune_maxpool2d(const void* x, int n, int c, int h, int w, int k, int stride, int pad,
@@ -320,7 +320,7 @@ int cprune_net_output_shape(const cprune_net* net, int* c_out, int* h_out, int* 
 int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out);
 /* The first two layers in one kernel, where the network opens with two 3x3 / stride 1 / pad 1 convolutions,
  * the first on the image (at most 3 channels) with at most 32 filters and read by the second only (the
- * VGG-16 of Sec. 4.1, Table 2; channel counts as Sec. 3.5 leaves them): the first layer's output, the
+ * VGG-16 of the motivating experiment that opens Section 3, Fig. 1; channel counts as Sec. 3.5 leaves them): the first layer's output, the
  * largest activation of such a network, is then never written.  cprune_net_create(tune = 1) times both
  * forms and keeps the faster; this call forces one.  enable: 0 / 1.  CPRUNE_ERR_UNSUPPORTED when the
  * network does not open that way.  Synchronises; recorded graphs are dropped. */
@@ -389,13 +389,62 @@ int cprune_order_tasks(const double* exec_time, const int* n_subgraphs, int n_ta
  * those are built on 16-filter blocks. */
 int cprune_net_task_table(const cprune_net* net, int* task_of_layer, int* n_tasks_out);
 
+/* The key cprune_net_task_table groups by, for layer `layer` (a dense conv / fully connected
+ * layer): key_out, host [CPRUNE_TASK_KEY_INTS], holds the layer's shape at the handle's batch
+ * size, stride, padding, activation, shortcut flag and the layout it runs in (channel strides,
+ * fused pool, channels-last output).  Two layers are one task iff their keys are equal. */
+#define CPRUNE_TASK_KEY_INTS 18
+int cprune_net_task_key(const cprune_net* net, int layer, int32_t* key_out);
+
+/* Section 3.2, Algorithm 1, as a state machine (host only).  The caller owns the models and
+ * does the pruning, tuning, measuring and accuracy evaluation; this object takes the
+ * decisions.  Tasks are caller-chosen 64-bit ids that mean the same task from model to model.
+ *   start(tasks of the input model by descending impact, its latency l_m, its accuracy a_p):
+ *       target latency l_t = beta * l_m.
+ *   next_task: the task to prune next, or *done_out = 1 when the search is over: the accuracy
+ *       of the accepted model is at or below a_goal, no task is left, max_passes passes over
+ *       the list have been made, or a whole pass neither accepted a candidate nor dropped a task.
+ *   then exactly one of
+ *     report_exhausted: the task's layers cannot lose filters; the task is out for good.
+ *     report_latency(l_m of the tuned candidate): l_m >= l_t -> logged as slow, the task stays
+ *       in the list, *needs_accuracy_out = 0; l_m < l_t -> *needs_accuracy_out = 1 and the
+ *       caller must follow with
+ *     report_accuracy(a_s, the candidate's tasks by descending impact): a_s < alpha * a_p ->
+ *       the task is out for good; otherwise the candidate is accepted: it becomes the model,
+ *       its task list minus the tasks that are out becomes the list, l_t = beta * l_m,
+ *       a_p = a_s, and the next pass starts at the head of the new list.
+ * Calls out of this order: CPRUNE_ERR_INVALID_ARG.  The log has one entry per reported
+ * candidate; l_m / a_s are NaN where they were not measured. */
+#define CPRUNE_SEARCH_SLOW 1
+#define CPRUNE_SEARCH_INACCURATE 2
+#define CPRUNE_SEARCH_ACCEPTED 3
+#define CPRUNE_SEARCH_EXHAUSTED 4
+typedef struct cprune_search cprune_search;
+int cprune_search_create(double a_goal, double alpha, double beta, int64_t max_passes,
+                         cprune_search** out);
+int cprune_search_start(cprune_search* s, const int64_t* tasks_by_impact, int n_tasks, double l_m,
+                        double a_p);
+int cprune_search_next_task(cprune_search* s, int64_t* task_out, int* done_out);
+int cprune_search_report_exhausted(cprune_search* s);
+int cprune_search_report_latency(cprune_search* s, double l_m, int* needs_accuracy_out);
+int cprune_search_report_accuracy(cprune_search* s, double a_s, const int64_t* tasks_by_impact,
+                                  int n_tasks, int* accepted_out);
+int cprune_search_log_size(const cprune_search* s);
+int cprune_search_log_entry(const cprune_search* s, int index, int64_t* task_out, double* l_m_out,
+                            double* l_t_out, double* a_s_out, int* verdict_out);
+int cprune_search_destroy(cprune_search* s);
+
 /* ---- measured ceilings (for reporting kernel throughput against what the device
  * delivers, next to its datasheet peaks; the paper reports end-to-end rates only) ----
  * cprune_probe_mfma: rate of back-to-back dense MFMA instructions of `dtype` on register
  * operands, no memory traffic (the better of the 16x16 and the 32x32 block forms); scratch: device, >= cprune_probe_scratch_bytes() (values
  * written there are meaningless); tflops_out: host.  cprune_probe_copy: rate of a plain
  * copy of `bytes` (a multiple of 16) from src to dst (device, 16-byte aligned, not
- * overlapping), counted as bytes read + bytes written; gbps_out: host.  cprune_probe_l2_read:
+ * overlapping), counted as bytes read + bytes written, the fastest of eight launch shapes (4 or
+ * 8 pieces of 16 bytes in flight per thread, cached or non-temporal accesses, one step per
+ * work-group or resident work-groups walking the buffer); gbps_out: host.  cprune_probe_read /
+ * cprune_probe_write: the same for a kernel that only reads `bytes` (scratch16: 16 bytes of
+ * device memory, never written in practice) or only writes them.  cprune_probe_l2_read:
  * GB/s one compute unit reads from L2-resident data with 16-byte-per-lane loads, the form in
  * which a kernel takes MFMA operands straight from global memory; pattern 0: each wavefront-wide
  * load covers 1 KiB of consecutive memory, pattern 1: 16 rows x 64 bytes (an operand tile of a
@@ -405,6 +454,8 @@ size_t cprune_probe_scratch_bytes(void);
 int cprune_probe_mfma(cprune_dtype dtype, void* scratch, size_t scratch_bytes, float* tflops_out,
                       void* stream);
 int cprune_probe_copy(const void* src, void* dst, size_t bytes, float* gbps_out, void* stream);
+int cprune_probe_read(const void* src, void* scratch16, size_t bytes, float* gbps_out, void* stream);
+int cprune_probe_write(void* dst, size_t bytes, float* gbps_out, void* stream);
 size_t cprune_probe_l2_bytes(void);
 int cprune_probe_l2_read(int pattern, const void* buf, size_t buf_bytes, float* scratch,
                          float* gbps_per_cu_out, void* stream);

@@ -62,10 +62,14 @@ EXPORTS = [
     "cprune_net_set_layer_variant", "cprune_net_fuse_depthwise", "cprune_net_fuse_block",
     "cprune_net_fuse_first_layers", "cprune_net_layer_fused",
     "cprune_net_destroy",
-    "cprune_probe_scratch_bytes", "cprune_probe_mfma", "cprune_probe_copy",
+    "cprune_probe_scratch_bytes", "cprune_probe_mfma", "cprune_probe_copy", "cprune_probe_read",
+    "cprune_probe_write",
     "cprune_probe_l2_bytes", "cprune_probe_l2_read",
     "cprune_lcm_step", "cprune_prune_count", "cprune_variant_filter_splits",
-    "cprune_variant_prune_step", "cprune_order_tasks", "cprune_net_task_table",
+    "cprune_variant_prune_step", "cprune_order_tasks", "cprune_net_task_table", "cprune_net_task_key",
+    "cprune_search_create", "cprune_search_start", "cprune_search_next_task",
+    "cprune_search_report_exhausted", "cprune_search_report_latency", "cprune_search_report_accuracy",
+    "cprune_search_log_size", "cprune_search_log_entry", "cprune_search_destroy",
 ]
 
 _lib = None
@@ -440,6 +444,71 @@ def cprune_order_tasks(exec_time, n_subgraphs):
     return list(order), list(impact)
 
 
+class Search:
+    """Owner of a cprune_search object (the decisions of Algorithm 1); tasks are integers here."""
+
+    def __init__(self, a_goal: float, alpha: float, beta: float, max_passes: int):
+        self._h = C.c_void_p(None)
+        _check(lib().cprune_search_create(C.c_double(a_goal), C.c_double(alpha), C.c_double(beta),
+                                          C.c_int64(min(int(max_passes), (1 << 62))), C.byref(self._h)),
+               "cprune_search_create")
+
+    @staticmethod
+    def _ids(tasks):
+        return (C.c_int64 * max(len(tasks), 1))(*tasks), C.c_int(len(tasks))
+
+    def start(self, tasks_by_impact, l_m: float, a_p: float) -> None:
+        arr, n = self._ids(tasks_by_impact)
+        _check(lib().cprune_search_start(self._h, arr, n, C.c_double(l_m), C.c_double(a_p)), "cprune_search_start")
+
+    def next_task(self) -> Optional[int]:
+        """The task to prune next, or None when the search is over."""
+        task, done = C.c_int64(0), C.c_int(0)
+        _check(lib().cprune_search_next_task(self._h, C.byref(task), C.byref(done)), "cprune_search_next_task")
+        return None if done.value else int(task.value)
+
+    def report_exhausted(self) -> None:
+        _check(lib().cprune_search_report_exhausted(self._h), "cprune_search_report_exhausted")
+
+    def report_latency(self, l_m: float) -> bool:
+        """-> True when the candidate passed the latency gate and its accuracy is wanted."""
+        need = C.c_int(0)
+        _check(lib().cprune_search_report_latency(self._h, C.c_double(l_m), C.byref(need)),
+               "cprune_search_report_latency")
+        return bool(need.value)
+
+    def report_accuracy(self, a_s: float, tasks_by_impact) -> bool:
+        """-> True when the candidate was accepted."""
+        arr, n = self._ids(tasks_by_impact)
+        acc = C.c_int(0)
+        _check(lib().cprune_search_report_accuracy(self._h, C.c_double(a_s), arr, n, C.byref(acc)),
+               "cprune_search_report_accuracy")
+        return bool(acc.value)
+
+    def log(self):
+        """-> [(task, l_m or None, l_t, a_s or None, verdict code)]"""
+        out = []
+        for i in range(int(lib().cprune_search_log_size(self._h))):
+            t, v = C.c_int64(0), C.c_int(0)
+            l_m, l_t, a_s = C.c_double(0), C.c_double(0), C.c_double(0)
+            _check(lib().cprune_search_log_entry(self._h, C.c_int(i), C.byref(t), C.byref(l_m), C.byref(l_t),
+                                                 C.byref(a_s), C.byref(v)), "cprune_search_log_entry")
+            nn = lambda x: None if x != x else x
+            out.append((int(t.value), nn(l_m.value), l_t.value, nn(a_s.value), int(v.value)))
+        return out
+
+    def close(self):
+        if self._h:
+            lib().cprune_search_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 # ---- measured ceilings ---------------------------------------------------------
 
 def cprune_probe_mfma(dtype: int = F32, stream=None) -> float:
@@ -459,6 +528,25 @@ def cprune_probe_copy(nbytes: int = 1 << 30, stream=None) -> float:
     out = C.c_float(0.0)
     st = lib().cprune_probe_copy(_ptr(src), _ptr(dst), C.c_size_t(nbytes), C.byref(out), _stream(stream))
     _check(st, "cprune_probe_copy")
+    return float(out.value)
+
+
+def cprune_probe_read(nbytes: int = 1 << 30, stream=None) -> float:
+    """GB/s of a kernel that only reads `nbytes` of device memory."""
+    src = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    scratch = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    out = C.c_float(0.0)
+    st = lib().cprune_probe_read(_ptr(src), _ptr(scratch), C.c_size_t(nbytes), C.byref(out), _stream(stream))
+    _check(st, "cprune_probe_read")
+    return float(out.value)
+
+
+def cprune_probe_write(nbytes: int = 1 << 30, stream=None) -> float:
+    """GB/s of a kernel that only writes `nbytes` of device memory."""
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    out = C.c_float(0.0)
+    st = lib().cprune_probe_write(_ptr(dst), C.c_size_t(nbytes), C.byref(out), _stream(stream))
+    _check(st, "cprune_probe_write")
     return float(out.value)
 
 
@@ -483,6 +571,7 @@ class Net:
                  stream=None):
         arr = (LayerDesc * len(layer_descs))(*layer_descs)
         self._h = C.c_void_p(None)
+        self._graph_logits = {}
         self.n_layers = len(layer_descs)
         self.dtype = dtype
         self.max_batch = max_batch
@@ -499,6 +588,13 @@ class Net:
 
     def forward(self, x, logits=None, use_graph=False, stream=None):
         n = x.shape[0]
+        if logits is None and use_graph:
+            # a recorded graph is keyed by (n, x, logits): without a buffer of the caller's, the same one is
+            # handed out for every replay at this batch size (a later call overwrites an earlier result)
+            logits = self._graph_logits.get(n)
+            if logits is None:
+                logits = torch.empty((n,) + self.out_shape, dtype=TORCH_DTYPE[self.dtype], device=x.device)
+                self._graph_logits[n] = logits
         if logits is None:
             logits = torch.empty((n,) + self.out_shape, dtype=TORCH_DTYPE[self.dtype], device=x.device)
         elif logits.numel() < n * self.out_features or logits.dtype != TORCH_DTYPE[self.dtype]:
@@ -529,6 +625,12 @@ class Net:
         n = C.c_int(0)
         _check(lib().cprune_net_task_table(self._h, tasks, C.byref(n)), "cprune_net_task_table")
         return list(tasks), int(n.value)
+
+    def task_key(self, layer: int) -> Tuple[int, ...]:
+        """The key the task table groups by, for a dense conv / fully connected layer."""
+        key = (C.c_int32 * 18)()
+        _check(lib().cprune_net_task_key(self._h, C.c_int(layer), key), "cprune_net_task_key")
+        return tuple(key)
 
     def fuse_depthwise(self, layer: int, enable: bool):
         _check(lib().cprune_net_fuse_depthwise(self._h, C.c_int(layer), C.c_int(1 if enable else 0)),

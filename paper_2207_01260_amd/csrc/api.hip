@@ -140,11 +140,13 @@ static int select_tile_impl(const cprune_conv_desc& d, const void* x, const void
     return CPRUNE_OK;
   };
   std::vector<std::pair<float, int>> timed;
+  int supported = d.groups == 1 ? 0 : 1;   // variants that can run the shape (timed or not)
   const int nv = d.groups == 1 ? num_variants() : 1;
   for (int v = 0; v < nv && rc == CPRUNE_OK; ++v) {
     if (all_ms_out) all_ms_out[v] = -1.0f;
     if (d.groups == 1) {
       if (!variant_supports(d, v, lay)) continue;
+      ++supported;
       if (conv_ws_bytes(d, v, lay) > ws_bytes) continue;  // not timed: the caller's scratch cannot run it
     }
     for (int i = 0; i < warmup && rc == CPRUNE_OK; ++i) rc = conv_dispatch(d, x, w, bias, residual, y, v, ws, ws_bytes, s, lay);
@@ -170,7 +172,7 @@ static int select_tile_impl(const cprune_conv_desc& d, const void* x, const void
   hipEventDestroy(e0);
   hipEventDestroy(e1);
   if (rc != CPRUNE_OK) return rc;
-  if (timed.empty()) return CPRUNE_ERR_WORKSPACE;
+  if (timed.empty()) return supported ? CPRUNE_ERR_WORKSPACE : CPRUNE_ERR_UNSUPPORTED;
   const int best_v = timed[0].second;
   if (d.groups == 1) remember_variant(d, best_v, lay);
   if (variant_out) *variant_out = best_v;
@@ -380,7 +382,9 @@ struct cprune_net {
   bool convert_input = true;  // false when every reader of the input takes the caller's NCHW tensor itself
   void* ws = nullptr;
   size_t ws_bytes = 0;
-  std::map<GraphKey, hipGraphExec_t> graphs;
+  struct GraphEntry { hipGraphExec_t exec; uint64_t last_use; };
+  std::map<GraphKey, GraphEntry> graphs;   // at most kMaxGraphs: the least recently used one makes room
+  uint64_t graph_clock = 0;
   hipStream_t capture_stream = nullptr;  // graphs are recorded here (the caller's may be the null stream)
   int last_n = 0;
 };
@@ -419,8 +423,15 @@ static ConvLayout layer_layout(const NetLayer& L) {
   return lay;
 }
 
+constexpr size_t kMaxGraphs = 8;
+
+static void drop_graphs(cprune_net* net) {
+  for (auto& g : net->graphs) hipGraphExecDestroy(g.second.exec);
+  net->graphs.clear();
+}
+
 static void net_free(cprune_net* net) {
-  for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
+  drop_graphs(net);
   if (net->capture_stream) hipStreamDestroy(net->capture_stream);
   for (void* p : net->allocs) hipFree(p);
   delete net;
@@ -682,6 +693,17 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
   }
   if (rc != CPRUNE_OK) { net_free(net); return rc; }
 
+  // A 3x3 / stride 1 / pad 1 conv on a 2x2 map reads the whole input map for every output pixel:
+  // it runs as one matrix product per image, 4/9 of the multiply-adds of the nine-tap form
+  // (the other 5/9 would multiply padding).
+  for (int i = 0; i < n_layers; ++i) {
+    NetLayer& L = net->layers[i];
+    const cprune_layer_desc& d = L.d;
+    if (d.kind == CPRUNE_LAYER_CONV && d.groups == 1 && d.k == 3 && d.stride == 1 && d.pad == 1 &&
+        L.h_in == 2 && L.w_in == 2 && L.cp_out == round_up_vec(d.c_out, dtype))
+      L.map2x2 = true;
+  }
+
   // A 2x2 / stride 2 max-pool whose only producer is a plain 3x3 stride-1 conv that nobody
   // else reads runs in that conv's epilogue: one launch and one round trip through HBM less.
   for (int i = 0; i < n_layers; ++i) {
@@ -696,20 +718,15 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     for (int j = 0; j < n_layers; ++j)
       if (j != i && (net->layers[j].d.input == pd.input || net->layers[j].d.residual == pd.input)) shared = true;
     if (shared) continue;
+    // only where some variant can run the layer with the pool in its epilogue (none can on e.g. a 2 x 8 map)
     Cv.fused_pool = true;
+    const cprune_conv_desc fd = layer_conv_desc(*net, Cv, max_batch);
+    const ConvLayout fl = layer_layout(Cv);
+    bool runnable = false;
+    for (int v = 0; v < num_variants() && !runnable; ++v) runnable = variant_supports(fd, v, fl);
+    if (!runnable) { Cv.fused_pool = false; continue; }
     Cv.per_image = (size_t)Cv.cp_out * Pl.h_out * Pl.w_out;
     Pl.alias = true;
-  }
-
-  // A 3x3 / stride 1 / pad 1 conv on a 2x2 map reads the whole input map for every output pixel:
-  // it runs as one matrix product per image, 4/9 of the multiply-adds of the nine-tap form
-  // (the other 5/9 would multiply padding).
-  for (int i = 0; i < n_layers; ++i) {
-    NetLayer& L = net->layers[i];
-    const cprune_layer_desc& d = L.d;
-    if (d.kind == CPRUNE_LAYER_CONV && d.groups == 1 && d.k == 3 && d.stride == 1 && d.pad == 1 &&
-        L.h_in == 2 && L.w_in == 2 && L.cp_out == round_up_vec(d.c_out, dtype))
-      L.map2x2 = true;
   }
 
   // A dense conv on the network input reads the caller's NCHW tensor directly (its few input
@@ -1018,9 +1035,20 @@ extern "C" int cprune_net_forward(cprune_net* net, const void* x, int n, void* l
     e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
     hipGraphDestroy(graph);
     if (e != hipSuccess) { set_last_hip_error(e); return CPRUNE_ERR_DEVICE; }
-    it = net->graphs.emplace(key, exec).first;
+    if (net->graphs.size() >= kMaxGraphs) {
+      // make room: the least recently replayed graph goes, once nothing can still be running it
+      auto victim = net->graphs.begin();
+      for (auto g = net->graphs.begin(); g != net->graphs.end(); ++g)
+        if (g->second.last_use < victim->second.last_use) victim = g;
+      hipError_t se = hipDeviceSynchronize();
+      hipGraphExecDestroy(victim->second.exec);
+      net->graphs.erase(victim);
+      if (se != hipSuccess) { hipGraphExecDestroy(exec); set_last_hip_error(se); return CPRUNE_ERR_DEVICE; }
+    }
+    it = net->graphs.emplace(key, cprune_net::GraphEntry{exec, 0}).first;
   }
-  CPRUNE_HIP_TRY(hipGraphLaunch(it->second, s));
+  it->second.last_use = ++net->graph_clock;
+  CPRUNE_HIP_TRY(hipGraphLaunch(it->second.exec, s));
   return CPRUNE_OK;
 }
 
@@ -1097,6 +1125,16 @@ extern "C" int cprune_net_task_table(const cprune_net* net, int* task_of_layer, 
   return CPRUNE_OK;
 }
 
+extern "C" int cprune_net_task_key(const cprune_net* net, int layer, int32_t* key_out) {
+  if (!net || !key_out || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
+  const NetLayer& L = net->layers[layer];
+  if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) return CPRUNE_ERR_INVALID_ARG;
+  const DescKey key = key_of(layer_conv_desc(*net, L, net->max_batch), layer_layout(L));
+  static_assert(std::tuple_size<DescKey>::value == CPRUNE_TASK_KEY_INTS, "key length is part of the ABI");
+  for (size_t i = 0; i < key.size(); ++i) key_out[i] = key[i];
+  return CPRUNE_OK;
+}
+
 static void restore_variant(cprune_net* net, NetLayer& L) {
   if (L.variant < 0 && !L.stem)
     L.variant = cached_or_heuristic_variant(layer_conv_desc(*net, L, net->max_batch), nullptr, layer_layout(L));
@@ -1109,8 +1147,7 @@ extern "C" int cprune_net_fuse_first_layers(cprune_net* net, int enable) {
     if (net->layers[i].stem_reader >= 0) { first = i; break; }
   if (first < 0) return CPRUNE_ERR_UNSUPPORTED;
   CPRUNE_HIP_TRY(hipDeviceSynchronize());
-  for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
-  net->graphs.clear();
+  drop_graphs(net);
   NetLayer& F = net->layers[first];
   NetLayer& L = net->layers[F.stem_reader];
   F.fused_away = enable != 0;
@@ -1125,8 +1162,7 @@ extern "C" int cprune_net_fuse_depthwise(cprune_net* net, int layer, int enable)
   NetLayer& D = net->layers[layer];
   if (D.dw_reader < 0) return CPRUNE_ERR_UNSUPPORTED;
   CPRUNE_HIP_TRY(hipDeviceSynchronize());
-  for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
-  net->graphs.clear();
+  drop_graphs(net);
   NetLayer& P = net->layers[D.dw_reader];
   if (P.fuse_block >= 0) {             // leaves the one-kernel block form either way
     NetLayer& E = net->layers[P.fuse_block];
@@ -1146,8 +1182,7 @@ extern "C" int cprune_net_fuse_block(cprune_net* net, int layer, int enable) {
   NetLayer& D = net->layers[layer];
   if (D.dw_reader < 0 || D.block_expand < 0) return CPRUNE_ERR_UNSUPPORTED;
   CPRUNE_HIP_TRY(hipDeviceSynchronize());
-  for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
-  net->graphs.clear();
+  drop_graphs(net);
   NetLayer& P = net->layers[D.dw_reader];
   NetLayer& E = net->layers[D.block_expand];
   if (enable) {
@@ -1179,8 +1214,7 @@ extern "C" int cprune_net_set_layer_variant(cprune_net* net, int layer, int vari
   if (!variant_supports(cd, variant, lay)) return CPRUNE_ERR_UNSUPPORTED;
   if (conv_ws_bytes(cd, variant, lay) > net->ws_bytes) return CPRUNE_ERR_WORKSPACE;
   CPRUNE_HIP_TRY(hipDeviceSynchronize());
-  for (auto& g : net->graphs) hipGraphExecDestroy(g.second);
-  net->graphs.clear();
+  drop_graphs(net);
   L.variant = variant;
   return CPRUNE_OK;
 }

@@ -1,5 +1,5 @@
-"""Per-configuration report: every evaluated workload shape of the paper (Section 4: VGG-16
-on CIFAR-sized inputs, ResNet-18, MobileNetV2 and MnasNet1.0 on ImageNet-sized inputs) as a seeded,
+"""Per-configuration report: every workload shape of the paper (VGG-16 on CIFAR-sized inputs, the
+motivating experiment of Section 3, Fig. 1; ResNet-18, MobileNetV2 and MnasNet1.0 on ImageNet-sized inputs, Section 4.1 and Table 1) as a seeded,
 synthetic, channel-pruned network, plus the single pruned layer and the measured ceilings of
 the device.  One JSON object per line.
 

@@ -20,56 +20,54 @@ from . import binding as B
 from . import pipeline, synth
 
 
-# ---- Algorithm 1, control flow only ------------------------------------------------
+# ---- Algorithm 1: the library decides, the caller measures ------------------------------
 
-def algorithm1(model, a_goal: float, alpha: float, beta: float, tune: Callable, prune: Callable,
+VERDICT = {1: "slow", 2: "inaccurate", 3: "accepted", 4: "exhausted"}
+
+
+def run_search(model, a_goal: float, alpha: float, beta: float, tune: Callable, prune: Callable,
                measure: Callable, accuracy: Callable, max_iterations: int = 1 << 30):
-    """Algorithm 1 over callbacks.  tune(model) -> (table: task -> (subgraphs, program), tasks
-    by descending impact); prune(model, task, subgraphs, program) -> candidate or None when
-    nothing can be pruned; measure(model) -> time; accuracy(model) -> accuracy.
+    """Drives the library's search object (cprune_search_*, the decisions of Algorithm 1) with
+    measurements made here.  tune(model) -> (table: task -> (subgraphs, program), tasks by
+    descending impact); prune(model, task, subgraphs, program) -> candidate or None when nothing
+    can be pruned; measure(model) -> time; accuracy(model) -> accuracy.  Tasks are hashable keys
+    that mean the same task from model to model; the library sees them as integers.
+    -> (final model, log of (task, l_m or None, l_t, a_s or None, verdict))."""
+    ids: Dict = {}
+    names: List = []
 
-    A candidate must be faster than the target time l_t (beta x the time of the last accepted
-    model) and keep accuracy >= alpha x the last accepted accuracy.  Too slow: try the next
-    task.  Too inaccurate, or nothing left to prune: the task is out for the rest of the
-    search.  Accepted: it becomes the model, its task list (minus the tasks already out) the
-    list.  Ends when accuracy reaches a_goal, the list is empty, or a whole pass changes
-    nothing.  Tasks are identified by hashable keys that persist across models.
-    -> (model, log of (task, l_m, l_t, a_s, verdict))."""
+    def as_ids(tasks):
+        out = []
+        for t in tasks:
+            if t not in ids:
+                ids[t] = len(names)
+                names.append(t)
+            out.append(ids[t])
+        return out
+
     table, order = tune(model)
-    todo = list(order)
-    out_for_good = set()
-    l_t = beta * measure(model)
-    a_p = accuracy(model)
-    log = []
-    passes = 0
-    while a_p > a_goal and todo and passes < max_iterations:
-        passes += 1
-        progress = False      # a task left the list or a candidate was accepted in this pass
-        for task in tuple(todo):
+    state = B.Search(a_goal, alpha, beta, max_iterations)
+    try:
+        state.start(as_ids(order), measure(model), accuracy(model))
+        candidate = cand_table = None
+        while True:
+            task_id = state.next_task()
+            if task_id is None:
+                break
+            task = names[task_id]
             subgraphs, program = table[task]
-            cand = prune(model, task, subgraphs, program)
-            if cand is None:
-                todo.remove(task); out_for_good.add(task); progress = True
-                log.append((task, None, l_t, None, "exhausted"))
+            candidate = prune(model, task, subgraphs, program)
+            if candidate is None:
+                state.report_exhausted()
                 continue
-            cand_table, cand_order = tune(cand)
-            l_m = measure(cand)
-            if not l_m < l_t:
-                log.append((task, l_m, l_t, None, "slow"))
+            cand_table, cand_order = tune(candidate)
+            if not state.report_latency(measure(candidate)):
                 continue
-            a_s = accuracy(cand)
-            if a_s < alpha * a_p:
-                todo.remove(task); out_for_good.add(task); progress = True
-                log.append((task, l_m, l_t, a_s, "inaccurate"))
-                continue
-            log.append((task, l_m, l_t, a_s, "accepted"))
-            model, table = cand, cand_table
-            todo = [t for t in cand_order if t not in out_for_good]
-            l_t, a_p = beta * l_m, a_s
-            progress = True
-            break
-        if not progress:
-            break
+            if state.report_accuracy(accuracy(candidate), as_ids(cand_order)):
+                model, table = candidate, cand_table
+        log = [(names[t], l_m, l_t, a_s, VERDICT[v]) for t, l_m, l_t, a_s, v in state.log()]
+    finally:
+        state.close()
     return model, log
 
 
@@ -88,6 +86,7 @@ class DeviceSearch:
         self.x = torch.from_numpy(synth.net_input(net, config_id, batch)).cuda().to(B.TORCH_DTYPE[dtype])
         self.prunable = [i for i, L in enumerate(net.layers) if L.prune_out == "own"]
         self._cache: Dict[Tuple, dict] = {}
+        self.trace: List[Tuple] = []      # (model, table, order, ms) of every model tuned, in order
 
     def initial_model(self, params: List[dict]) -> Dict[int, int]:
         return {i: int(params[i]["keep"]) for i in self.prunable}
@@ -109,12 +108,9 @@ class DeviceSearch:
         # a task's execution time: the mean over its subgraphs' measured times
         times = [sum(lt[i] for i in m) / len(m) for m in members]
         order, impact = B.cprune_order_tasks(times, [len(m) for m in members])
-        # tasks carry their shape as identity, so that they persist from model to model
-        keys = []
-        for m in members:
-            L = self.net.layers[m[0]]
-            cin, cout, ho, wo = shp[m[0]]
-            keys.append((L.kind, cin, cout, ho, wo, L.k, L.stride, L.pad, L.act, L.residual is not None))
+        # a task's identity is the key the library groups by (shape, stride, padding, activation,
+        # shortcut, layout): the same from model to model as long as the task's shape is untouched
+        keys = [handle.task_key(m[0]) for m in members]
         out = handle.forward(self.x)
         for _ in range(5):
             handle.forward(self.x, out)
@@ -134,6 +130,7 @@ class DeviceSearch:
         handle.close()
         st = {"table": table, "order": [keys[t] for t in order], "ms": ms}
         self._cache[key] = st
+        self.trace.append((dict(model), table, st["order"], ms))
         return st
 
     def tune(self, model):
@@ -167,7 +164,7 @@ def run(net_name="vgg16", batch=64, dtype=B.F32, alpha=0.95, beta=0.98, a_goal=0
     ds = DeviceSearch(net, params, cid, batch, dtype)
     model = ds.initial_model(params)
     acc = accuracy or (lambda m: 1.0)
-    final, log = algorithm1(model, a_goal, alpha, beta, ds.tune, ds.prune, ds.measure, acc,
+    final, log = run_search(model, a_goal, alpha, beta, ds.tune, ds.prune, ds.measure, acc,
                             max_iterations=iterations)
     return ds, model, final, log
 

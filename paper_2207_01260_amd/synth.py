@@ -11,7 +11,7 @@ named by ``stream_key(base_seed, *tags)`` so tensors are independent of the
 order in which they are drawn.
 
 Networks follow the workloads the paper evaluates (VGG-16 on 32x32 inputs in
-its motivation experiment, Section 2.2 / Fig. 1; ResNet-18 and MobileNetV2 in
+the motivating experiment that opens Section 3, Fig. 1; ResNet-18 and MobileNetV2 in
 Table 1; the CIFAR ResNet-18 of Table 2), as layer lists whose multiply-add and
 parameter counts reproduce the figures printed in Tables 1 and 2.
 """

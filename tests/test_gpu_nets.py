@@ -14,11 +14,7 @@ pytestmark = pytest.mark.gpu
 TOL = {B.F32: 1e-4, B.F16: 2e-2, B.BF16: 2e-2}
 
 
-def nmax(g, r):
-    g = np.asarray(g, dtype=np.float64)
-    r = np.asarray(r, dtype=np.float64)
-    assert g.shape == r.shape, (g.shape, r.shape)
-    return float(np.max(np.abs(g - r)) / max(np.max(np.abs(r)), 1e-30))
+from parity import check, nmax  # noqa: E402
 
 
 def _run(orc, net, cid, batch, dtype, tune, check_layers=True, use_graph=False):
@@ -53,10 +49,8 @@ def _run(orc, net, cid, batch, dtype, tune, check_layers=True, use_graph=False):
                 assert e.status == B.ERR_UNSUPPORTED
                 assert net.layers[i + 1].kind == "maxpool" or handle.layer_fused(i)
                 continue
-            e = nmax(a, r)
-            assert e < tol, (net.layers[i].name, e)
-    err = nmax(logits.float().cpu().numpy(), ref_acts[-1])
-    assert err < tol, err
+            check(a, r, dtype, net.layers[i].name)
+    check(logits.float().cpu().numpy(), ref_acts[-1], dtype, "logits")
     return handle, xd, logits, ref_acts[-1]
 
 
@@ -169,7 +163,7 @@ def test_resnet18_shortcuts_full_size_fp16(orc):
 
 
 def test_resnet18_bf16(orc):
-    handle, *_ = _run(orc, synth.resnet18(100, 64), 3, 2, B.BF16, tune=False, check_layers=False)
+    handle, *_ = _run(orc, synth.resnet18(100, 64), 3, 2, B.BF16, tune=False)
     handle.close()
 
 

@@ -1,7 +1,7 @@
 """Search-side rows on the device: the handle's task table against the oracle's grouping,
-Algorithm 1 driven by measured latencies (its gate, order and cuts checked against the oracle's
-rules; the loop's control flow itself is compared with the oracle's on synthetic latencies in
-test_search_rules.py), and the predicted prune step against the measured latency staircase."""
+Algorithm 1 driven by measured latencies (the recorded tables and latencies are replayed through
+the oracle's loop: same final model, same log), and the predicted prune step against the
+measured latency staircase."""
 import numpy as np
 import pytest
 import torch
@@ -40,13 +40,16 @@ def test_task_table_resnet18_unpruned():
 
 
 def test_algorithm1_on_measured_latencies():
+    """Algorithm 1 on the device (tune = rank + gather + tuned handle + task table + layer times,
+    measure = forward time), then the recorded (model -> table, order, latency) replayed through
+    the oracle's loop with the oracle's own prune rule: same final model, same log."""
     print("algorithm 1, vgg16 b8", flush=True)
     net = synth.vgg16(10, 32)
     params = synth.layer_params(net, 2)
     ds = psearch.DeviceSearch(net, params, 2, batch=8, steps=10)
     start = ds.initial_model(params)
     acc = lambda m: 1.0
-    final, log = psearch.algorithm1(start, 0.0, 0.95, 0.999, ds.tune, ds.prune, ds.measure, acc, max_iterations=2)
+    final, log = psearch.run_search(start, 0.0, 0.95, 0.999, ds.tune, ds.prune, ds.measure, acc, max_iterations=3)
     assert log, "no candidate was tried"
     for task, l_m, l_t, a_s, verdict in log:
         assert verdict in ("accepted", "slow", "exhausted")
@@ -57,6 +60,31 @@ def test_algorithm1_on_measured_latencies():
     assert all(final[i] <= start[i] for i in start)
     n_acc = sum(v == "accepted" for *_, v in log)
     assert sum(start.values()) - sum(final.values()) > 0 if n_acc else final == start
+
+    # replay: the oracle's loop over the latencies and tables the device produced
+    recorded = {tuple(sorted(m.items())): (table, order, ms) for m, table, order, ms in ds.trace}
+
+    def tune(model):
+        table, order, _ = recorded[tuple(sorted(model.items()))]
+        return table, order
+
+    def measure(model):
+        return recorded[tuple(sorted(model.items()))][2]
+
+    def prune(model, task, subgraphs, program):
+        cand, changed = dict(model), False
+        for i in subgraphs:
+            if i in cand:
+                cut = osearch.prune_count(cand[i], program["step"])
+                if cut > 0:
+                    cand[i] -= cut
+                    changed = True
+        return cand if changed else None
+
+    want_final, want_log = osearch.algorithm1(start, 0.0, 0.95, 0.999, tune, prune, measure, acc, max_iterations=3)
+    assert final == want_final
+    assert log == want_log, (log, want_log)
+
     # the first candidate is the task with the largest impact, and its cut is the one the step
     # rule gives for the structure of the variant that task runs (the oracle's rule on the
     # variant's split, the oracle's prune count)
@@ -71,6 +99,62 @@ def test_algorithm1_on_measured_latencies():
         assert start[i] - cand[i] == osearch.prune_count(start[i], program["step"])
     imp = osearch.pruning_impact([table[t][1]["time_ms"] for t in order], [len(table[t][0]) for t in order])
     assert all(a >= b for a, b in zip(imp, imp[1:]))
+
+
+def test_equal_shapes_with_and_without_pool_are_two_tasks(orc):
+    """Two convolutions of the same shape, one of them with a 2x2 pool in its epilogue, run
+    different programs: two tasks, two distinct keys, and the 2 x 8 map whose pool no kernel can
+    fuse still builds and runs (the pool stays a layer of its own)."""
+    for hw, fusable in (((8, 8), True), ((2, 8), False)):
+        net = synth.NetSpec("two_convs", 8, hw[0], hw[1])
+        a = net.add(synth.Layer("conv", -1, 8, 8, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="a"))
+        b = net.add(synth.Layer("conv", a, 8, 8, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="b"))
+        p = net.add(synth.Layer("maxpool", b, 8, 8, k=2, stride=2, name="pool"))
+        net.add(synth.Layer("conv", p, 8, 5, k=3, stride=1, pad=1, act=synth.ACT_NONE, bn=True, name="c"))
+        params = synth.layer_params(net, 77)
+        x = synth.net_input(net, 77, 2)
+        ref_layers, _ = orc.prune_net(net, params)
+        ref = orc.forward(net, ref_layers, x)
+        layers, _ = pipeline.prune_net(net, pipeline.upload_params(params))
+        handle = pipeline.build_net(net, layers, 2, B.F32, tune=False)
+        task_of, n_tasks = handle.task_table()
+        y = handle.forward(torch.from_numpy(x).cuda()).cpu().numpy()
+        assert np.max(np.abs(y - ref)) / np.max(np.abs(ref)) < 1e-4
+        if fusable:
+            assert task_of[:2] == [0, 1] and n_tasks == 3
+            assert handle.task_key(0) != handle.task_key(1)
+        else:
+            assert task_of[:2] == [0, 0] and n_tasks == 2
+            assert handle.task_key(0) == handle.task_key(1)
+        handle.close()
+
+
+def test_graph_cache_stays_bounded():
+    """Replays with a fresh output buffer per call: the handle keeps a bounded number of recorded
+    graphs (the least recently used one makes room), results stay right throughout."""
+    net = synth.vgg16(10, 32)
+    params = synth.layer_params(net, 2)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params))
+    handle = pipeline.build_net(net, layers, 2, B.F32, tune=False)
+    x = torch.from_numpy(synth.net_input(net, 2, 2)).cuda()
+    want = handle.forward(x, use_graph=False).clone()
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    bufs = [torch.empty((2, 10), dtype=torch.float32, device="cuda") for _ in range(40)]
+    for rep in range(25):
+        for out in bufs:
+            handle.forward(x, out, use_graph=True)
+        torch.cuda.synchronize()
+        assert torch.equal(bufs[rep % 40], want)
+    free1 = torch.cuda.mem_get_info()[0]
+    assert free0 - free1 < 256 << 20, (free0, free1)      # 1000 replays through 40 buffers leak nothing
+    # without a buffer of the caller's, replays share one per batch size
+    a = handle.forward(x, use_graph=True)
+    b = handle.forward(x, use_graph=True)
+    assert a.data_ptr() == b.data_ptr()
+    torch.cuda.synchronize()
+    assert torch.equal(a, want)
+    handle.close()
 
 
 def test_predicted_step_against_measured_staircase():

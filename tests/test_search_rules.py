@@ -89,8 +89,9 @@ def test_variant_structure_and_step():
 
 
 def test_algorithm1_control_flow_against_oracle():
-    """The product's loop and the oracle's loop take the same decisions on seeded toy models
-    (per-task filter counts, linear latency, accuracy that falls with every cut)."""
+    """The library's search object (driven by run_search) and the oracle's loop take the same
+    decisions on seeded toy models (per-task filter counts, linear latency, accuracy that falls
+    with every cut)."""
     from paper_2207_01260_amd import search as psearch
     rng = random.Random(3)
     for trial in range(60):
@@ -121,6 +122,45 @@ def test_algorithm1_control_flow_against_oracle():
             return sum(lat[t] * model[t] for t in range(n))
 
         want = search.algorithm1(start, goal, alpha, beta, tune, prune, measure, acc)
-        got = psearch.algorithm1(start, goal, alpha, beta, tune, prune, measure, acc)
+        got = psearch.run_search(start, goal, alpha, beta, tune, prune, measure, acc)
         assert got[0] == want[0], trial
         assert got[1] == want[1], trial
+
+
+def test_search_object_rejects_calls_out_of_order():
+    s = B.Search(0.0, 0.9, 0.9, 10)
+    with pytest.raises(B.CPruneError):
+        s.next_task()                      # not started
+    s.start([7, 3], 1.0, 1.0)
+    with pytest.raises(B.CPruneError):
+        s.report_exhausted()               # no task handed out
+    assert s.next_task() == 7
+    with pytest.raises(B.CPruneError):
+        s.next_task()                      # a report is due
+    with pytest.raises(B.CPruneError):
+        s.report_accuracy(1.0, [7, 3])     # latency first
+    assert s.report_latency(2.0) is False  # 2.0 >= 0.9: slow, task stays
+    assert s.next_task() == 3
+    assert s.report_latency(0.5) is True
+    with pytest.raises(B.CPruneError):
+        s.report_exhausted()               # accuracy is due
+    assert s.report_accuracy(0.95, [3, 7]) is True
+    assert s.next_task() == 3              # the accepted model's list from its head
+    s.report_exhausted()
+    assert s.next_task() == 7
+    assert s.report_latency(0.44) is True  # target is now 0.9 * 0.5
+    assert s.report_accuracy(0.5, [7]) is False   # 0.5 < 0.9 * 0.95: out for good
+    assert s.next_task() is None
+    assert [e[4] for e in s.log()] == [1, 3, 4, 2]
+    s.close()
+
+
+def test_search_pass_limit():
+    s = B.Search(0.0, 0.0, 2.0, 2)       # beta 2: every candidate passes the gate
+    s.start([1], 1.0, 1.0)
+    for _ in range(2):
+        assert s.next_task() == 1
+        assert s.report_latency(1.0)
+        assert s.report_accuracy(1.0, [1])
+    assert s.next_task() is None
+    s.close()
