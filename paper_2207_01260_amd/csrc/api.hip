@@ -820,7 +820,7 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     NetLayer& L = net->layers[i];
     const cprune_layer_desc& d = L.d;
     if (!(d.kind == CPRUNE_LAYER_CONV && d.groups == 1 && d.k == 3 && d.stride == 1 && d.pad == 1)) continue;
-    if (L.map2x2 || L.nchw_in || L.h_in < 3 || L.w_in < 3 || L.h_in > 16 || L.w_in > 16) continue;
+    if (L.map2x2 || L.nchw_in || L.h_in < 3 || L.w_in < 3 || L.h_in > 32 || L.w_in > 32) continue;
     if (wave_packed_bytes(d.c_out, L.cp_in, dtype) >= ((size_t)1 << 31)) continue;   // 31-bit offsets in the kernel
     rc = dev_alloc(wave_packed_bytes(d.c_out, L.cp_in, dtype), &L.w_wave);
     if (rc == CPRUNE_OK) rc = launch_repack_wave(L.w, d.c_out, L.cp_in, dtype, L.w_wave, s);

@@ -178,9 +178,10 @@ __device__ __forceinline__ void unit_range(const ConvArgs& a, int g, int& ub, in
 
 // bias + residual + activation + channels-last store of one 16x16 block column:
 // a lane holds 4 consecutive channels of one pixel.
+// (bias: the four values load_bias4 gives for o; kernels on short layers fetch them before their main loop,
+// where the wait for them hides, and pass them in)
 template <typename T>
-__device__ __forceinline__ void nhwc_store4(const ConvArgs& a, const float4_t& acc, int p, int o) {
-  const float4_t bias = load_bias4(a.bias, a.O, o);
+__device__ __forceinline__ void nhwc_store4(const ConvArgs& a, const float4_t& acc, int p, int o, const float4_t& bias) {
   if (a.pool4) {
     if (o >= a.O) return;
     float m = apply_act(acc[0] + bias[0], a.act);
@@ -226,6 +227,11 @@ __device__ __forceinline__ void nhwc_store4(const ConvArgs& a, const float4_t& a
       }
     }
   }
+}
+
+template <typename T>
+__device__ __forceinline__ void nhwc_store4(const ConvArgs& a, const float4_t& acc, int p, int o) {
+  nhwc_store4<T>(a, acc, p, o, load_bias4(a.bias, a.O, o));
 }
 
 // bias + residual + activation + store of one wave's accumulators.

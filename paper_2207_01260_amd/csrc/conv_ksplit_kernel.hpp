@@ -43,6 +43,8 @@ __global__ __launch_bounds__(64 * KW) void conv_ksplit_kernel(ConvArgs a) {
 
   const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);
   const __amdgpu_buffer_rsrc_t wr = make_rsrc(a.w, a.w_bytes);
+  // requested now, used in the epilogue: on a short layer a load issued there would be waited for in full
+  const float4_t bias4 = load_bias4(a.bias, a.O, o0 + 4 * g4);
   const unsigned row_bytes = (unsigned)a.K * ES;          // a multiple of 16: channel strides are whole vectors
   const int rounds = (int)((row_bytes + 63) / 64);
   const int lo = (int)((long)wave * rounds / KW), hi = (int)((long)(wave + 1) * rounds / KW);
@@ -107,7 +109,7 @@ __global__ __launch_bounds__(64 * KW) void conv_ksplit_kernel(ConvArgs a) {
   for (int w = 1; w < KW; ++w) acc += red[w][wave][lane];
   const int p = p0 + wave * 16 + r;
   if (p >= a.P) return;
-  nhwc_store4<T>(a, acc, p, o0 + 4 * g4);
+  nhwc_store4<T>(a, acc, p, o0 + 4 * g4, bias4);
 }
 
 // Variants: id, nb (16-pixel blocks per work-group), kw (wavefronts splitting the reduction)

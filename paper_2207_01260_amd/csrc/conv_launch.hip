@@ -21,7 +21,7 @@ const int kScheds[] = {0, 1, 2, 3, 4, 6, 8};
 constexpr int kNumScheds = sizeof(kScheds) / sizeof(kScheds[0]);
 constexpr int kMinUnitsPerGroup = 4;
 constexpr long kMaxKsplitGroups = 8192;
-constexpr int kMaxWaveMap = 16;
+constexpr int kMaxWaveMap = 32;
 
 unsigned magic_for(unsigned d) {
   if (d <= 1) return 0;

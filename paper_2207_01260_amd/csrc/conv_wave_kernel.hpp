@@ -18,6 +18,8 @@
 // traffic hide behind another's MFMAs.  The slices meet in LDS at the end (the only two
 // barriers) and wavefront j stores block j.  NP * NB also chooses how evenly a layer's blocks
 // spread over the compute units (5 turns 304 four-block tiles into 247 five-block ones).
+// With a batch of one image a layer is a handful of blocks: then one block per group and 4 to 16
+// slices of the reduction (NP = NB = 1) put the most wavefronts on it, and that is what wins there.
 //
 // Same MFMA blocks, lane layout and k-permutation as the other dense kernels.
 #pragma once
@@ -69,6 +71,8 @@ __global__ __launch_bounds__(64 * NP * KS) void conv_wave_kernel(PatchArgs a) {
 
   const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);
   const __amdgpu_buffer_rsrc_t wr = make_rsrc(a.w, a.w_bytes);
+  // requested now, used in the epilogue: on a short layer a load issued there would be waited for in full
+  const float4_t bias4 = load_bias4(a.bias, a.O, o0 + 4 * g4);
 
   // ---- staging items of the patches: (block, patch pixel, quad) ----
   unsigned b_off[NB][NIB];
@@ -202,24 +206,23 @@ __global__ __launch_bounds__(64 * NP * KS) void conv_wave_kernel(PatchArgs a) {
     const int by = (int)fast_div((unsigned)rest, a.magic_x);
     const int oy = by * 4 + ty, ox = (rest - by * a.tiles_x) * 4 + tx;
     if (!a.pool) {
-      if (oy < a.H && ox < a.W) nhwc_store4<T>(e, acc, (n * a.H + oy) * a.W + ox, o);
+      if (oy < a.H && ox < a.W) nhwc_store4<T>(e, acc, (n * a.H + oy) * a.W + ox, o, bias4);
     } else {
       // bias + activation, then the max over each 2x2 window (partners: lanes r ^ 1 and r ^ 4); the
       // activation is monotone, so max(act(.)) equals act-then-pool.  The even/even corner stores.
       ConvArgs ep = e;
       ep.act = CPRUNE_ACT_NONE;
       ep.bias = nullptr;
-      const float4_t bias = load_bias4(a.bias, a.O, o);
       float4_t m;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        float x = apply_act(acc[c] + bias[c], a.act);
+        float x = apply_act(acc[c] + bias4[c], a.act);
         x = fmaxf(x, __shfl_xor(x, 1, 64));
         x = fmaxf(x, __shfl_xor(x, 4, 64));
         m[c] = x;
       }
       if (!((ty | tx) & 1) && oy < a.H && ox < a.W)
-        nhwc_store4<T>(ep, m, (n * (a.H >> 1) + (oy >> 1)) * (a.W >> 1) + (ox >> 1), o);
+        nhwc_store4<T>(ep, m, (n * (a.H >> 1) + (oy >> 1)) * (a.W >> 1) + (ox >> 1), o, (float4_t){0.f, 0.f, 0.f, 0.f});
     }
   }
 }
@@ -238,9 +241,15 @@ __global__ __launch_bounds__(64 * NP * KS) void conv_wave_kernel(PatchArgs a) {
   X(8, 2, 3, 4) \
   X(9, 2, 2, 2) \
   X(10, 4, 1, 2) \
-  X(11, 3, 2, 4)
+  X(11, 3, 2, 4) \
+  X(12, 1, 1, 16) \
+  X(13, 1, 1, 8) \
+  X(14, 1, 2, 8) \
+  X(15, 2, 1, 8) \
+  X(16, 1, 1, 4) \
+  X(17, 1, 2, 4)
 
-constexpr int kNumWave = 12;
+constexpr int kNumWave = 18;
 
 constexpr size_t wave_lds_bytes(int np, int nb, int ks) { return (size_t)np * ks * nb * (36 * 80); }
 
