@@ -30,16 +30,24 @@ PEAK = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}   # dense MFMA TFLOP/s, MI3
 # Bytes between L2 and fabric per launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the counter
 # reads for a copy kernel of known size), by (kernel instantiation, batch, layers it ran), for the default
 # workload: from the rocprofv3 counter runs summarised in profiles/vgg16_b64_f32_hbm_traffic.md.  The
-# timed selection decides which layers a kernel runs; when that differs from the profiled runs the
-# figure does not apply and null is reported.
+# figures belong to the kernel sources they were measured on: TRAFFIC_SOURCE_HASH is kernel_source_hash()
+# of that tree, and any change to a file under csrc/ since then reports null instead of a stale figure
+# (as does a timed selection that gives a kernel other layers than the profiled run had).
+TRAFFIC_SOURCE_HASH = "unset"
 TRAFFIC = {
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, ("conv3", "conv5", "conv6")): 8474991,            # algorithmic 5.8e6
-    ("conv_patch_kernel<float, 2, 8, 8, 1, 1, 1>", 64, ("conv4",)): 10103478,                            # algorithmic 8.2e6
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 2>", 64, ("conv7",)): 12106091,                            # algorithmic 4.7e6
-    ("conv_wave_kernel<float, 5, 1, 3>", 64, ("conv8", "conv10")): 10499238,                             # algorithmic 3.7e6
-    ("conv_wave_kernel<float, 2, 2, 4>", 64, ("conv9",)): 15049592,                                      # algorithmic 4.8e6
-    ("conv_stem2_kernel<float, 2>", 64, ("conv2",)): 3348295,             # conv1 + conv2; algorithmic 2.7e6
 }
+
+
+def kernel_source_hash():
+    """sha256 over the HIP sources the library is built from (names and contents, in name order)."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2207_01260_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".hpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def main():
@@ -63,10 +71,18 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip batch-1 and fp16 side figures")
     ap.add_argument("--cpu-images", type=int, default=0, help="oracle sample size (0 = auto)")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the side figures of the other workloads (single layer, ResNet-18, MobileNetV2, "
+                         "channel sweep points)")
+    ap.add_argument("--print-source-hash", action="store_true",
+                    help="print kernel_source_hash() of this tree and exit (what traffic figures are stamped with)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB channel copy (gather_channels_kernel with the identity "
                          "list) three times, as the known-size reference for HBM traffic counters")
     args = ap.parse_args()
+    if args.print_source_hash:
+        print(kernel_source_hash())
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
               "use --gpus 1", file=sys.stderr)
@@ -220,8 +236,11 @@ def main():
                      "achieved": round(achieved, 2), "peak": PEAK[args.dtype], "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK[args.dtype], 4),
                      "layers": d_layers,
-                     "traffic": TRAFFIC.get((dom, args.batch, tuple(d_layers))),
-                     "traffic_unit": "bytes per launch between L2 and fabric (FETCH_SIZE + WRITE_SIZE, scaled)",
+                     "traffic": (TRAFFIC.get((dom, args.batch, tuple(d_layers)))
+                                 if kernel_source_hash() == TRAFFIC_SOURCE_HASH else None),
+                     "traffic_unit": "bytes per launch between L2 and fabric (FETCH_SIZE + WRITE_SIZE, scaled); null when "
+                                     "the kernel sources differ from the profiled tree or the kernel ran other layers",
+                     "kernel_source_hash": kernel_source_hash(),
                      "avg_launch_us": round(d_ms / d_n * 1e3, 2),
                      "useful_gflop_per_launch": round(d_fl / d_n / 1e9, 3),
                      "share_of_step": round(d_ms / ms, 3)},
@@ -244,19 +263,87 @@ def main():
         del big
 
     if not args.no_extras:
+        from paper_2207_01260_amd import report
         extras = {}
         for name, dtype, batch in [("f32_b1", B.F32, 1), ("f16_b64", B.F16, 64), ("f16_b1", B.F16, 1),
                                    ("f32_b64", B.F32, 64)]:
             if dtype == dt and batch == args.batch:
                 continue
-            h, _, _, _ = build(dtype, batch, not args.no_tune)
+            h, lay_b, kept_b, _ = build(dtype, batch, not args.no_tune)
             xb = torch.from_numpy(synth.net_input(net, cid, batch)).cuda().to(B.TORCH_DTYPE[dtype])
             m_graph = time_forward(h, xb, max(50, args.steps // 2), 10, True)
             m_eager = time_forward(h, xb, max(50, args.steps // 2), 10, False)
             extras[name] = {"images_per_s": round(batch / (min(m_graph, m_eager) * 1e-3), 1),
                             "ms_graph": round(m_graph, 4), "ms_eager": round(m_eager, 4)}
+            if batch == 1:
+                # back-to-back replays keep the weights in the last-level cache; this is with the caches
+                # scrubbed (a 1 GiB fill) before every forward, timed by events around the forward alone
+                extras[name]["ms_cold_caches"] = round(report.time_forward_cold(h, xb, 20), 4)
+                lt1 = h.layer_times(xb, iters=20)
+                extras[name]["launches"] = sum(1 for t in lt1 if t > 0)
+                extras[name]["sum_of_layer_us"] = round(sum(lt1) * 1e3, 2)
+            if name == "f16_b64":
+                # per layer: which roofline bounds it (arithmetic intensity on input + weights + output once
+                # against the ridge 2.5 PFLOP/s / 8 TB/s = 312 FLOP/B) and how close the layer runs to it
+                kc = {i: int(k.numel()) for i, k in kept_b.items()}
+                shp16 = synth.shapes(net, kc)
+                rows, t_bound, t_meas = [], 0.0, 0.0
+                for i, (L, t) in enumerate(zip(net.layers, h.layer_times(xb, iters=20))):
+                    if L.kind != "conv" or t <= 0:
+                        continue
+                    cin, cout, ho, wo = shp16[i]
+                    hin = net.in_h if L.input < 0 else shp16[L.input][2]
+                    fl = 2.0 * batch * cout * cin * 9 * ho * wo
+                    if L.input >= 0 and h.layer_fused(L.input):      # carries the first layer's work
+                        ci0, co0, h0, w0 = shp16[L.input]
+                        fl += 2.0 * batch * co0 * ci0 * 9 * h0 * w0
+                    by = 2.0 * (batch * cin * hin * hin + cout * cin * 9 + batch * cout * ho * wo)
+                    t_mfma, t_hbm = fl / 2.5e15, by / 8e12
+                    bound = "mfma" if t_mfma >= t_hbm else "hbm"
+                    floor = max(t_mfma, t_hbm)
+                    rows.append({"layer": L.name, "us": round(t * 1e3, 2), "flop_per_byte": round(fl / by, 1),
+                                 "bound": bound, "floor_us": round(floor * 1e6, 2),
+                                 "frac_of_bound": round(floor / (t * 1e-3), 4)})
+                    t_bound += floor; t_meas += t * 1e-3
+                extras[name]["roofline"] = {"peak_tflops": 2500.0, "peak_gbs": 8000.0, "ridge_flop_per_byte": 312.5,
+                                            "conv_layers_frac_of_bound": round(t_bound / t_meas, 4),
+                                            "note": "a layer's floor is the larger of its MFMA time and its HBM time; "
+                                                    "launches of 3-10 us each, about 2 us of which is the launch itself",
+                                            "layers": rows}
             h.close()
         out["extras"] = extras
+
+        if not args.no_configs:
+            cfg = {}
+            # the single pruned layer: 64 filters ranked, 45 kept, 32x32, batch 1 (53 MFLOP: latency-bound)
+            row = report.single_layer_report(50)[0]
+            cfg["single_conv_64to45_32x32_b1_f32"] = {"us_in_handle": row["us_in_handle"],
+                                                      "us_entry_point": row["us_entry_point"], "bound": "launch latency"}
+            # ResNet-18 224x224, batch 32
+            for dtype in (B.F32, B.BF16):
+                r = report.net_report("resnet18", synth.resnet18(1000, 224), 3, 32, dtype, 20)
+                d = r["by_layer_kind"]["dense_conv"]
+                cfg["resnet18_224_b32_" + r["dtype"]] = {
+                    "images_per_s": r["images_per_s"], "ms": r["ms_per_forward"], "bound": "mfma",
+                    "dense_conv_tflops": d.get("tflops"), "frac": d.get("frac_mfma_peak")}
+            # MobileNetV2 224x224, batch 64: bandwidth-bound layers
+            r = report.net_report("mobilenetv2", synth.mobilenetv2(1000, 224), 4, 64, B.F32, 20)
+            k = r["by_layer_kind"]
+            cfg["mobilenetv2_224_b64_f32"] = {
+                "images_per_s": r["images_per_s"], "ms": r["ms_per_forward"], "bound": "hbm",
+                "dense_conv_gbs": k["dense_conv"].get("gbs"), "frac": k["dense_conv"].get("frac_hbm_peak"),
+                "depthwise_gbs": k.get("depthwise", {}).get("gbs"),
+                "depthwise_fused_into_reader": k.get("depthwise", {}).get("fused_into_their_1x1_reader", 0)}
+            # channel sweep of the 56x56 layer, seven of the 128 counts (tests/test_gpu_fullsize.py runs all)
+            from paper_2207_01260_amd import sweep
+            counts = [1, 16, 17, 45, 64, 112, 128]
+            rows = {r["c_out"]: r for r in sweep.run(step=1, counts=counts)}
+            us = [rows[c]["us"] for c in counts]
+            cfg["conv3x3_56x56_cin128_b8_f32_sweep"] = {
+                "us_by_c_out": {str(c): rows[c]["us"] for c in counts},
+                "tflops_at_128": rows[128]["tflops"], "frac_at_128": round(rows[128]["tflops"] / 157.3, 4),
+                "bound": "mfma", "inversions_over_3pct": sum(1 for a, b in zip(us, us[1:]) if b < 0.97 * a)}
+            extras["configs"] = cfg
 
     if not args.no_cpu_baseline:
         import oracle
@@ -286,6 +373,54 @@ def main():
         oracle.set_threads(threads)
         out["cpu_baseline"]["single_thread"] = {"value": round(n1 / dt1, 2), "unit": "images/s",
                                                 "sample": f"{n1} images, {dt1:.1f} s"}
+        # the same loops accumulating in float (the GPU path's own accumulation width), all threads
+        oracle.timing_build(True)
+        try:
+            t0 = time.perf_counter()
+            oracle.forward(net, ref_layers, xs[: max(16, n_img // 2)])
+            dtf = time.perf_counter() - t0
+        finally:
+            oracle.timing_build(False)
+        out["cpu_baseline"]["f32_accumulate"] = {"value": round(max(16, n_img // 2) / dtf, 2), "unit": "images/s",
+                                                 "sample": f"{max(16, n_img // 2)} images, {dtf:.1f} s, same loops with a "
+                                                           "float accumulator (timing only, never a reference)"}
+        # the GPU result on images of the same sample against the oracle's (the measure of the tests)
+        n_par = min(16, n_img)
+        hp, _, _, _ = build(dt, n_par, False)
+        got = hp.forward(torch.from_numpy(xs[:n_par]).cuda().to(B.TORCH_DTYPE[dt])).float().cpu().numpy().astype(np.float64)
+        hp.close()
+        want = oracle.forward(net, ref_layers, xs[:n_par]).astype(np.float64)
+        rtol = 1e-4 if args.dtype == "f32" else 2e-2
+        rms = float(np.sqrt(np.mean(want * want)))
+        out["cpu_baseline"]["parity_of_sample"] = {
+            "images": n_par, "max_abs_err_over_max_abs_ref": float(np.max(np.abs(got - want)) / np.max(np.abs(want))),
+            "rtol": rtol,
+            "elementwise_pass_rate": float(np.mean(np.abs(got - want) <= rtol * np.abs(want) + rtol * rms)),
+            "definition": "|g - r| <= rtol |r| + rtol rms(r) per logit"}
+        if not args.no_configs:
+            # the other workloads, one repetition each on a few images
+            others = {}
+            for label, onet, ocid, nimg in (("resnet18_224", synth.resnet18(1000, 224), 3, 4),
+                                            ("mobilenetv2_224", synth.mobilenetv2(1000, 224), 4, 4)):
+                op = synth.layer_params(onet, ocid)
+                ol, _ = oracle.prune_net(onet, op)
+                ox = synth.net_input(onet, ocid, nimg)
+                t0 = time.perf_counter()
+                oracle.forward(onet, ol, ox)
+                dto = time.perf_counter() - t0
+                others[label] = {"value": round(nimg / dto, 2), "unit": "images/s", "sample": f"{nimg} images, {dto:.1f} s"}
+            snet = synth.single_conv(128, 128, 56)
+            sp = synth.layer_params(snet, 5)
+            sx = synth.net_input(snet, 5, 8)
+            sweep_rows = {}
+            for k in (1, 16, 45, 64, 128):
+                sp[0]["keep"] = k
+                sl, _ = oracle.prune_net(snet, sp)
+                t0 = time.perf_counter()
+                oracle.forward(snet, sl, sx)
+                sweep_rows[str(k)] = round((time.perf_counter() - t0) * 1e3, 1)
+            others["conv3x3_56x56_cin128_b8_sweep_ms_by_c_out"] = sweep_rows
+            out["cpu_baseline"]["other_workloads"] = others
     print(json.dumps(out))
 
 

@@ -16,15 +16,32 @@ import numpy as np
 from . import build as _build
 
 _lib = None
+_lib_f32acc = None
+_timing_build = False
 
 
 def lib():
-    global _lib
+    """The C oracle: the parity build (fp64 accumulation) unless timing_build(True) is in force."""
+    global _lib, _lib_f32acc
+    if _timing_build:
+        if _lib_f32acc is None:
+            _lib_f32acc = C.CDLL(_build.build_f32acc())
+            _lib_f32acc.oracle_conv2d_point.restype = C.c_double
+            _lib_f32acc.oracle_rank.restype = C.c_int
+        return _lib_f32acc
     if _lib is None:
         _lib = C.CDLL(_build.build())
         _lib.oracle_conv2d_point.restype = C.c_double
         _lib.oracle_rank.restype = C.c_int
     return _lib
+
+
+def timing_build(on: bool) -> None:
+    """Switches every later call to the build whose convolution loops accumulate in float (the
+    same loops otherwise).  For timing the CPU baseline only: never on while a reference value
+    is computed, and the tests never turn it on except to check that it exists."""
+    global _timing_build
+    _timing_build = bool(on)
 
 
 def set_threads(n: int) -> None:

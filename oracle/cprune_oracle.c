@@ -29,6 +29,14 @@
 #include <stdlib.h>
 #include <string.h>
 
+/* Accumulator of the convolution loops.  double: the parity build, the only one the tests
+ * compare against.  Compiled with -DORACLE_ACC_T=float the same loops accumulate in float:
+ * that build exists for the CPU timing row of the benchmark alone (what the loops cost at the
+ * GPU path's own accumulation width) and is never used as a reference. */
+#ifndef ORACLE_ACC_T
+#define ORACLE_ACC_T double
+#endif
+
 #define ACT_NONE 0
 #define ACT_RELU 1
 #define ACT_RELU6 2
@@ -140,7 +148,7 @@ void oracle_conv2d_f64(const float* x, const float* wt, int n, int c_in, int h, 
       int g = o / opg;
       for (int y = 0; y < ho; ++y)
         for (int xo = 0; xo < wo; ++xo) {
-          double acc = 0.0;
+          ORACLE_ACC_T acc = 0;
           for (int c = 0; c < cpg; ++c)
             for (int u = 0; u < kh; ++u) {
               int iy = y * stride + u - pad;
@@ -148,11 +156,11 @@ void oracle_conv2d_f64(const float* x, const float* wt, int n, int c_in, int h, 
               for (int v = 0; v < kw; ++v) {
                 int ix = xo * stride + v - pad;
                 if (ix < 0 || ix >= w) continue;
-                acc += (double)x[(((long)b * c_in + g * cpg + c) * h + iy) * w + ix] *
-                       (double)wt[(((long)o * cpg + c) * kh + u) * kw + v];
+                acc += (ORACLE_ACC_T)x[(((long)b * c_in + g * cpg + c) * h + iy) * w + ix] *
+                       (ORACLE_ACC_T)wt[(((long)o * cpg + c) * kh + u) * kw + v];
               }
             }
-          z[(((long)b * c_out + o) * ho + y) * wo + xo] = acc;
+          z[(((long)b * c_out + o) * ho + y) * wo + xo] = (double)acc;
         }
     }
 }

@@ -78,6 +78,13 @@ __global__ __launch_bounds__(256) void conv_patch32_kernel(PatchArgs a) {
 
   const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);
   const __amdgpu_buffer_rsrc_t wr = make_rsrc(a.w, a.w_bytes);
+  // bias values of the epilogue (register v of a 32 x 32 block: filter 8 * (v / 4) + 4 * h + v % 4), requested
+  // ahead of the main loop: asked for in the epilogue, the last tiles of a layer would wait for them in full
+  float4_t bias4[MB2][4];
+#pragma unroll
+  for (int i = 0; i < MB2; ++i)
+#pragma unroll
+    for (int vq = 0; vq < 4; ++vq) bias4[i][vq] = load_bias4(a.bias, a.O, o0 + i * 32 + 8 * vq + 4 * h);
 
   // ---- staging items (as conv_patch_kernel) ----
   unsigned b_off[NIB];
@@ -276,7 +283,7 @@ __global__ __launch_bounds__(256) void conv_patch32_kernel(PatchArgs a) {
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
           const float4_t four = (float4_t){acc[i][j][4 * vq], acc[i][j][4 * vq + 1], acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]};
-          nhwc_store4<T>(e, four, p, o0 + i * 32 + 8 * vq + 4 * h);
+          nhwc_store4<T>(e, four, p, o0 + i * 32 + 8 * vq + 4 * h, bias4[i][vq]);
         }
     }
   } else {
@@ -300,7 +307,7 @@ __global__ __launch_bounds__(256) void conv_patch32_kernel(PatchArgs a) {
         for (int vq = 0; vq < 4; ++vq) {
           const int o = o0 + i * 32 + 8 * vq + 4 * h;
           float4_t m;
-          const float4_t bias = load_bias4(a.bias, a.O, o);
+          const float4_t bias = bias4[i][vq];
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             float x = acc[i][j][4 * vq + c] + bias[c];
@@ -309,7 +316,7 @@ __global__ __launch_bounds__(256) void conv_patch32_kernel(PatchArgs a) {
             x = fmaxf(x, __shfl_xor(x, TW, 64));
             m[c] = x;
           }
-          if (writer) nhwc_store4<T>(e, m, p, o);
+          if (writer) nhwc_store4<T>(e, m, p, o, (float4_t){0.f, 0.f, 0.f, 0.f});
         }
     }
   }

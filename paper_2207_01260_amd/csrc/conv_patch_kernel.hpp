@@ -83,9 +83,11 @@ __device__ __forceinline__ void mma_round(const uint4 (&af)[MB], const uint4 (&b
 // Epilogue of the patch tilings: wavefront `wave` holds NB 16-pixel blocks (pixel id = wave * NB * 16 + j * 16 + r in
 // the (image, row, column) order of a TH x TW tile) x MB filter blocks; bias, residual, activation, 16-byte
 // channels-last stores, or the 2x2 / stride-2 max-pool fused behind the activation.
+// bias4[i]: the four bias values of filter block i for this lane (load_bias4 at o0 + i * 16 + 4 * g4), fetched by
+// the caller before its main loop: asked for here, the last tiles of a layer would wait for them in full.
 template <typename T, int MB, int TH, int TW, int NB>
 __device__ __forceinline__ void patch_epilogue(const PatchArgs& a, float4_t (&acc)[MB][NB], int wave, int r, int g4,
-                                               int n0, int ty0, int tx0, int o0) {
+                                               int n0, int ty0, int tx0, int o0, const float4_t (&bias4)[MB]) {
   ConvArgs e;
   e.bias = a.bias; e.res = a.res; e.y = a.y; e.O = a.O; e.Cop = a.Cop; e.act = a.act; e.vec_out = a.vec_out; e.pool4 = 0;
   if (!a.pool) {
@@ -97,7 +99,7 @@ __device__ __forceinline__ void patch_epilogue(const PatchArgs& a, float4_t (&ac
       if (n >= a.N || oy >= a.H || ox >= a.W) continue;
       const int p = (n * a.H + oy) * a.W + ox;
 #pragma unroll
-      for (int i = 0; i < MB; ++i) nhwc_store4<T>(e, acc[i][j], p, o0 + i * 16 + 4 * g4);
+      for (int i = 0; i < MB; ++i) nhwc_store4<T>(e, acc[i][j], p, o0 + i * 16 + 4 * g4, bias4[i]);
     }
   } else {
     // bias + activation, then the max over each 2x2 window.  Horizontal partner: lane
@@ -111,7 +113,7 @@ __device__ __forceinline__ void patch_epilogue(const PatchArgs& a, float4_t (&ac
     for (int i = 0; i < MB; ++i) {
       const int o = o0 + i * 16 + 4 * g4;
       float4_t v[NB];
-      const float4_t bias = load_bias4(a.bias, a.O, o);
+      const float4_t bias = bias4[i];
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
 #pragma unroll
@@ -136,10 +138,16 @@ __device__ __forceinline__ void patch_epilogue(const PatchArgs& a, float4_t (&ac
         const int oy = ty0 + ty, ox = tx0 + tx, n = n0 + img;
         if ((ty & 1) || (tx & 1) || n >= a.N || oy >= a.H || ox >= a.W) continue;
         const int p = (n * hp + (oy >> 1)) * wp + (ox >> 1);
-        nhwc_store4<T>(e, m, p, o);
+        nhwc_store4<T>(e, m, p, o, (float4_t){0.f, 0.f, 0.f, 0.f});
       }
     }
   }
+}
+
+template <typename T, int MB>
+__device__ __forceinline__ void load_tile_bias(const PatchArgs& a, int o0, int g4, float4_t (&bias4)[MB]) {
+#pragma unroll
+  for (int i = 0; i < MB; ++i) bias4[i] = load_bias4(a.bias, a.O, o0 + i * 16 + 4 * g4);
 }
 
 template <typename T, int MB, int TH, int TW, int NI, int KQ, int KS>
@@ -193,6 +201,8 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
 
   const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);
   const __amdgpu_buffer_rsrc_t wr = make_rsrc(a.w, a.w_bytes);
+  float4_t bias4[MB];
+  load_tile_bias<T, MB>(a, o0, g4, bias4);
 
   // ---- staging items ----
   unsigned b_off[NIB];   // byte offset of (patch pixel, quad) at chunk 0, kOutOfRange outside the image
@@ -367,7 +377,7 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
   }
 
   // ---- epilogue ----
-  patch_epilogue<T, MB, TH, TW, NB>(a, acc, wave, r, g4, n0, ty0, tx0, o0);
+  patch_epilogue<T, MB, TH, TW, NB>(a, acc, wave, r, g4, n0, ty0, tx0, o0, bias4);
 }
 
 // Patch variants: id, mb, th, tw, ni (images per tile, for maps smaller than the tile),

@@ -186,6 +186,8 @@ __global__ __launch_bounds__(256) void conv_stem2_kernel(Stem2Args a) {
   __syncthreads();
 
   // ---- stage 2: the second layer, every input channel in one chunk ----
+  float4_t bias4[MB];    // for the epilogue, requested ahead of the multiply
+  load_tile_bias<T, MB>(p, o0, g4, bias4);
   int b_frag[NB];
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
@@ -229,7 +231,7 @@ __global__ __launch_bounds__(256) void conv_stem2_kernel(Stem2Args a) {
     default: break;
   }
 
-  patch_epilogue<T, MB, TH, TW, NB>(p, acc, wave, r, g4, n, ty0, tx0, o0);
+  patch_epilogue<T, MB, TH, TW, NB>(p, acc, wave, r, g4, n, ty0, tx0, o0, bias4);
 }
 
 // LDS bytes of the kernel for a filter tile of mb blocks and an element size

@@ -17,17 +17,17 @@ from . import binding as B
 from . import pipeline, synth
 
 
-def run(c_in=128, c_full=128, hw=56, batch=8, dtype=B.F32, step=1, iters=20, direct_api=False):
+def run(c_in=128, c_full=128, hw=56, batch=8, dtype=B.F32, step=1, iters=20, direct_api=False, counts=None):
     """One row per number of surviving filters.  Default: the layer runs inside a one-layer
     inference handle (channels-last kernels, variant picked by timing at handle creation,
     time = device time of the layer by HIP events).  direct_api=True times the NCHW entry
-    point cprune_conv2d_bn_relu with cprune_select_tile instead."""
+    point cprune_conv2d_bn_relu with cprune_select_tile instead.  counts: only these filter counts."""
     net = synth.single_conv(c_in, c_full, hw)
     params = synth.layer_params(net, 5)
     dparams = pipeline.upload_params(params)
     x = torch.from_numpy(synth.net_input(net, 5, batch)).cuda().to(B.TORCH_DTYPE[dtype])
     rows = []
-    for c_out in range(1, c_full + 1, step):
+    for c_out in (counts if counts is not None else range(1, c_full + 1, step)):
         layers, _ = pipeline.prune_net(net, dparams, dtype, keep_override={0: c_out})
         w, b = layers[0]["w"], layers[0]["b"]
         if direct_api:

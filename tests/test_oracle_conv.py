@@ -228,3 +228,21 @@ def test_fc_brute_force(orc):
     y = orc.fc(x, w, b)
     assert y.tolist() == [[1, 7, 1, -7], [0, 2, -4, -9.5]]
     assert orc.fc(x, w, b, synth.ACT_RELU).tolist() == [[1, 7, 1, 0], [0, 2, 0, 0]]
+
+
+def test_timing_build_is_the_same_loops_in_float():
+    """The build whose accumulator is float (for the benchmark's CPU timing row) runs the same
+    loops: it agrees with the parity build to float rounding, and is not the parity build."""
+    import oracle
+    x = synth.tensor_normal((2, 24, 11, 11), 901)
+    w = synth.tensor_normal((7, 24, 3, 3), 902, std=0.1)
+    ref = oracle.conv2d_bias_act(x, w, None, 1, 1, 1, 0, None)
+    oracle.timing_build(True)
+    try:
+        f32 = oracle.conv2d_bias_act(x, w, None, 1, 1, 1, 0, None)
+    finally:
+        oracle.timing_build(False)
+    again = oracle.conv2d_bias_act(x, w, None, 1, 1, 1, 0, None)
+    assert np.array_equal(ref, again)
+    assert not np.array_equal(ref, f32)
+    assert np.max(np.abs(ref - f32)) < 1e-5 * np.max(np.abs(ref))
