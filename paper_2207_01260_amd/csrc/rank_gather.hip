@@ -10,6 +10,7 @@
 // every layer in a second and gathers + folds every layer in a third.
 #include "common.hpp"
 
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -80,39 +81,57 @@ __global__ __launch_bounds__(256) void l1_score_group_kernel(const float* __rest
 }
 
 // ---- rank / select ---------------------------------------------------------------
-// Enumeration sort in one work-group: rank(i) = #{ j : s_j > s_i or (s_j == s_i and j < i) }.
-// order[rank(i)] = i; filter i survives iff rank(i) < keep; its slot in the ascending kept
-// list is the number of surviving filters with a lower index (wavefront ballots + a scan
-// over the 16 wavefront totals).
+// One work-group sorts a layer's filters by (score descending, index ascending) with a bitonic
+// network in LDS (a total order: equal scores rank the lower index first, so the result is
+// unique), then marks the first `keep` of that order as surviving and writes them out in
+// ascending index: a filter's slot is the number of surviving filters with a lower index
+// (wavefront ballots + a scan over the 16 wavefront totals).  The list is padded to a power of
+// two with entries that rank behind every filter.
+__device__ __forceinline__ bool ranks_before(double sa, int ia, double sb, int ib) {
+  return sa > sb || (sa == sb && ia < ib);
+}
+
 __device__ __forceinline__ void rank_select(const double* __restrict__ scores, int c, int keep,
                                             int32_t* __restrict__ order, int32_t* __restrict__ kept,
-                                            double* s, int* wave_total) {
-  for (int i = threadIdx.x; i < c; i += 1024) s[i] = scores[i];
+                                            double* s, int* idx, unsigned char* alive, int* wave_total) {
+  int n = 64;
+  while (n < c) n <<= 1;
+  for (int i = threadIdx.x; i < n; i += 1024) {
+    s[i] = i < c ? scores[i] : -1.0;   // scores are sums of absolute values: never negative
+    idx[i] = i;
+  }
+  __syncthreads();
+  for (int k = 2; k <= n; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = threadIdx.x; t < (n >> 1); t += 1024) {
+        const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;   // the pair this thread orders
+        const bool up = (lo & k) == 0;                                       // direction of its subsequence
+        const double sl = s[lo], sh = s[hi];
+        const int il = idx[lo], ih = idx[hi];
+        if (ranks_before(sh, ih, sl, il) == up) { s[lo] = sh; s[hi] = sl; idx[lo] = ih; idx[hi] = il; }
+      }
+      __syncthreads();
+    }
+  }
+  for (int i = threadIdx.x; i < c; i += 1024) alive[i] = 0;
+  __syncthreads();
+  for (int rnk = threadIdx.x; rnk < c; rnk += 1024) {
+    const int i = idx[rnk];
+    if (order) order[rnk] = i;
+    if (rnk < keep) alive[i] = 1;
+  }
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int base = 0;   // surviving filters below the current round of 1024 indices
   for (int i0 = 0; i0 < c; i0 += 1024) {
     const int i = i0 + threadIdx.x;
-    bool alive = false;
-    if (i < c) {
-      const double si = s[i];
-      int rank = 0;
-      int j = 0;
-      for (; j + 1 < c; j += 2) {
-        const double a = s[j], b = s[j + 1];
-        rank += (a > si || (a == si && j < i)) ? 1 : 0;
-        rank += (b > si || (b == si && j + 1 < i)) ? 1 : 0;
-      }
-      if (j < c) { const double a = s[j]; rank += (a > si || (a == si && j < i)) ? 1 : 0; }
-      if (order) order[rank] = i;
-      alive = rank < keep;
-    }
-    const unsigned long long mask = __ballot(alive);
+    const bool live = i < c && alive[i];
+    const unsigned long long mask = __ballot(live);
     if (lane == 0) wave_total[wave] = __popcll(mask);
     __syncthreads();
     int before = base;
     for (int k = 0; k < wave; ++k) before += wave_total[k];
-    if (alive) kept[before + __popcll(mask & ((1ull << lane) - 1ull))] = i;
+    if (live) kept[before + __popcll(mask & ((1ull << lane) - 1ull))] = i;
     int all = 0;
     for (int k = 0; k < 16; ++k) all += wave_total[k];
     base += all;
@@ -124,8 +143,10 @@ __global__ __launch_bounds__(1024) void rank_select_kernel(const double* __restr
                                                            int32_t* __restrict__ order,
                                                            int32_t* __restrict__ kept) {
   __shared__ double s[kMaxRankFilters];
+  __shared__ int idx[kMaxRankFilters];
+  __shared__ unsigned char alive[kMaxRankFilters];
   __shared__ int wave_total[16];
-  rank_select(scores, c, keep, order, kept, s, wave_total);
+  rank_select(scores, c, keep, order, kept, s, idx, alive, wave_total);
 }
 
 __device__ __forceinline__ int clamp_index(int v, int n) { return v < 0 ? 0 : (v >= n ? n - 1 : v); }
@@ -214,9 +235,11 @@ __device__ __forceinline__ void gather_row(const GatherJob& g, int i, int slice,
   }
 }
 
+// dynamic LDS: the staged source row (as long as the launch's longest; more work-groups fit a compute unit
+// when rows are short)
 template <typename T>
 __global__ __launch_bounds__(256) void gather_fold_kernel(GatherJob g) {
-  __shared__ __align__(16) float row[kRowLds];
+  extern __shared__ __align__(16) float row[];
   __shared__ double terms[2];
   gather_row<T>(g, blockIdx.x, blockIdx.y, row, terms);
 }
@@ -257,14 +280,16 @@ __global__ __launch_bounds__(256) void plan_score_kernel(const RankJob* __restri
 __global__ __launch_bounds__(1024) void plan_rank_kernel(const RankJob* __restrict__ jobs,
                                                          const double* __restrict__ scores) {
   __shared__ double s[kMaxRankFilters];
+  __shared__ int idx[kMaxRankFilters];
+  __shared__ unsigned char alive[kMaxRankFilters];
   __shared__ int wave_total[16];
   const RankJob jb = jobs[blockIdx.x];
-  rank_select(scores + jb.score0, jb.c, jb.keep, nullptr, jb.kept, s, wave_total);
+  rank_select(scores + jb.score0, jb.c, jb.keep, nullptr, jb.kept, s, idx, alive, wave_total);
 }
 
 template <typename T>
 __global__ __launch_bounds__(256) void plan_gather_kernel(const GatherJob* __restrict__ jobs, int n_jobs) {
-  __shared__ __align__(16) float row[kRowLds];
+  extern __shared__ __align__(16) float row[];
   __shared__ double terms[2];
   const int b = blockIdx.x;
   int lo = 0, hi = n_jobs - 1;           // last job whose block0 <= b
@@ -448,9 +473,10 @@ extern "C" int cprune_gather_pruned_weights(const float* w, int c_out, int c_in,
   int rc = finish_gather_job(&g);
   if (rc != CPRUNE_OK) return rc;
   dim3 grid((unsigned)n_out, (unsigned)g.slices);
-  if (out_dtype == CPRUNE_F32) hipLaunchKernelGGL(gather_fold_kernel<float>, grid, dim3(256), 0, s, g);
-  else if (out_dtype == CPRUNE_F16) hipLaunchKernelGGL(gather_fold_kernel<_Float16>, grid, dim3(256), 0, s, g);
-  else hipLaunchKernelGGL(gather_fold_kernel<__bf16>, grid, dim3(256), 0, s, g);
+  const size_t lds = g.staged ? (size_t)c_in * g.khw * sizeof(float) : 0;
+  if (out_dtype == CPRUNE_F32) hipLaunchKernelGGL(gather_fold_kernel<float>, grid, dim3(256), lds, s, g);
+  else if (out_dtype == CPRUNE_F16) hipLaunchKernelGGL(gather_fold_kernel<_Float16>, grid, dim3(256), lds, s, g);
+  else hipLaunchKernelGGL(gather_fold_kernel<__bf16>, grid, dim3(256), lds, s, g);
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }
@@ -464,6 +490,7 @@ struct cprune_prune_plan {
   GatherJob* d_gather_jobs = nullptr;
   double* d_scores = nullptr;
   int n_waves = 0, n_blocks = 0, dtype = CPRUNE_F32;
+  size_t gather_lds = 0;   // bytes of the longest source row any layer stages
   long weights_read = 0, weights_written = 0;   // elements
 };
 
@@ -547,6 +574,7 @@ extern "C" int cprune_prune_plan_create(const cprune_prune_layer* layers, int n_
     g.n_in = L.cols_from >= 0 ? layers[L.cols_from].keep : L.c_in;
     g.eps = (double)eps;
     rc = finish_gather_job(&g);
+    if (g.staged) p->gather_lds = std::max(p->gather_lds, (size_t)g.c_in * g.khw * sizeof(float));
     g.block0 = p->n_blocks;
     p->n_blocks += g.n_out * g.slices;
     p->weights_read += (long)g.n_out * g.c_in * g.khw;
@@ -584,9 +612,10 @@ extern "C" int cprune_prune_plan_run(cprune_prune_plan* p, void* stream) {
   }
   if (n_gather > 0) {
     dim3 grid((unsigned)p->n_blocks);
-    if (p->dtype == CPRUNE_F32) hipLaunchKernelGGL(plan_gather_kernel<float>, grid, dim3(256), 0, s, p->d_gather_jobs, n_gather);
-    else if (p->dtype == CPRUNE_F16) hipLaunchKernelGGL(plan_gather_kernel<_Float16>, grid, dim3(256), 0, s, p->d_gather_jobs, n_gather);
-    else hipLaunchKernelGGL(plan_gather_kernel<__bf16>, grid, dim3(256), 0, s, p->d_gather_jobs, n_gather);
+    const size_t lds = p->gather_lds;
+    if (p->dtype == CPRUNE_F32) hipLaunchKernelGGL(plan_gather_kernel<float>, grid, dim3(256), lds, s, p->d_gather_jobs, n_gather);
+    else if (p->dtype == CPRUNE_F16) hipLaunchKernelGGL(plan_gather_kernel<_Float16>, grid, dim3(256), lds, s, p->d_gather_jobs, n_gather);
+    else hipLaunchKernelGGL(plan_gather_kernel<__bf16>, grid, dim3(256), lds, s, p->d_gather_jobs, n_gather);
     CPRUNE_LAUNCH_CHECK();
   }
   return CPRUNE_OK;
