@@ -60,7 +60,7 @@ def time_forward_cold(handle, x, steps):
     return total / steps
 
 
-def net_report(name, net, cid, batch, dtype, steps):
+def net_report(name, net, cid, batch, dtype, steps, ceilings=None):
     params = synth.layer_params(net, cid)
     dparams = pipeline.upload_params(params)
     layers, kept = pipeline.prune_net(net, dparams, dtype)
@@ -98,6 +98,8 @@ def net_report(name, net, cid, batch, dtype, steps):
         if g["bytes"] and g["ms"] > 0:
             gbs = g["bytes"] / (g["ms"] * 1e-3) / 1e9
             row.update(gbs=round(gbs, 1), frac_hbm_peak=round(gbs / PEAK_GBS, 4))
+            if ceilings:     # the same rate against what a plain copy of the same bytes reaches on this device
+                row.update(frac_of_measured_copy=round(gbs / ceilings["copy_gbs"], 4))
         by_kind[kind] = row
     total = pipeline.useful_flops(net, kept_counts, batch)
     fused = sum(1 for i, L in enumerate(net.layers) if L.kind == "conv" and L.groups != 1 and handle.layer_fused(i))
@@ -143,8 +145,9 @@ def main():
     print(json.dumps({"device": props.name, "compute_units": props.multi_processor_count,
                       "clock_mhz": getattr(props, "clock_rate", 0) // 1000,
                       "hbm_gib": round(props.total_memory / 2 ** 30, 1)}), flush=True)
+    ceilings = None
     if not args.only:
-        report_device(steps)
+        ceilings = report_device(steps)
     cases = [("pruned VGG-16 32x32", synth.vgg16(10, 32), 2, [(1, B.F32), (64, B.F32), (1, B.F16), (64, B.F16)]),
              ("pruned ResNet-18 224x224", synth.resnet18(1000, 224), 3, [(1, B.F32), (32, B.F32), (1, B.BF16), (32, B.BF16)]),
              ("pruned MobileNetV2 224x224", synth.mobilenetv2(1000, 224), 4, [(1, B.F32), (64, B.F32)]),
@@ -157,20 +160,23 @@ def main():
                 continue
             if args.only and ((args.batch and batch != args.batch) or (args.dtype and DT_NAME[dtype] != args.dtype)):
                 continue
-            print(json.dumps(net_report(name, net, cid, batch, dtype, steps)), flush=True)
+            print(json.dumps(net_report(name, net, cid, batch, dtype, steps, ceilings)), flush=True)
 
 
 def report_device(steps):
     ceil = {"mfma_f32_tflops": round(B.cprune_probe_mfma(B.F32), 1),
             "mfma_f16_tflops": round(B.cprune_probe_mfma(B.F16), 1),
             "mfma_bf16_tflops": round(B.cprune_probe_mfma(B.BF16), 1),
-            "copy_gbs": round(B.cprune_probe_copy(1 << 30), 1),
+            "copy_gbs": round(B.cprune_probe_copy(1 << 32), 1),      # 4 GiB each way: well past the 256 MiB last-level cache
+            "read_only_gbs": round(B.cprune_probe_read(1 << 32), 1),
+            "write_only_gbs": round(B.cprune_probe_write(1 << 32), 1),
             "l2_read_gbs_per_cu": {"consecutive_kib": round(B.cprune_probe_l2_read(0), 1),
                                    "rows_of_64_bytes": round(B.cprune_probe_l2_read(1), 1)},
             "datasheet": {"mfma_f32_tflops": 157.3, "mfma_f16_bf16_tflops": 2500.0, "hbm_gbs": 8000.0}}
     print(json.dumps({"measured_ceilings": ceil}), flush=True)
     for row in single_layer_report(steps):
         print(json.dumps(row), flush=True)
+    return ceil
 
 
 if __name__ == "__main__":
