@@ -325,6 +325,15 @@ int cprune_net_layer_variant(const cprune_net* net, int layer, int* variant_out)
  * forms and keeps the faster; this call forces one.  enable: 0 / 1.  CPRUNE_ERR_UNSUPPORTED when the
  * network does not open that way.  Synchronises; recorded graphs are dropped. */
 int cprune_net_fuse_first_layers(cprune_net* net, int enable);
+/* How a 7x7 / stride 2 / pad 3 first layer on the image (at most 3 channels) runs in a 16-bit handle: the
+ * opening of the ImageNet networks of Section 4.1 (ResNet-18, Table 1).  form 0: the general kernels;
+ * 1: the kernel made for this layer in 16-bit data; 2: that kernel with the 3x3 / stride 2 / pad 1 max-pool
+ * behind the layer inside it (the conv map is then never stored: cprune_net_copy_activation of the conv
+ * layer returns CPRUNE_ERR_UNSUPPORTED, the pool layer's activation is the pooled map as always).
+ * cprune_net_create(tune = 1) times the forms and keeps the fastest, tune = 0 takes the highest available.
+ * CPRUNE_ERR_UNSUPPORTED for fp32 handles, for networks that do not open that way, and for form 2 when
+ * the conv map has another reader or no such pool follows.  Synchronises; recorded graphs are dropped. */
+int cprune_net_first_layer_form(cprune_net* net, int form);
 
 /* A depthwise conv (3x3 or 5x5, stride 1 or 2, "same" padding) whose only reader is a 1x1
  * conv can run inside that conv's kernel (the tensor between them is then never stored).

@@ -60,7 +60,7 @@ EXPORTS = [
     "cprune_net_create", "cprune_net_forward", "cprune_net_layer_times",
     "cprune_net_copy_activation", "cprune_net_output_shape", "cprune_net_layer_variant",
     "cprune_net_set_layer_variant", "cprune_net_fuse_depthwise", "cprune_net_fuse_block",
-    "cprune_net_fuse_first_layers", "cprune_net_layer_fused",
+    "cprune_net_fuse_first_layers", "cprune_net_first_layer_form", "cprune_net_layer_fused",
     "cprune_net_destroy",
     "cprune_probe_scratch_bytes", "cprune_probe_mfma", "cprune_probe_copy", "cprune_probe_read",
     "cprune_probe_write",
@@ -639,6 +639,10 @@ class Net:
     def fuse_block(self, layer: int, enable: bool):
         _check(lib().cprune_net_fuse_block(self._h, C.c_int(layer), C.c_int(1 if enable else 0)),
                "cprune_net_fuse_block")
+
+    def first_layer_form(self, form: int):
+        """How a 16-bit 7x7 / stride 2 first layer runs: 0 general kernels, 1 its own kernel, 2 with the max-pool."""
+        _check(lib().cprune_net_first_layer_form(self._h, C.c_int(form)), "cprune_net_first_layer_form")
 
     def fuse_first_layers(self, enable: bool):
         _check(lib().cprune_net_fuse_first_layers(self._h, C.c_int(1 if enable else 0)),

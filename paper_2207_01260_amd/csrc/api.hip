@@ -360,6 +360,10 @@ struct NetLayer {
   void* w_wave = nullptr;     // 3x3 / stride 1 / pad 1 layer on a small map: weights once more, packed for the
                               // independent-wavefront kernel
   bool stem = false;          // nchw_in layer that runs the first-layer kernel (whole reduction in LDS)
+  void* w_stem7 = nullptr;    // 16-bit 7x7 / stride 2 / pad 3 first layer: weights packed for the kernel made for it
+  int stem7 = 0;              // 1: that kernel runs the layer; 2: and the 3x3 / stride 2 max-pool pool3 with it
+  int pool3 = -1;             // the max-pool that can run inside that kernel (the layer's only reader), or -1
+  bool in_producer = false;   // max-pool computed inside its producer's kernel: no launch, its buffer is written there
   int stem_ok = 0;            // that kernel exists for the layer's window and stride
   bool nchw_in = false;       // dense conv on the network input: reads the caller's NCHW tensor and its own
                               // OIHW weights, writes channels-last (no layout conversion pass)
@@ -469,6 +473,42 @@ static int net_run_stem(cprune_net* net, int i, int n, const void* x, void* dst,
   return CPRUNE_OK;
 }
 
+// The 16-bit 7x7 / stride 2 first-layer kernel on the caller's NCHW input, with or without the max-pool behind it.
+static int net_run_stem7(cprune_net* net, int i, int n, const void* x, void* dst, hipStream_t s) {
+  const NetLayer& L = net->layers[i];
+  const bool pool = L.stem7 == 2;
+  StemArgs a;
+  a.x = x; a.w = L.w_stem7; a.bias = L.b; a.y = dst;
+  a.N = n; a.C = L.d.c_in; a.H = L.h_in; a.W = L.w_in; a.Ho = L.h_out; a.Wo = L.w_out;
+  a.O = L.d.c_out; a.Cop = L.cp_out; a.pad = L.d.pad; a.act = L.d.act;
+  const int mb = L.d.c_out <= 32 ? 2 : 4;
+  a.tiles_m = (a.O + mb * 16 - 1) / (mb * 16);
+  if (pool) {
+    const NetLayer& P = net->layers[L.pool3];
+    a.y = P.act; a.Hp = P.h_out; a.Wp = P.w_out; a.Cop = P.cp_out;
+    a.tiles_y = (a.Hp + 6) / 7; a.tiles_x = (a.Wp + 6) / 7;
+  } else {
+    a.tiles_y = (a.Ho + 15) / 16; a.tiles_x = (a.Wo + 15) / 16;
+  }
+  a.vec_out = (a.Cop % 4) == 0 ? 1 : 0;
+  a.magic_x = a.tiles_x > 1 ? (unsigned)((0x100000000ull + a.tiles_x - 1) / a.tiles_x) : 0u;
+  a.magic_y = a.tiles_y > 1 ? (unsigned)((0x100000000ull + a.tiles_y - 1) / a.tiles_y) : 0u;
+  const long ptiles = (long)n * a.tiles_y * a.tiles_x;
+  // as many workers as stay resident: weight tile + patch (+ the conv block the pool reads)
+  const long lds = (long)mb * 16 * (kStem7K * 2 + 16) + 37L * 320 + (pool ? 256L * (mb * 32 + 16) : 16L);
+  long per_cu = (160 * 1024) / lds;
+  per_cu = per_cu > 8 ? 8 : (per_cu < 1 ? 1 : per_cu);
+  const long workers = ptiles < 256 * per_cu ? ptiles : 256 * per_cu;
+  dim3 grid((unsigned)workers, (unsigned)a.tiles_m);
+  int rc;
+  if (net->dtype == CPRUNE_F16) rc = launch_conv_stem7_f16(mb, pool ? 1 : 0, grid, s, a);
+  else if (net->dtype == CPRUNE_BF16) rc = launch_conv_stem7_bf16(mb, pool ? 1 : 0, grid, s, a);
+  else rc = CPRUNE_ERR_UNSUPPORTED;
+  if (rc != CPRUNE_OK) return rc;
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
 // First layer L.fuse_stem and the 3x3 layer i in one kernel: reads the caller's NCHW image.
 static int net_run_stem2(cprune_net* net, int i, int n, const void* x, void* dst, hipStream_t s) {
   const NetLayer& L = net->layers[i];
@@ -568,6 +608,7 @@ static int net_run_layer(cprune_net* net, int i, int n, const void* x, void* out
   if (L.fuse_block >= 0) return net_run_mbconv(net, i, n, dst, s);
   if (L.fuse_dw >= 0) return net_run_dwproj(net, i, n, dst, s);
   if (L.fuse_stem >= 0) return net_run_stem2(net, i, n, x, dst, s);
+  if (L.stem7) return net_run_stem7(net, i, n, src, dst, s);
   if (L.stem) return net_run_stem(net, i, n, src, dst, s);
   switch (L.d.kind) {
     case CPRUNE_LAYER_CONV:
@@ -580,7 +621,7 @@ static int net_run_layer(cprune_net* net, int i, int n, const void* x, void* out
       return conv_dispatch(d, src, L.w, L.b, res, dst, v, net->ws, net->ws_bytes, s, lay);
     }
     case CPRUNE_LAYER_MAXPOOL:
-      if (L.alias) return CPRUNE_OK;
+      if (L.alias || L.in_producer) return CPRUNE_OK;
       return launch_maxpool_nhwc(src, n, L.cp_in, L.h_in, L.w_in, L.d.k, L.d.stride, L.d.pad, net->dtype, dst, s);
     case CPRUNE_LAYER_GAVGPOOL:
       return launch_gavgpool_nhwc(src, n, L.cp_in, L.h_in * L.w_in, net->dtype, dst, s);
@@ -718,7 +759,7 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     for (int j = 0; j < n_layers; ++j)
       if (j != i && (net->layers[j].d.input == pd.input || net->layers[j].d.residual == pd.input)) shared = true;
     if (shared) continue;
-    // only where some variant can run the layer with the pool in its epilogue (none can on e.g. a 2 x 8 map)
+    // only where some variant can run the layer with the pool in its epilogue (none can on e.g. a 2 x 18 map)
     Cv.fused_pool = true;
     const cprune_conv_desc fd = layer_conv_desc(*net, Cv, max_batch);
     const ConvLayout fl = layer_layout(Cv);
@@ -883,6 +924,51 @@ extern "C" int cprune_net_create(const cprune_layer_desc* layers, int n_layers, 
     }
     L.stem = use;
     if (use) L.variant = -1;
+  }
+
+  // 16-bit data, 7x7 / stride 2 / pad 3 on the image (the first layer of the ImageNet networks): a kernel whose
+  // reduction order makes every MFMA operand one LDS read, and which can run the 3x3 / stride 2 / pad 1 max-pool
+  // behind the layer as well when nobody else reads the conv map.  With tune != 0 the three forms (as decided so far;
+  // that kernel; that kernel with the pool) are timed and the fastest kept; otherwise the most fused one is taken.
+  for (int i = 0; i < n_layers && rc == CPRUNE_OK; ++i) {
+    NetLayer& L = net->layers[i];
+    const cprune_layer_desc& d = L.d;
+    if (dtype == CPRUNE_F32 || !L.nchw_in || d.c_in > 3 || d.k != 7 || d.stride != 2 || d.pad != 3 || d.residual >= 0) continue;
+    {
+      const int mb = d.c_out <= 32 ? 2 : 4;
+      const int rows = (d.c_out + mb * 16 - 1) / (mb * 16) * (mb * 16);
+      rc = dev_alloc((size_t)rows * kStem7K * es, &L.w_stem7);
+      if (rc == CPRUNE_OK) rc = launch_repack_stem7(L.w, d.c_out, d.c_in, rows, dtype, L.w_stem7, s);
+      if (rc != CPRUNE_OK) break;
+    }
+    int reader = -1, readers = 0;
+    for (int j = 0; j < n_layers; ++j) {
+      if (net->layers[j].d.input == i) { reader = j; ++readers; }
+      if (net->layers[j].d.residual == i) readers += 2;
+    }
+    if (readers == 1 && reader != n_layers - 1) {
+      const cprune_layer_desc& pd = net->layers[reader].d;
+      if (pd.kind == CPRUNE_LAYER_MAXPOOL && pd.k == 3 && pd.stride == 2 && pd.pad == 1) L.pool3 = reader;
+    }
+    auto set_form = [&](int form) {
+      L.stem7 = form;
+      if (L.pool3 >= 0) net->layers[L.pool3].in_producer = form == 2;
+    };
+    const int n_forms = L.pool3 >= 0 ? 3 : 2;
+    int best = n_forms - 1;
+    if (tune) {
+      const int pair[2] = {i, L.pool3};
+      float ms[3] = {0.f, 0.f, 0.f};
+      for (int form = 0; form < n_forms && rc == CPRUNE_OK; ++form) {
+        set_form(form);
+        rc = time_layers(net, pair, L.pool3 >= 0 ? 2 : 1, max_batch, net->x_cl, s, &ms[form]);
+      }
+      best = 0;
+      for (int form = 1; form < n_forms; ++form)
+        if (ms[form] < ms[best]) best = form;
+    }
+    set_form(best);
+    if (best) L.variant = -1;
   }
 
   // A first layer (3x3 / stride 1, at most 32 filters) whose only reader is another 3x3 / stride 1 conv can run
@@ -1070,7 +1156,7 @@ extern "C" int cprune_net_layer_times(cprune_net* net, const void* x, int n, int
   for (int i = 0; i < nl && rc == CPRUNE_OK; ++i) {
     ms_out[i] = 0.0f;
     rc = net_run_layer(net, i, n, x, nullptr, s);   // untimed first run
-    if (rc != CPRUNE_OK || net->layers[i].alias || net->layers[i].fused_away) continue;
+    if (rc != CPRUNE_OK || net->layers[i].alias || net->layers[i].fused_away || net->layers[i].in_producer) continue;
     hipError_t e = hipEventRecord(e0, s);
     for (int it = 0; it < iters && rc == CPRUNE_OK && e == hipSuccess; ++it) rc = net_run_layer(net, i, n, x, nullptr, s);
     if (e == hipSuccess) e = hipEventRecord(e1, s);
@@ -1090,7 +1176,7 @@ extern "C" int cprune_net_copy_activation(cprune_net* net, int layer, int n, voi
   if (!net || !dst || layer < 0 || layer >= (int)net->layers.size()) return CPRUNE_ERR_INVALID_ARG;
   if (n < 1 || n > net->max_batch) return CPRUNE_ERR_INVALID_ARG;
   const NetLayer& L = net->layers[layer];
-  if (L.fused_pool) return CPRUNE_ERR_UNSUPPORTED;  // only the pooled map exists: ask for the pool layer
+  if (L.fused_pool || L.stem7 == 2) return CPRUNE_ERR_UNSUPPORTED;  // only the pooled map exists: ask for the pool layer
   if (L.fused_away) return CPRUNE_ERR_UNSUPPORTED;  // computed inside its consumer's kernel, never stored
   const size_t bytes = (size_t)L.d.c_out * L.h_out * L.w_out * n * dtype_size(net->dtype);
   if (dst_bytes < bytes) return CPRUNE_ERR_INVALID_ARG;
@@ -1136,7 +1222,7 @@ extern "C" int cprune_net_task_key(const cprune_net* net, int layer, int32_t* ke
 }
 
 static void restore_variant(cprune_net* net, NetLayer& L) {
-  if (L.variant < 0 && !L.stem)
+  if (L.variant < 0 && !L.stem && !L.stem7)
     L.variant = cached_or_heuristic_variant(layer_conv_desc(*net, L, net->max_batch), nullptr, layer_layout(L));
 }
 
@@ -1153,6 +1239,23 @@ extern "C" int cprune_net_fuse_first_layers(cprune_net* net, int enable) {
   F.fused_away = enable != 0;
   L.fuse_stem = enable ? first : -1;
   if (enable) L.variant = -1;
+  else restore_variant(net, L);
+  return CPRUNE_OK;
+}
+
+extern "C" int cprune_net_first_layer_form(cprune_net* net, int form) {
+  if (!net || form < 0 || form > 2) return CPRUNE_ERR_INVALID_ARG;
+  int first = -1;
+  for (int i = 0; i < (int)net->layers.size(); ++i)
+    if (net->layers[i].w_stem7) { first = i; break; }
+  if (first < 0) return CPRUNE_ERR_UNSUPPORTED;
+  NetLayer& L = net->layers[first];
+  if (form == 2 && L.pool3 < 0) return CPRUNE_ERR_UNSUPPORTED;
+  CPRUNE_HIP_TRY(hipDeviceSynchronize());
+  drop_graphs(net);
+  L.stem7 = form;
+  if (L.pool3 >= 0) net->layers[L.pool3].in_producer = form == 2;
+  if (form) L.variant = -1;
   else restore_variant(net, L);
   return CPRUNE_OK;
 }
@@ -1209,6 +1312,10 @@ extern "C" int cprune_net_set_layer_variant(cprune_net* net, int layer, int vari
   if (!(L.d.kind == CPRUNE_LAYER_FC || (L.d.kind == CPRUNE_LAYER_CONV && L.d.groups == 1))) return CPRUNE_ERR_INVALID_ARG;
   if (L.fuse_dw >= 0 || L.fuse_stem >= 0 || L.fused_away) return CPRUNE_ERR_INVALID_ARG;   // runs inside a fused kernel: no variants
   if (L.stem) L.stem = false;                          // a pinned variant means the general kernel
+  if (L.stem7) {
+    if (L.pool3 >= 0) net->layers[L.pool3].in_producer = false;
+    L.stem7 = 0;
+  }
   const cprune_conv_desc cd = layer_conv_desc(*net, L, net->max_batch);
   const ConvLayout lay = layer_layout(L);
   if (!variant_supports(cd, variant, lay)) return CPRUNE_ERR_UNSUPPORTED;

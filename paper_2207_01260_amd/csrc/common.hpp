@@ -209,6 +209,8 @@ struct StemArgs {
   unsigned magic_x, magic_y;   // ceil(2^32 / tiles_x), ceil(2^32 / tiles_y), 0 for a divisor of 1 (exact while
                                // pixel blocks x divisor < 2^32: always, for tensors below 2^31 bytes)
   int vec_out;
+  int Hp = 0, Wp = 0;   // 7x7 / stride 2 kernel with the 3x3 / stride 2 / pad 1 max-pool inside: the pooled map; y is
+                        // then [n][hp][wp][cop] and tiles_y, tiles_x count 7 x 7 blocks of it
 };
 // (k, stride) in {(3, 1), (3, 2), (7, 2)}, mb in {2, 4} (16-filter blocks per tile); grid.x = workers
 // that share the (image, 8x16 output block) list round-robin, grid.y = filter tiles.
@@ -218,5 +220,13 @@ int launch_repack_stem(const void* w, int o, int ktot, int rows, int kp, int dt,
 int launch_conv_stem_f32(int k, int stride, int mb, dim3 grid, hipStream_t s, const StemArgs& a);
 int launch_conv_stem_f16(int k, int stride, int mb, dim3 grid, hipStream_t s, const StemArgs& a);
 int launch_conv_stem_bf16(int k, int stride, int mb, dim3 grid, hipStream_t s, const StemArgs& a);
+// 16-bit 7x7 / stride 2 / pad 3 first layer with the reduction ordered (window row, 8 window columns, 4 channels):
+// weights [rows][224] from launch_repack_stem7 (k = u * 32 + (v + 1) * 4 + c; zero for column slot 0, channel
+// slot 3, channels beyond c and rows beyond o).  mb in {2, 4}; pool = 1 runs the 3x3 / stride 2 / pad 1 max-pool
+// too (StemArgs::Hp, Wp); grid.x = workers sharing the (image, block) list, grid.y = filter tiles.
+constexpr int kStem7K = 224;
+int launch_repack_stem7(const void* w, int o, int c, int rows, int dt, void* y, hipStream_t s);
+int launch_conv_stem7_f16(int mb, int pool, dim3 grid, hipStream_t s, const StemArgs& a);
+int launch_conv_stem7_bf16(int mb, int pool, dim3 grid, hipStream_t s, const StemArgs& a);
 
 }  // namespace cprune

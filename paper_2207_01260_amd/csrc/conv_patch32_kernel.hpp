@@ -337,9 +337,10 @@ __global__ __launch_bounds__(256) void conv_patch32_kernel(PatchArgs a) {
   X(9, 1, 1, 1, 4, 8, 1, 2)      \
   X(10, 1, 1, 1, 4, 4, 2, 2)     \
   X(11, 1, 1, 1, 4, 4, 2, 1)     \
-  X(12, 2, 1, 1, 4, 4, 2, 1)
+  X(12, 2, 1, 1, 4, 4, 2, 1)     \
+  X(13, 1, 1, 4, 8, 8, 2, 2)
 
-constexpr int kNumPatch32 = 13;
+constexpr int kNumPatch32 = 14;
 
 template <typename T>
 inline void launch_patch32(int id, dim3 grid, hipStream_t s, const PatchArgs& a) {

@@ -380,7 +380,8 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
   patch_epilogue<T, MB, TH, TW, NB>(a, acc, wave, r, g4, n0, ty0, tx0, o0, bias4);
 }
 
-// Patch variants: id, mb, th, tw, ni (images per tile, for maps smaller than the tile),
+// Patch variants: id, mb, th, tw, ni (images per tile, for maps smaller than the tile; two images of a 7x7 map
+// share an 8x8 x 2 tile),
 // kq (64-byte channel rounds per chunk), ks (wave groups per tile: 2 = eight wavefronts,
 // each group multiplying half of every chunk's rounds; for layers with about as many
 // tiles as compute units, where one group per unit leaves the MFMA pipe waiting)
@@ -407,9 +408,10 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
   X(19, 2, 4, 4, 4, 2, 2)   \
   X(20, 1, 2, 2, 16, 2, 2)  \
   X(21, 4, 8, 8, 1, 1, 2)   \
-  X(22, 2, 8, 16, 1, 1, 2)
+  X(22, 2, 8, 16, 1, 1, 2)  \
+  X(23, 2, 8, 8, 2, 2, 1)
 
-constexpr int kNumPatch = 23;
+constexpr int kNumPatch = 24;
 
 template <typename T>
 inline void launch_patch(int id, dim3 grid, hipStream_t s, const PatchArgs& a) {

@@ -437,6 +437,21 @@ __global__ __launch_bounds__(256) void repack_stem_kernel(const T* __restrict__ 
   y[i] = v;
 }
 
+// OIHW 7x7 weights -> [rows][224]: k = u * 32 + (v + 1) * 4 + c (window row, window column shifted by one slot,
+// channel), zero elsewhere
+template <typename T>
+__global__ __launch_bounds__(256) void repack_stem7_kernel(const T* __restrict__ w, T* __restrict__ y, long total,
+                                                           int o_count, int c_count) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int k = (int)(i % kStem7K);
+  const long o = i / kStem7K;
+  const int u = k >> 5, slot = (k >> 2) & 7, c = k & 3;
+  T v = (T)0.0f;
+  if (o < o_count && c < c_count && slot >= 1) v = w[((o * c_count + c) * 7 + u) * 7 + (slot - 1)];
+  y[i] = v;
+}
+
 inline dim3 blocks_for(long total) { return dim3((unsigned)((total + 255) / 256)); }
 
 int plane_slices(int total) {
@@ -661,6 +676,14 @@ int launch_repack_stem(const void* w, int o, int ktot, int rows, int kp, int dt,
   const long total = (long)rows * kp;
   CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_stem_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w, (T*)y,
                                          total, o, ktot, kp));
+  CPRUNE_LAUNCH_CHECK();
+  return CPRUNE_OK;
+}
+
+int launch_repack_stem7(const void* w, int o, int c, int rows, int dt, void* y, hipStream_t s) {
+  const long total = (long)rows * kStem7K;
+  CPRUNE_BY_DTYPE(dt, hipLaunchKernelGGL(repack_stem7_kernel<T>, blocks_for(total), dim3(256), 0, s, (const T*)w, (T*)y,
+                                         total, o, c));
   CPRUNE_LAUNCH_CHECK();
   return CPRUNE_OK;
 }

@@ -158,6 +158,7 @@ def test_pool_fc_net_reject_bad_args():
     assert L.cprune_net_destroy(None) == B.ERR_INVALID_ARG
     assert L.cprune_net_set_layer_variant(None, C.c_int(0), C.c_int(0)) == B.ERR_INVALID_ARG
     assert L.cprune_net_fuse_first_layers(None, C.c_int(1)) == B.ERR_INVALID_ARG
+    assert L.cprune_net_first_layer_form(None, C.c_int(1)) == B.ERR_INVALID_ARG
     assert L.cprune_net_fuse_depthwise(None, C.c_int(0), C.c_int(1)) == B.ERR_INVALID_ARG
     assert L.cprune_net_fuse_block(None, C.c_int(0), C.c_int(1)) == B.ERR_INVALID_ARG
     dims = (C.c_int * 3)()

@@ -199,6 +199,82 @@ def test_mobilenetv2_full_size_batch1(orc):
     handle.close()
 
 
+def _check_forward(handle, net, xd, ref_acts, dtype, batch, use_graph=False):
+    logits = handle.forward(xd, use_graph=use_graph)
+    torch.cuda.synchronize()
+    stored = 0
+    for i, r in enumerate(ref_acts[:-1]):
+        try:
+            a = handle.activation(i, batch, r.shape[1:]).float().cpu().numpy()
+        except B.CPruneError as e:
+            assert e.status == B.ERR_UNSUPPORTED
+            assert net.layers[i + 1].kind == "maxpool" or handle.layer_fused(i)
+            continue
+        stored += 1
+        check(a, r, dtype, net.layers[i].name)
+    check(logits.float().cpu().numpy(), ref_acts[-1], dtype, "logits")
+    return stored
+
+
+def _first_layer_probe(c_in, c1, h, w):
+    """image -> 7x7 / stride 2 conv -> 3x3 / stride 2 max-pool -> 3x3 conv, on a map of any size"""
+    net = synth.NetSpec(f"stemprobe_{c_in}_{c1}_{h}_{w}", c_in, h, w)
+    a = net.add(synth.Layer("conv", -1, c_in, c1, k=7, stride=2, pad=3, act=synth.ACT_RELU, bn=True, name="stem"))
+    p = net.add(synth.Layer("maxpool", a, c1, c1, k=3, stride=2, pad=1, name="pool"))
+    net.add(synth.Layer("conv", p, c1, 24, k=3, stride=1, pad=1, act=synth.ACT_NONE, bn=True, name="b"))
+    return net
+
+
+@pytest.mark.parametrize("case", [
+    ("resnet18", 3, B.F16), ("resnet18", 3, B.BF16),
+    ((3, 20, 37, 35), 2, B.BF16),     # odd image width (element-wise patch loads), ragged 7x7 pooled blocks, 32-filter tile
+    ((1, 40, 30, 50), 3, B.F16),      # one input channel, 64-filter tile with 40 filters
+    ((3, 70, 18, 22), 2, B.F16),      # two filter tiles
+])
+def test_first_layer_forms_16bit(orc, case):
+    """The 7x7 / stride 2 first layer in 16-bit data: through the general kernels (form 0), through the kernel
+    made for it (1), and with the 3x3 / stride 2 max-pool inside that kernel (2, what an untimed handle takes):
+    every stored activation and the output within the bar in each form, graph replay included."""
+    which, batch, dtype = case
+    print("first layer forms", case, flush=True)
+    net = synth.resnet18(100, 64) if which == "resnet18" else _first_layer_probe(*which)
+    cid = 70
+    params = synth.layer_params(net, cid)
+    x = synth.net_input(net, cid, batch)
+    ref_layers, _ = orc.prune_net(net, params)
+    ref_acts = orc.forward(net, ref_layers, x, return_all=True)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), dtype)
+    handle = pipeline.build_net(net, layers, batch, dtype, tune=False)
+    xd = torch.from_numpy(x).cuda().to(B.TORCH_DTYPE[dtype])
+    fused = _check_forward(handle, net, xd, ref_acts, dtype, batch)
+    with pytest.raises(B.CPruneError):          # the conv map is not stored in the form taken by default
+        handle.activation(0, batch, ref_acts[0].shape[1:])
+    for form in (1, 0, 2):
+        handle.first_layer_form(form)
+        stored = _check_forward(handle, net, xd, ref_acts, dtype, batch, use_graph=(form == 2))
+        assert stored == fused + (1 if form < 2 else 0)
+    handle.close()
+
+
+def test_first_layer_form_needs_16bit_and_a_7x7_opening(orc):
+    net = synth.resnet18(100, 64)
+    params = synth.layer_params(net, 3)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), B.F32)
+    handle = pipeline.build_net(net, layers, 1, B.F32, tune=False)
+    with pytest.raises(B.CPruneError) as e:
+        handle.first_layer_form(1)
+    assert e.value.status == B.ERR_UNSUPPORTED
+    handle.close()
+    net = synth.vgg16(10, 32)
+    params = synth.layer_params(net, 2)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), B.F16)
+    handle = pipeline.build_net(net, layers, 1, B.F16, tune=False)
+    with pytest.raises(B.CPruneError) as e:
+        handle.first_layer_form(1)
+    assert e.value.status == B.ERR_UNSUPPORTED
+    handle.close()
+
+
 # ---- the channels-last kernels on arbitrary layer shapes, every variant -----------------
 
 def _two_layer_net(c0, c1, c2, hw, k, stride, pad, act, residual):

@@ -103,9 +103,9 @@ def test_algorithm1_on_measured_latencies():
 
 def test_equal_shapes_with_and_without_pool_are_two_tasks(orc):
     """Two convolutions of the same shape, one of them with a 2x2 pool in its epilogue, run
-    different programs: two tasks, two distinct keys, and the 2 x 8 map whose pool no kernel can
+    different programs: two tasks, two distinct keys, and the 2 x 18 map whose pool no kernel can
     fuse still builds and runs (the pool stays a layer of its own)."""
-    for hw, fusable in (((8, 8), True), ((2, 8), False)):
+    for hw, fusable in (((8, 8), True), ((2, 8), True), ((2, 18), False)):
         net = synth.NetSpec("two_convs", 8, hw[0], hw[1])
         a = net.add(synth.Layer("conv", -1, 8, 8, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="a"))
         b = net.add(synth.Layer("conv", a, 8, 8, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="b"))
