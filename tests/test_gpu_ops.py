@@ -34,6 +34,7 @@ def host(t):
 @pytest.mark.parametrize("shape,keep", [
     ((64, 64, 3, 3), 45), ((7, 3, 3, 3), 1), ((1, 5, 1, 1), 1), ((130, 17, 3, 3), 129),
     ((512, 512, 3, 3), 300), ((960, 160, 1, 1), 500), ((32, 1, 3, 3), 11), ((64, 3, 7, 7), 64),
+    ((4096, 16, 1, 1), 2000),   # the most filters one ranking work-group sorts
 ])
 def test_rank_filters_bit_exact(orc, shape, keep):
     print("rank", shape, keep, flush=True)
