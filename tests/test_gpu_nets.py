@@ -367,6 +367,55 @@ def test_pooled_layer_every_variant(orc, cfg):
     assert ran >= 12 and "conv_wave_kernel" in names and "conv_patch_kernel" in names, (ran, names)
 
 
+def _random_layer_cases():
+    rng = np.random.RandomState(220701260)
+    cases = []
+    for i in range(18):
+        k = int(rng.choice([1, 3, 3, 3]))
+        stride = int(rng.choice([1, 1, 2]))
+        h, w = int(rng.randint(1, 21)), int(rng.randint(1, 21))
+        c0, c1, c2 = int(rng.randint(1, 9)), int(rng.randint(1, 91)), int(rng.randint(1, 91))
+        residual = bool(k == 3 and stride == 1 and rng.randint(0, 3) == 0)
+        if residual:
+            c2 = c1
+        act = int(rng.choice([synth.ACT_RELU, synth.ACT_NONE, synth.ACT_RELU6]))
+        cases.append((c0, c1, c2, h, w, k, stride, act, residual, int(rng.randint(1, 6)), [B.F32, B.F16, B.BF16][i % 3]))
+    return cases
+
+
+@pytest.mark.parametrize("cfg", _random_layer_cases())
+def test_random_layer_shapes_every_variant(orc, cfg):
+    """Seeded random layer shapes (maps from 1x1 to 20x20, not square, 1-90 channels, 1x1 and 3x3 windows, both
+    strides, every activation, with and without a shortcut) through every variant that accepts them."""
+    c0, c1, c2, h, w, k, stride, act, residual, batch, dtype = cfg
+    print("random probe", cfg, flush=True)
+    net = synth.NetSpec(f"rprobe_{c0}_{c1}_{c2}_{h}_{w}_{k}_{stride}", c0, h, w)
+    a = net.add(synth.Layer("conv", -1, c0, c1, k=3, stride=1, pad=1, act=synth.ACT_RELU, bn=True, name="a"))
+    net.add(synth.Layer("conv", a, c1, c2, k=k, stride=stride, pad=k // 2, act=act, bn=True,
+                        residual=(a if residual else None), name="b"))
+    cid = 90 + k + stride
+    params = synth.layer_params(net, cid)
+    x = synth.net_input(net, cid, batch)
+    ref_layers, _ = orc.prune_net(net, params)
+    ref = orc.forward(net, ref_layers, x)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), dtype)
+    handle = pipeline.build_net(net, layers, batch, dtype, tune=False)
+    xd = torch.from_numpy(x).cuda().to(B.TORCH_DTYPE[dtype])
+    ran = 0
+    for v in range(B.cprune_num_tile_variants()):
+        try:
+            handle.set_layer_variant(1, v)
+        except B.CPruneError as e:
+            assert e.status == B.ERR_UNSUPPORTED
+            continue
+        ran += 1
+        out = handle.forward(xd)
+        torch.cuda.synchronize()
+        check(out.float().cpu().numpy(), ref, dtype, f"{cfg} {B.cprune_tile_variant_name(v, True, dtype)}")
+    handle.close()
+    assert ran >= 50
+
+
 @pytest.mark.parametrize("cfg", [
     # c0, c1, c2, hw, pool, batch, dtype: image -> 3x3 conv -> 3x3 conv [-> 2x2 pool] as one kernel
     (3, 28, 29, 32, True, 5, B.F32),      # the opening of the benchmark's network
