@@ -222,6 +222,32 @@ def test_conv_16bit(orc, dtype):
     _conv_case(orc, 1, 3, 37, 35, 20, 7, 2, 3, dtype=dtype, variants=(-1, 5), tag=4)
 
 
+@pytest.mark.parametrize("dtype", [B.F16, B.BF16])
+def test_conv_16bit_kernel_error_alone(orc, dtype):
+    """Diagnostic beside the headline bar: against the oracle fed the SAME 16-bit-rounded input and weights the
+    only differences left are the fp32 summation order and the final rounding of the output to 16 bits, so
+    the error must be about one unit in the last place of the output type (2^-11 fp16, 2^-8 bf16), far inside
+    the 2e-2 that covers the quantisation of inputs and weights as well."""
+    n, c_in, h, w, c_out = 2, 45, 13, 11, 37
+    td = B.TORCH_DTYPE[dtype]
+    x = synth.tensor_normal((n, c_in, h, w), 130, 1)
+    wt = synth.tensor_normal((c_out, c_in, 3, 3), 131, 1, std=(2.0 / (c_in * 9)) ** 0.5)
+    bias = synth.tensor_normal((c_out,), 132, 1, std=0.1)
+    xr = torch.from_numpy(x).to(td).float().numpy()       # round to nearest even, back to fp32 exactly
+    wr = torch.from_numpy(wt).to(td).float().numpy()
+    ref = orc.conv2d_bias_act(xr, wr, bias, 1, 1, 1, B.ACT_RELU, None)
+    d = B.conv_desc(x.shape, wt.shape, 1, 1, 1, dtype, B.ACT_RELU, False)
+    ulp = 2.0 ** -11 if dtype == B.F16 else 2.0 ** -8
+    for v in (-1, 0, 130, 150):
+        try:
+            y = B.cprune_conv2d_bn_relu(d, dev(x, dtype), dev(wt, dtype), dev(bias), None, v)
+        except B.CPruneError as e:
+            assert e.status == B.ERR_UNSUPPORTED
+            continue
+        g = host(y)
+        assert np.max(np.abs(g - ref)) / np.max(np.abs(ref)) < 1.5 * ulp, (v, np.max(np.abs(g - ref)) / np.max(np.abs(ref)))
+
+
 def test_conv_repeatable(orc):
     x = dev(synth.tensor_normal((2, 64, 16, 16), 124))
     w = dev(synth.tensor_normal((96, 64, 3, 3), 125, std=0.05))

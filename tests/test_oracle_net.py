@@ -45,6 +45,17 @@ def test_exact_counts():
     assert synth.count_macs_params(synth.mnasnet()) == (314415872, 4345392)
 
 
+def test_activations_stay_inside_fp16_range(orc):
+    """Self-test of the generators: no activation of the seeded networks comes near the largest fp16 value,
+    so a 16-bit run can only differ from the fp32-master oracle by rounding, never by overflow."""
+    for net, cid, batch in ((synth.vgg16(10, 32), 2, 2), (synth.resnet18(100, 64), 3, 1), (synth.mobilenetv2(100, 64), 4, 1)):
+        params = synth.layer_params(net, cid)
+        layers, _ = orc.prune_net(net, params)
+        acts = orc.forward(net, layers, synth.net_input(net, cid, batch), return_all=True)
+        worst = max(float(np.max(np.abs(a))) for a in acts)
+        assert worst < 65504.0 / 16, (net.name, worst)
+
+
 def test_keep_count_rule():
     assert synth.keep_count(0.7, 64) == 45
     assert synth.keep_count(0.5, 3) == 2          # 1.5 rounds half up
