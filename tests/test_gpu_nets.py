@@ -96,6 +96,31 @@ def test_vgg16_16bit(orc, dtype):
     handle.close()
 
 
+def test_two_handles_on_two_streams(orc):
+    """The caller owns the stream: two handles of the same net run side by side on two streams of the
+    caller's (default priority), eagerly and as recorded graphs, and give the bits of a run on one stream."""
+    net = synth.vgg16(10, 32)
+    params = synth.layer_params(net, 2)
+    layers, _ = pipeline.prune_net(net, pipeline.upload_params(params))
+    x = torch.from_numpy(synth.net_input(net, 2, 4)).cuda()
+    h0 = pipeline.build_net(net, layers, 4, tune=False)
+    h1 = pipeline.build_net(net, layers, 4, tune=False)
+    want = h0.forward(x).clone()
+    torch.cuda.synchronize()
+    s0, s1 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for rep in range(4):
+        with torch.cuda.stream(s0):
+            a = h0.forward(x, use_graph=(rep % 2 == 1)).clone()
+        with torch.cuda.stream(s1):
+            b = h1.forward(x, use_graph=(rep % 2 == 1)).clone()
+        outs += [a, b]
+    s0.synchronize(); s1.synchronize()
+    for o in outs:
+        assert torch.equal(o, want)
+    h0.close(); h1.close()
+
+
 def test_vgg16_smaller_batch_than_max(orc):
     net = synth.vgg16(10, 32)
     params = synth.layer_params(net, 2)
