@@ -3,10 +3,14 @@ motivating experiment of Section 3, Fig. 1; ResNet-18, MobileNetV2 and MnasNet1.
 synthetic, channel-pruned network, plus the single pruned layer and the measured ceilings of
 the device.  One JSON object per line.
 
-    python -m paper_2207_01260_amd.report [--quick] [--only NAME [--batch N] [--dtype f32|f16|bf16]]
+    python -m paper_2207_01260_amd.report [--quick] [--only NAME [--batch N] [--dtype f32|f16|bf16]
+                                           [--variants=v0,v1,...] [--first-layer-form F]]
 
 --only keeps the networks whose name contains NAME (and, with --batch / --dtype, that one run) and
-skips the device ceilings and the single layer: the form a profiler run of one workload uses.
+skips the device ceilings and the single layer: the form a profiler run of one workload uses.  Every line
+carries the tile variant each layer ran (`variants`, -1 for layers without one); --variants pins them (and skips
+the timed selection, which a profiler's per-launch overhead would distort), --first-layer-form pins how a 16-bit
+7x7 first layer runs, so that a profiled run executes the kernels an undisturbed run chose.
 
 For each network and batch: images/s and ms per forward (at batch 1 also with the caches scrubbed
 before every run: back-to-back replays keep the weights in the last-level cache) (HIP graph replay or eager launches,
@@ -60,12 +64,22 @@ def time_forward_cold(handle, x, steps):
     return total / steps
 
 
-def net_report(name, net, cid, batch, dtype, steps, ceilings=None):
+def net_report(name, net, cid, batch, dtype, steps, ceilings=None, variants=None, first_layer_form=None):
     params = synth.layer_params(net, cid)
     dparams = pipeline.upload_params(params)
     layers, kept = pipeline.prune_net(net, dparams, dtype)
     kept_counts = {i: int(k.numel()) for i, k in kept.items()}
-    handle = pipeline.build_net(net, layers, batch, dtype, tune=True)
+    handle = pipeline.build_net(net, layers, batch, dtype, tune=variants is None)
+    if first_layer_form is not None:
+        handle.first_layer_form(first_layer_form)
+    if variants is not None:
+        if len(variants) != len(net.layers):
+            raise SystemExit("--variants needs %d entries for %s" % (len(net.layers), name))
+        for i, v in enumerate(variants):
+            if v >= 0:
+                handle.set_layer_variant(i, v)
+    chosen = [handle.layer_variant(i) if (L.kind == "fc" or (L.kind == "conv" and L.groups == 1)) else -1
+              for i, L in enumerate(net.layers)]
     x = torch.from_numpy(synth.net_input(net, cid, batch)).cuda().to(B.TORCH_DTYPE[dtype])
     ms = min(time_forward(handle, x, steps, g) for g in (False, True))
     ms_cold = time_forward_cold(handle, x, min(steps, 20)) if batch == 1 else None
@@ -110,7 +124,7 @@ def net_report(name, net, cid, batch, dtype, steps, ceilings=None):
             "ms_per_forward": round(ms, 4),
             **({"ms_per_forward_cold_caches": round(ms_cold, 4)} if ms_cold is not None else {}),
             "useful_gflop": round(total / 1e9, 3),
-            "useful_tflops": round(total / (ms * 1e-3) / 1e12, 2), "by_layer_kind": by_kind}
+            "useful_tflops": round(total / (ms * 1e-3) / 1e12, 2), "by_layer_kind": by_kind, "variants": chosen}
 
 
 def single_layer_report(steps):
@@ -139,6 +153,10 @@ def main():
     ap.add_argument("--only", default="", help="only the networks whose name contains this (case-insensitive)")
     ap.add_argument("--batch", type=int, default=0, help="with --only: only this batch size")
     ap.add_argument("--dtype", default="", choices=["", "f32", "f16", "bf16"], help="with --only: only this dtype")
+    ap.add_argument("--variants", default="", help="with --only, --batch and --dtype: pin these tile variants (one per layer, "
+                                                   "-1 = leave) instead of selecting by timing")
+    ap.add_argument("--first-layer-form", type=int, default=None, choices=[0, 1, 2],
+                    help="with --variants: how a 16-bit 7x7 / stride 2 first layer runs (see cprune_net_first_layer_form)")
     args = ap.parse_args()
     steps = 20 if args.quick else 100
     props = torch.cuda.get_device_properties(0)
@@ -160,7 +178,10 @@ def main():
                 continue
             if args.only and ((args.batch and batch != args.batch) or (args.dtype and DT_NAME[dtype] != args.dtype)):
                 continue
-            print(json.dumps(net_report(name, net, cid, batch, dtype, steps, ceilings)), flush=True)
+            pinned = [int(v) for v in args.variants.split(",")] if args.variants else None
+            if pinned is not None and not (args.only and args.batch and args.dtype):
+                raise SystemExit("--variants needs --only, --batch and --dtype")
+            print(json.dumps(net_report(name, net, cid, batch, dtype, steps, ceilings, pinned, args.first_layer_form)), flush=True)
 
 
 def report_device(steps):
