@@ -34,42 +34,45 @@ PEAK = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}   # dense MFMA TFLOP/s, MI3
 # to the kernel sources they were measured on: TRAFFIC_SOURCE_HASH is kernel_source_hash() of that tree,
 # and any change to a file under csrc/ since then reports null instead of a stale figure (as does a
 # selection that runs a kernel on a layer it was not profiled on).
-TRAFFIC_SOURCE_HASH = "b84ceed6853814e8"
+TRAFFIC_SOURCE_HASH = "44ade6751b488d6a"
 TRAFFIC = {
     ("conv_stem2_kernel<float, 2>", 64, "conv2"): 3350342,
     ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, "conv3"): 10522153,
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 1>", 64, "conv3"): 10553895,
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 2>", 64, "conv3"): 10530345,
-    ("conv_patch32_kernel<float, 1, 1, 4, 8, 16, 1, 1>", 64, "conv4"): 10128046,
-    ("conv_patch_kernel<float, 2, 8, 16, 1, 1, 1>", 64, "conv4"): 10122921,
-    ("conv_patch_kernel<float, 2, 8, 16, 1, 1, 2>", 64, "conv4"): 10113719,
-    ("conv_patch_kernel<float, 2, 8, 8, 1, 1, 1>", 64, "conv4"): 10100406,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 1>", 64, "conv3"): 10552867,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 2>", 64, "conv3"): 10528295,
+    ("conv_patch_kernel<float, 2, 8, 8, 1, 1, 1>", 64, "conv3"): 10578463,
+    ("conv_patch32_kernel<float, 1, 1, 4, 8, 16, 1, 1>", 64, "conv4"): 10128045,
+    ("conv_patch_kernel<float, 2, 8, 16, 1, 1, 1>", 64, "conv4"): 10117802,
+    ("conv_patch_kernel<float, 2, 8, 16, 1, 1, 2>", 64, "conv4"): 10109612,
+    ("conv_patch_kernel<float, 2, 8, 8, 1, 1, 1>", 64, "conv4"): 10100399,
     ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, "conv5"): 4493931,
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 1>", 64, "conv5"): 4525672,
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 2>", 64, "conv5"): 4502125,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 1>", 64, "conv5"): 4524648,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 2>", 64, "conv5"): 4500075,
     ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, "conv6"): 10399661,
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 1>", 64, "conv6"): 10431411,
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 2>", 64, "conv6"): 10407857,
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, "conv7"): 12096871,
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 1>", 64, "conv7"): 12127595,
-    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 2>", 64, "conv7"): 12104043,
-    ("conv_wave_kernel<float, 2, 2, 2>", 64, "conv8"): 9398222,
-    ("conv_wave_kernel<float, 2, 2, 4>", 64, "conv8"): 9401296,
-    ("conv_wave_kernel<float, 5, 1, 3>", 64, "conv8"): 16851365,
-    ("conv_wave_kernel<float, 2, 2, 2>", 64, "conv9"): 15053687,
-    ("conv_wave_kernel<float, 2, 2, 4>", 64, "conv9"): 15056752,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 1>", 64, "conv6"): 10430378,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 2>", 64, "conv6"): 10405808,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 1, 1>", 64, "conv7"): 12095845,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 1>", 64, "conv7"): 12126557,
+    ("conv_patch_kernel<float, 1, 8, 8, 1, 2, 2>", 64, "conv7"): 12104034,
+    ("conv_wave_kernel<float, 2, 2, 2>", 64, "conv7"): 13495440,
+    ("conv_wave_kernel<float, 2, 2, 2>", 64, "conv8"): 9394120,
+    ("conv_wave_kernel<float, 2, 2, 4>", 64, "conv8"): 9401286,
+    ("conv_wave_kernel<float, 5, 1, 3>", 64, "conv8"): 16851363,
+    ("conv_wave_kernel<float, 2, 2, 2>", 64, "conv9"): 15049581,
+    ("conv_wave_kernel<float, 2, 2, 4>", 64, "conv9"): 15056750,
     ("conv_wave_kernel<float, 5, 1, 3>", 64, "conv9"): 20934069,
-    ("conv_wave_kernel<float, 2, 2, 2>", 64, "conv10"): 11488649,
-    ("conv_wave_kernel<float, 2, 2, 4>", 64, "conv10"): 11491729,
+    ("conv_wave_kernel<float, 2, 2, 2>", 64, "conv10"): 11484552,
+    ("conv_wave_kernel<float, 2, 2, 4>", 64, "conv10"): 11491715,
     ("conv_wave_kernel<float, 5, 1, 3>", 64, "conv10"): 18686818,
-    ("conv_ksplit_kernel<float, 1, 16>", 64, "conv11"): 7694007,
-    ("conv_ksplit_kernel<float, 1, 4>", 64, "conv11"): 7678646,
-    ("conv_ksplit_kernel<float, 1, 8>", 64, "conv11"): 7689914,
-    ("conv_ksplit_kernel<float, 1, 16>", 64, "conv12"): 6407796,
+    ("conv_ksplit_kernel<float, 1, 16>", 64, "conv11"): 7694001,
+    ("conv_ksplit_kernel<float, 1, 4>", 64, "conv11"): 7678645,
+    ("conv_ksplit_kernel<float, 1, 8>", 64, "conv11"): 7689905,
+    ("conv_ksplit_kernel<float, 1, 16>", 64, "conv12"): 6407791,
     ("conv_ksplit_kernel<float, 1, 4>", 64, "conv12"): 6392431,
-    ("conv_ksplit_kernel<float, 1, 8>", 64, "conv12"): 6403697,
-    ("conv_ksplit_kernel<float, 2, 4>", 64, "conv13"): 7537591,
-    ("conv_ksplit_kernel<float, 2, 8>", 64, "conv13"): 7537588,
+    ("conv_ksplit_kernel<float, 1, 8>", 64, "conv12"): 6403696,
+    ("conv_ksplit_kernel<float, 1, 4>", 64, "conv13"): 7768205,
+    ("conv_ksplit_kernel<float, 2, 4>", 64, "conv13"): 7537585,
+    ("conv_ksplit_kernel<float, 2, 8>", 64, "conv13"): 7537586,
 }
 
 

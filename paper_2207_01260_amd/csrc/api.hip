@@ -226,6 +226,8 @@ extern "C" int cprune_tile_variant_name(int v, int channels_last, cprune_dtype d
   else if (tv.blk32)
     n = snprintf(buf, buf_bytes, "conv_patch32_kernel<%s, %d, %d, %d, %d, %d, %d, %d>", t, tv.mb / 2, tv.nb / 2, tv.wn, tv.th,
                  tv.tw, tv.ni, tv.kq);
+  else if (tv.stride == 2)
+    n = snprintf(buf, buf_bytes, "conv_patch_s2_kernel<%s, %d, %d, %d, %d>", t, tv.mb, tv.th, tv.tw, tv.kq);
   else
     n = snprintf(buf, buf_bytes, "conv_patch_kernel<%s, %d, %d, %d, %d, %d, %d>", t, tv.mb, tv.th, tv.tw, tv.ni, tv.kq, tv.ks);
   return (n < 0 || (size_t)n >= buf_bytes) ? CPRUNE_ERR_INVALID_ARG : CPRUNE_OK;

@@ -46,6 +46,8 @@ struct TileVariant {
   int ks = 1;     // patch kernels on 16x16 blocks: wave groups per tile
   int kwaves = 0; // reduction-split kernel: wavefronts that share one tile's reduction (patch_id indexes its list)
   int nr = 0;     // short-reduction 1x1 kernel: 64-byte rounds of the reduction its filter tile holds
+  int stride = 1; // spatial-patch kernel on 16x16 blocks: the window stride it is built for (patch_id then indexes the
+                  // stride-2 list)
   int tile_m() const { return wm * mb * 16; }
   int tile_p() const { return wn * nb * 16; }
 };

@@ -64,11 +64,11 @@ Plan make_plan(const cprune_conv_desc& d, const TileVariant& tv, const ConvLayou
 
 }  // namespace
 
-int num_variants() { return kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw + kNumWave; }
+int num_variants() { return kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw + kNumWave + kNumPatchS2; }
 
 namespace {
 struct VariantTable {
-  TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw + kNumWave];
+  TileVariant table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw + kNumWave + kNumPatchS2];
   VariantTable() {
 #define CPRUNE_PATCH_ROW(ID, MB_, TH_, TW_, NI_, KQ_, KS_)                                 \
     {                                                                         \
@@ -110,6 +110,15 @@ struct VariantTable {
     }
     CPRUNE_WAVE_LIST(CPRUNE_WAVE_ROW)
 #undef CPRUNE_WAVE_ROW
+    // (new families go behind the existing ones, so that stored variant numbers keep their meaning)
+#define CPRUNE_PATCH_S2_ROW(ID, MB_, TH_, TW_, KQ_)                                        \
+    {                                                                                      \
+      TileVariant& pv = table[kNumTiles * kNumScheds + kNumPatch + kNumPatch32 + kNumKsplit + kNumPw + kNumWave + ID]; \
+      pv.wm = 1; pv.wn = 4; pv.mb = MB_; pv.nb = (TH_ * TW_) / 64; pv.kq = KQ_; pv.ni = 1;  \
+      pv.sched = -1; pv.th = TH_; pv.tw = TW_; pv.patch_id = ID; pv.stride = 2;            \
+    }
+    CPRUNE_PATCH_S2_LIST(CPRUNE_PATCH_S2_ROW)
+#undef CPRUNE_PATCH_S2_ROW
     for (int t = 0; t < kNumTiles; ++t)
       for (int s = 0; s < kNumScheds; ++s) {
         table[t * kNumScheds + s] = kTiles[t];
@@ -161,12 +170,13 @@ bool variant_supports(const cprune_conv_desc& d, int v, const ConvLayout& lay) {
     return groups <= kMaxKsplitGroups;
   }
   if (tv.sched < 0) {
-    if (!(lay.nhwc && d.kh == 3 && d.kw == 3 && d.stride == 1 && d.pad == 1)) return false;
-    if (lay.pool == 2 || (lay.pool && ((d.h | d.w) & 1))) return false;
+    if (!(lay.nhwc && d.kh == 3 && d.kw == 3 && d.stride == tv.stride && d.pad == 1)) return false;
+    if (lay.pool == 2 || (lay.pool && ((d.h | d.w) & 1)) || (lay.pool && tv.stride != 1)) return false;
+    const int ho = conv_out_dim(d.h, 3, d.stride, 1), wo = conv_out_dim(d.w, 3, d.stride, 1);   // = h, w at stride 1
     // multi-image tiles are for maps that fit one tile; single-image tiles for the rest
-    if (tv.ni > 1 ? !(d.h <= tv.th && d.w <= tv.tw) : !(d.h * 2 > tv.th && d.w * 2 > tv.tw)) return false;
+    if (tv.ni > 1 ? !(ho <= tv.th && wo <= tv.tw) : !(ho * 2 > tv.th && wo * 2 > tv.tw)) return false;
     // the kernels decode their tile with multiply-high divisions, exact while groups x divisor < 2^32
-    const long tiles_s = (long)((d.n + tv.ni - 1) / tv.ni) * ((d.h + tv.th - 1) / tv.th) * ((d.w + tv.tw - 1) / tv.tw);
+    const long tiles_s = (long)((d.n + tv.ni - 1) / tv.ni) * ((ho + tv.th - 1) / tv.th) * ((wo + tv.tw - 1) / tv.tw);
     const long groups = tiles_s * ((d.c_out + tv.tile_m() - 1) / tv.tile_m());
     return groups * tiles_s < (1L << 32);
   }
@@ -297,8 +307,9 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     pa.N = d.n; pa.H = d.h; pa.W = d.w; pa.O = d.c_out; pa.Cp = lay.cp_in; pa.Cop = lay.cp_out;
     pa.tiles_n = (d.n + tv.ni - 1) / tv.ni;
     pa.pool = lay.pool;
-    pa.tiles_y = (d.h + tv.th - 1) / tv.th;
-    pa.tiles_x = (d.w + tv.tw - 1) / tv.tw;
+    pa.Ho = conv_out_dim(d.h, 3, d.stride, 1); pa.Wo = conv_out_dim(d.w, 3, d.stride, 1);   // = h, w at stride 1
+    pa.tiles_y = (pa.Ho + tv.th - 1) / tv.th;
+    pa.tiles_x = (pa.Wo + tv.tw - 1) / tv.tw;
     pa.tiles_m = (d.c_out + tv.tile_m() - 1) / tv.tile_m();
     pa.x_bytes = (unsigned)((size_t)d.n * lay.cp_in * d.h * d.w * es);
     pa.w_bytes = (unsigned)((size_t)d.c_out * 9 * lay.cp_in * es);
@@ -309,7 +320,11 @@ int launch_conv_dense(const cprune_conv_desc& d, const void* x, const void* w, c
     pa.magic_x = magic_for((unsigned)pa.tiles_x); pa.magic_y = magic_for((unsigned)pa.tiles_y);
     pa.magic_xy = 0;
     dim3 pgrid((unsigned)(pa.tiles_n * pa.tiles_y * pa.tiles_x * pa.tiles_m));
-    if (tv.blk32) {
+    if (tv.stride == 2) {
+      if (d.dtype == CPRUNE_F32) launch_conv_patch_s2_f32(tv.patch_id, pgrid, s, pa);
+      else if (d.dtype == CPRUNE_F16) launch_conv_patch_s2_f16(tv.patch_id, pgrid, s, pa);
+      else launch_conv_patch_s2_bf16(tv.patch_id, pgrid, s, pa);
+    } else if (tv.blk32) {
       if (d.dtype == CPRUNE_F32) launch_conv_patch32_f32(tv.patch_id, pgrid, s, pa);
       else if (d.dtype == CPRUNE_F16) launch_conv_patch32_f16(tv.patch_id, pgrid, s, pa);
       else launch_conv_patch32_bf16(tv.patch_id, pgrid, s, pa);

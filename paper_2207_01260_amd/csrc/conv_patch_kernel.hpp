@@ -41,6 +41,7 @@ struct PatchArgs {
   int m_major;  // tile order: 0 = filter tiles fastest (each chip quarter's L2 sees few input patches, all
                 // weights), 1 = pixel tiles fastest (few filters, all patches): whichever operand is larger
                 // is the one split between the L2s
+  int Ho = 0, Wo = 0;   // stride-2 form only: the output map (H, W are the input map); tiles count blocks of it
 };
 
 // One 64-byte round of MFMAs on NS accumulator sets.  A tile with fewer than four
@@ -150,8 +151,10 @@ __device__ __forceinline__ void load_tile_bias(const PatchArgs& a, int o0, int g
   for (int i = 0; i < MB; ++i) bias4[i] = load_bias4(a.bias, a.O, o0 + i * 16 + 4 * g4);
 }
 
-template <typename T, int MB, int TH, int TW, int NI, int KQ, int KS>
-__global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
+ // S: stride of the window (1, or 2 for the layers that halve the map: the patch is then (TH - 1) * 2 + 3 rows
+// by (TW - 1) * 2 + 3 columns and a lane's tap is the same compile-time offset from twice its pixel position)
+template <typename T, int MB, int TH, int TW, int NI, int KQ, int KS, int S>
+__device__ __forceinline__ void patch_body(const PatchArgs& a) {
   constexpr int NT = 256 * KS;            // KS groups of 4 wavefronts share a tile: each takes 1/KS of the rounds
   constexpr int ES = (int)sizeof(T);
   constexpr int EPI = 16 / ES;            // elements per quad
@@ -160,7 +163,7 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
   constexpr int PT = TH * TW * NI;        // output pixels per tile (NI images x TH x TW)
   constexpr int NB = PT / 64;             // 16-pixel blocks per wave
   constexpr int MT = MB * 16;
-  constexpr int PW = TW + 2, PH = TH + 2;
+  constexpr int PW = (TW - 1) * S + 3, PH = (TH - 1) * S + 3;
   constexpr int NPATCH = NI * PH * PW;
   constexpr int BROW = 64 * KQ + 16;      // patch pixel: the chunk's channels + 16 pad
   constexpr int AROW = 9 * 64 * KQ + 16;  // filter row: 9 taps x chunk + 16 pad
@@ -168,6 +171,7 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
   constexpr int NIA = (MT * 9 * NQ + NT - 1) / NT;
   constexpr int NS = (MB * (PT / 64) >= 4) ? 1 : 4 / (MB * (PT / 64));  // accumulator sets
   static_assert(PT % 64 == 0 && (TW == 2 || TW == 4 || TW == 8 || TW == 16) && (16 % TW == 0), "tile shape");
+  static_assert(S == 1 || (S == 2 && NI == 1 && KS == 1), "stride");
 
   __shared__ __attribute__((aligned(16))) unsigned char sA[MT * AROW];
   __shared__ __attribute__((aligned(16))) unsigned char sB[NPATCH * BROW];
@@ -214,7 +218,7 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
     const bool item = pp < NPATCH;
     const int img = pp / (PH * PW), pr = pp - img * (PH * PW);
     const int py = pr / PW, px = pr - py * PW;
-    const int iy = ty0 + py - 1, ix = tx0 + px - 1, n = n0 + img;
+    const int iy = ty0 * S + py - 1, ix = tx0 * S + px - 1, n = n0 + img;
     const bool inside = item && n < a.N && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
     b_off[j] = inside ? (unsigned)(((n * a.H + iy) * a.W + ix) * a.Cp + q * EPI) * ES : kOutOfRange;
     b_lds[j] = item ? pp * BROW + q * 16 : NPATCH * BROW - 16;   // no item: the last row's pad, which nobody reads
@@ -263,7 +267,7 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
     const int id = wave * (NB * 16) + j * 16 + r;
     const int img = id / (TH * TW), ir = id % (TH * TW);
     const int ty = ir / TW, tx = ir % TW;
-    b_frag[j] = ((img * PH + ty) * PW + tx) * BROW + g4 * 16;
+    b_frag[j] = ((img * PH + ty * S) * PW + tx * S) * BROW + g4 * 16;
   }
   const int a_frag = r * AROW + g4 * 16;
 
@@ -377,7 +381,26 @@ __global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
   }
 
   // ---- epilogue ----
-  patch_epilogue<T, MB, TH, TW, NB>(a, acc, wave, r, g4, n0, ty0, tx0, o0, bias4);
+  if constexpr (S == 1) {
+    patch_epilogue<T, MB, TH, TW, NB>(a, acc, wave, r, g4, n0, ty0, tx0, o0, bias4);
+  } else {
+    PatchArgs out = a;          // the epilogue indexes the map it writes
+    out.H = a.Ho; out.W = a.Wo;
+    patch_epilogue<T, MB, TH, TW, NB>(out, acc, wave, r, g4, n0, ty0, tx0, o0, bias4);
+  }
+}
+
+template <typename T, int MB, int TH, int TW, int NI, int KQ, int KS>
+__global__ __launch_bounds__(256 * KS) void conv_patch_kernel(PatchArgs a) {
+  patch_body<T, MB, TH, TW, NI, KQ, KS, 1>(a);
+}
+
+// 3x3 / stride 2 / pad 1 (the layers that halve the map between the stages of a residual network): the same
+// kernel on a patch of twice the extent.  An input element is still staged once per tile instead of once per tap
+// that touches it, as the im2col tiles of the general kernel do.
+template <typename T, int MB, int TH, int TW, int KQ>
+__global__ __launch_bounds__(256) void conv_patch_s2_kernel(PatchArgs a) {
+  patch_body<T, MB, TH, TW, 1, KQ, 1, 2>(a);
 }
 
 // Patch variants: id, mb, th, tw, ni (images per tile, for maps smaller than the tile; two images of a 7x7 map
@@ -423,7 +446,32 @@ inline void launch_patch(int id, dim3 grid, hipStream_t s, const PatchArgs& a) {
 #undef CPRUNE_PATCH_CASE
 }
 
+// Stride-2 variants: id, mb, th, tw, kq
+#define CPRUNE_PATCH_S2_LIST(X) \
+  X(0, 1, 8, 8, 1)   \
+  X(1, 2, 8, 8, 1)   \
+  X(2, 4, 8, 8, 1)   \
+  X(3, 2, 8, 16, 1)  \
+  X(4, 4, 8, 16, 1)  \
+  X(5, 2, 8, 8, 2)   \
+  X(6, 4, 8, 8, 2)
+
+constexpr int kNumPatchS2 = 7;
+
+template <typename T>
+inline void launch_patch_s2(int id, dim3 grid, hipStream_t s, const PatchArgs& a) {
+#define CPRUNE_PATCH_S2_CASE(ID, MB_, TH_, TW_, KQ_)                                              \
+  case ID:                                                                                        \
+    hipLaunchKernelGGL((conv_patch_s2_kernel<T, MB_, TH_, TW_, KQ_>), grid, dim3(256), 0, s, a);  \
+    break;
+  switch (id) { CPRUNE_PATCH_S2_LIST(CPRUNE_PATCH_S2_CASE) }
+#undef CPRUNE_PATCH_S2_CASE
+}
+
 void launch_conv_patch_f32(int id, dim3 grid, hipStream_t s, const PatchArgs& a);
+void launch_conv_patch_s2_f32(int id, dim3 grid, hipStream_t s, const PatchArgs& a);
+void launch_conv_patch_s2_f16(int id, dim3 grid, hipStream_t s, const PatchArgs& a);
+void launch_conv_patch_s2_bf16(int id, dim3 grid, hipStream_t s, const PatchArgs& a);
 void launch_conv_patch_f16(int id, dim3 grid, hipStream_t s, const PatchArgs& a);
 void launch_conv_patch_bf16(int id, dim3 grid, hipStream_t s, const PatchArgs& a);
 

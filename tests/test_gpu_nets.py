@@ -317,6 +317,8 @@ def _two_layer_net(c0, c1, c2, hw, k, stride, pad, act, residual):
     (6, 64, 100, 14, 1, 1, 0, synth.ACT_RELU6, False, 2, B.F32),     # 1x1
     (6, 40, 70, 15, 1, 2, 0, synth.ACT_NONE, False, 2, B.F32),       # strided 1x1 (downsample)
     (7, 19, 33, 17, 3, 2, 1, synth.ACT_RELU, False, 2, B.F32),       # strided 3x3
+    (8, 40, 70, 14, 3, 2, 1, synth.ACT_RELU, False, 3, B.BF16),      # strided 3x3, 16-bit, even map, five filter blocks
+    (6, 90, 37, 28, 3, 2, 1, synth.ACT_NONE, False, 1, B.F16),       # strided 3x3, three channel chunks, 28 -> 14
     (5, 9, 20, 21, 7, 2, 3, synth.ACT_RELU, False, 1, B.F32),        # 7x7 / 2
     (6, 12, 18, 11, 5, 1, 2, synth.ACT_RELU, False, 2, B.F32),       # 5x5
     (8, 44, 44, 8, 3, 1, 1, synth.ACT_RELU, True, 5, B.BF16),        # 16-bit, shortcut, 8x8 map
@@ -336,7 +338,7 @@ def test_channels_last_layer_every_variant(orc, cfg):
     layers, _ = pipeline.prune_net(net, pipeline.upload_params(params), dtype)
     handle = pipeline.build_net(net, layers, batch, dtype, tune=False)
     xd = torch.from_numpy(x).cuda().to(B.TORCH_DTYPE[dtype])
-    ran = 0
+    ran, names = 0, set()
     for v in range(B.cprune_num_tile_variants()):
         try:
             handle.set_layer_variant(1, v)
@@ -344,12 +346,15 @@ def test_channels_last_layer_every_variant(orc, cfg):
             assert e.status == B.ERR_UNSUPPORTED
             continue
         ran += 1
+        names.add(B.cprune_tile_variant_name(v, True, dtype).split("<")[0])
         out = handle.forward(xd)
         torch.cuda.synchronize()
         err = nmax(out.float().cpu().numpy(), ref)
         assert err < TOL[dtype], (v, B.cprune_tile_variant_name(v, True, dtype), err)
     handle.close()
     assert ran >= 100 or (k == 3 and stride == 1 and ran >= 110)
+    if k == 3 and stride == 2:
+        assert "conv_patch_s2_kernel" in names, names
 
 
 @pytest.mark.parametrize("cfg", [
